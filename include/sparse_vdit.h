@@ -1,0 +1,172 @@
+/*
+ * sparse_vdit.h - C ABI of the MI355X (gfx950) sparse 3D-attention forward of
+ * Sparse-vDiT (arxiv 2506.03065).
+ *
+ * What the library computes.  For every batch entry b and head h of one
+ * attention layer, with Q, K, V of shape [B, H, L, D]:
+ *
+ *     O[b,h,i,:] = sum_{j in kept_h(i)} softmax_j( Q[b,h,i,:].K[b,h,j,:] / sqrt(D) ) V[b,h,j,:]
+ *
+ * (Section 3, Eq. 1, restricted to the kept part of the attention map as in
+ * Section 3 "Sparse Attention" and Section 4.2 "Sparse Computation
+ * Pre-definition").  kept_h(i) depends on the head's mode M_0..M_4
+ * (Section 4.2) and its parameters (Section 4.1.2):
+ *
+ *     0 dense          every key j
+ *     1 skip           no key; the head's output is all zeros (Section 4.2)
+ *     2 diagonal       |j - i| <= half_width
+ *     3 multi-diagonal exists o in offsets: |j - i - o| <= half_width
+ *     4 vertical       j in cols
+ *
+ * The softmax is renormalised over the kept keys.  Heads of one layer that
+ * share a mode are fused into one kernel launch (Section 4.2, last paragraph).
+ * The per-head mode table is an input: the offline search that produces it
+ * (Section 4.2, Eq. 2-3, Algorithm 1) is not part of this library.
+ *
+ * Conventions for every entry point
+ *  - Tensors q, k, v, out are DEVICE pointers to bf16 (bfloat16) data described
+ *    by one svd_tensor_desc: element strides for the B, H and L axes, the D axis
+ *    is contiguous; every row start must be 16-byte aligned (base pointer and
+ *    strides multiples of 8 elements).  q, k, v are read only; out is fully
+ *    overwritten for every head (zeros for skipped heads).
+ *  - strategy_table and pattern_params are HOST pointers; they are read during
+ *    the call and not kept.  The same table applies to every batch entry.
+ *  - The library never allocates or frees device memory and never synchronises
+ *    the device.  Plans place their index lists in a caller-provided DEVICE
+ *    workspace that must stay alive and untouched while the plan is in use.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    Kernels are enqueued on it and the call returns without waiting.
+ *  - Every function returns an svd_status.  Arguments are validated on the host
+ *    before anything is enqueued; on error nothing is launched and out is left
+ *    untouched.  No exception or abort crosses this boundary.
+ */
+#ifndef SPARSE_VDIT_H
+#define SPARSE_VDIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t svd_status;
+enum {
+  SVD_OK = 0,
+  SVD_ERR_NULL = 1,          /* a required pointer is NULL */
+  SVD_ERR_SHAPE = 2,         /* B, H, L < 1, D not 64 or 128, bad group/list index */
+  SVD_ERR_DTYPE = 3,         /* reserved: only bf16 exists */
+  SVD_ERR_ALIGN = 4,         /* pointer or stride breaks the 16-byte row alignment */
+  SVD_ERR_MODE = 5,          /* mode id outside 0..4 */
+  SVD_ERR_PARAMS = 6,        /* negative width, no/duplicate offsets, column out of range or duplicate */
+  SVD_ERR_EMPTY_PATTERN = 7, /* some query row would keep no key */
+  SVD_ERR_WORKSPACE = 8,     /* workspace missing or too small */
+  SVD_ERR_UNSUPPORTED = 9,   /* block shape the kernels do not implement */
+  SVD_ERR_HIP = 10           /* a HIP call (copy, launch) failed */
+};
+
+/* Mode ids = M_0..M_4 of Section 4.2, sparse modes in the order of Section 4.1.2. */
+enum { SVD_DENSE = 0, SVD_SKIP = 1, SVD_DIAG = 2, SVD_MULTIDIAG = 3, SVD_VSTRIPE = 4 };
+
+typedef struct {
+  int32_t B, H, L, D;                     /* D in {64, 128} */
+  int64_t stride_b, stride_h, stride_l;   /* in elements; the D axis has stride 1 */
+} svd_tensor_desc;
+
+/* Parameters of one head (pattern_params is an array of H of these).  Only the
+ * fields of the head's mode are read. */
+typedef struct {
+  int32_t half_width;        /* w in tokens, modes 2 and 3; the band is inclusive: 2w+1 diagonals */
+  int32_t n_offsets;         /* mode 3: number of band centres */
+  const int32_t* offsets;    /* mode 3: band centres o (key index minus query index), any order, host */
+  int32_t n_cols;            /* mode 4: number of key columns */
+  const int32_t* cols;       /* mode 4: key columns in [0, L), any order, no duplicates, host */
+} svd_head_params;
+
+/* Block shape of the key-block lists: block_q query rows by block_k keys.
+ * 0 selects the shape the kernels run for the given D.  A plan compiled with
+ * another shape can be inspected but not launched. */
+typedef struct { int32_t block_q, block_k; } svd_plan_options;
+
+typedef struct svd_plan svd_plan;
+
+/* Block shape the kernels use for head dimension D (the default of the plan
+ * options).  D must be 64 or 128. */
+svd_status svd_default_blocks(int32_t D, int32_t* block_q, int32_t* block_k);
+
+/* Bytes of device workspace a plan for this layer needs.  Host only. */
+svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* strategy_table,
+                                    const svd_head_params* pattern_params,
+                                    const svd_plan_options* options, size_t* bytes);
+
+/* Pattern compiler (Section 4.2: head fusion + block-level sparsity).  Groups the
+ * heads by mode, builds for every distinct band pattern the CSR list of key
+ * blocks per query block and for every distinct column set the padded sorted
+ * column list, and copies them to device_workspace on hip_stream (the copy has
+ * completed when the call returns).  With device_workspace == NULL the plan is
+ * host-only: it can be inspected but svd_attn_forward_planned refuses it.
+ * options may be NULL.  The plan is released with svd_plan_destroy. */
+svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
+                           const int32_t* strategy_table, const svd_head_params* pattern_params,
+                           const svd_plan_options* options, void* device_workspace,
+                           size_t workspace_bytes, void* hip_stream);
+svd_status svd_plan_destroy(svd_plan* plan);
+
+/* Inspection of a compiled plan (host copies owned by the plan, valid until
+ * svd_plan_destroy).  Groups are ordered by ascending mode id. */
+svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups);
+/* heads: ascending head ids of the group; list_id[t]: which list of the group
+ * head heads[t] uses (heads with the same kept region share a list; ids are
+ * numbered by first appearance); n_lists is 0 for dense and skip groups. */
+svd_status svd_plan_group_info(const svd_plan* plan, int32_t group, int32_t* mode, int32_t* n_heads,
+                               const int32_t** heads, const int32_t** list_id, int32_t* n_lists);
+/* A list of a band group (modes 2, 3).  row_ptr[n_q_blocks+1] is the CSR
+ * pointer; for entry e: kv_block_idx[e] (ascending inside a query block),
+ * flags[e] = 1 if the whole block_q x block_k tile is kept for every in-range
+ * query row and lies inside [0, L) (no masking needed), else 0.  runs[2*r],
+ * runs[2*r+1] = inclusive bounds of the r-th maximal run of kept diagonals
+ * (key index minus query index) inside [-(L-1), L-1]; run_first[e] and
+ * run_count[e] name the consecutive runs that have a kept element in tile e. */
+svd_status svd_plan_band_list(const svd_plan* plan, int32_t group, int32_t list,
+                              int32_t* n_q_blocks, const int32_t** row_ptr,
+                              const int32_t** kv_block_idx, const int32_t** flags,
+                              const int32_t** run_first, const int32_t** run_count,
+                              int32_t* n_runs, const int32_t** runs);
+/* A list of a vertical-stripe group (mode 4): the sorted unique columns padded
+ * with -1 to padded_len, a multiple of block_k. */
+svd_status svd_plan_column_list(const svd_plan* plan, int32_t group, int32_t list,
+                                int32_t* n_cols, int32_t* padded_len, const int32_t** cols);
+/* Work the plan launches per forward pass, summed over batch and heads:
+ * computed_tiles counts block_q x block_k tiles (dense heads: all of them,
+ * vertical heads: column tiles), computed_flops = 4 * D * (tile area inside
+ * [0,L) x [0,L) or the column list) and kept_pairs the element-level count. */
+svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* computed_flops,
+                         double* kept_pairs);
+
+/* Forward pass of one layer with a compiled plan (Section 4.2: one fused launch
+ * per mode present in the table, heaviest group first, plus a zero fill for
+ * skipped heads).  The tensors must match the plan's descriptor. */
+svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
+                                    void* out, void* hip_stream);
+
+/* One-shot form: compiles the table (or reuses the plan compiled by the previous
+ * call with identical arguments and workspace) and launches.  workspace_bytes
+ * must be at least svd_plan_workspace_bytes(...). */
+svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
+                                    const int32_t* strategy_table,
+                                    const svd_head_params* pattern_params, void* out,
+                                    const svd_tensor_desc* desc, void* device_workspace,
+                                    size_t workspace_bytes, void* hip_stream);
+
+/* Eq. 1 for all H heads with the same kernel family: the dense baseline the
+ * sparse layer's speed-up is measured against.  Needs no workspace. */
+svd_status svd_dense_attn_forward(const void* q, const void* k, const void* v, void* out,
+                                  const svd_tensor_desc* desc, void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* svd_status_string(svd_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_VDIT_H */

@@ -1,0 +1,264 @@
+"""ctypes binding of the C-ABI library (argument marshalling only).
+
+Every function here has the name of the C entry point it calls (see
+include/sparse_vdit.h); all arithmetic of the attention path runs in the HIP
+kernels and the host pattern compiler inside the shared library.  PyTorch
+supplies device memory and streams.  There is no fallback: if the library is
+missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsparse_vdit.so")
+
+SVD_OK = 0
+STATUS_NAMES = {0: "SVD_OK", 1: "SVD_ERR_NULL", 2: "SVD_ERR_SHAPE", 3: "SVD_ERR_DTYPE", 4: "SVD_ERR_ALIGN",
+                5: "SVD_ERR_MODE", 6: "SVD_ERR_PARAMS", 7: "SVD_ERR_EMPTY_PATTERN", 8: "SVD_ERR_WORKSPACE",
+                9: "SVD_ERR_UNSUPPORTED", 10: "SVD_ERR_HIP"}
+SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
+
+EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
+           "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_band_list", "svd_plan_column_list",
+           "svd_plan_work", "svd_attn_forward_planned", "sparse_vdit_attn_forward",
+           "svd_dense_attn_forward", "svd_status_string"]
+
+
+class SvdError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {STATUS_NAMES.get(self.status, self.status)} ({status_string(self.status)})")
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("L", C.c_int32), ("D", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_l", C.c_int64)]
+
+
+class HeadParams(C.Structure):
+    _fields_ = [("half_width", C.c_int32), ("n_offsets", C.c_int32), ("offsets", C.POINTER(C.c_int32)),
+                ("n_cols", C.c_int32), ("cols", C.POINTER(C.c_int32))]
+
+
+class PlanOptions(C.Structure):
+    _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_03065_amd.build` "
+                               "(there is no fallback path)")
+        _lib = C.CDLL(LIB_PATH)
+        i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+        i32pp = C.POINTER(i32p)
+        descp, hpp, optp = C.POINTER(TensorDesc), C.POINTER(HeadParams), C.POINTER(PlanOptions)
+        sig = {
+            "svd_default_blocks": [C.c_int32, i32p, i32p],
+            "svd_plan_workspace_bytes": [descp, i32p, hpp, optp, C.POINTER(C.c_size_t)],
+            "svd_plan_create": [C.POINTER(vp), descp, i32p, hpp, optp, vp, C.c_size_t, vp],
+            "svd_plan_destroy": [vp],
+            "svd_plan_num_groups": [vp, i32p],
+            "svd_plan_group_info": [vp, C.c_int32, i32p, i32p, i32pp, i32pp, i32p],
+            "svd_plan_band_list": [vp, C.c_int32, C.c_int32, i32p, i32pp, i32pp, i32pp, i32pp, i32pp, i32p, i32pp],
+            "svd_plan_column_list": [vp, C.c_int32, C.c_int32, i32p, i32p, i32pp],
+            "svd_plan_work": [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
+            "svd_attn_forward_planned": [vp, vp, vp, vp, vp, vp],
+            "sparse_vdit_attn_forward": [vp, vp, vp, i32p, hpp, vp, descp, vp, C.c_size_t, vp],
+            "svd_dense_attn_forward": [vp, vp, vp, vp, descp, vp],
+        }
+        for name, args in sig.items():
+            fn = getattr(_lib, name)
+            fn.argtypes = args
+            fn.restype = C.c_int32
+        _lib.svd_status_string.argtypes = [C.c_int32]
+        _lib.svd_status_string.restype = C.c_char_p
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().svd_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != SVD_OK:
+        raise SvdError(status, where)
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def tensor_desc(B, H, L, D, stride_b=None, stride_h=None, stride_l=None) -> TensorDesc:
+    stride_l = D if stride_l is None else stride_l
+    stride_h = L * stride_l if stride_h is None else stride_h
+    stride_b = H * stride_h if stride_b is None else stride_b
+    return TensorDesc(B, H, L, D, stride_b, stride_h, stride_l)
+
+
+def desc_of(t) -> TensorDesc:
+    """Descriptor of a [B, H, L, D] torch tensor whose last axis is contiguous."""
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("expected a [B, H, L, D] tensor with a contiguous last axis")
+    B, H, L, D = t.shape
+    return TensorDesc(B, H, L, D, t.stride(0), t.stride(1), t.stride(2))
+
+
+class _Marshalled:
+    """Host arrays behind an svd_head_params[H]; keeps them alive."""
+
+    def __init__(self, strategy_table, pattern_params):
+        self.table = _i32(strategy_table)
+        H = self.table.size
+        if len(pattern_params) != H:
+            raise ValueError("pattern_params must have one entry per head")
+        self.keep = []
+        self.params = (HeadParams * H)()
+        for h, p in enumerate(pattern_params):
+            p = p or {}
+            offs = _i32(p.get("offsets", ()))
+            cols = _i32(p.get("cols", ()))
+            self.keep += [offs, cols]
+            self.params[h].half_width = int(p.get("half_width", 0))
+            self.params[h].n_offsets = offs.size
+            self.params[h].offsets = _ptr(offs) if offs.size else None
+            self.params[h].n_cols = cols.size
+            self.params[h].cols = _ptr(cols) if cols.size else None
+
+
+def svd_default_blocks(D: int):
+    bq, bk = C.c_int32(), C.c_int32()
+    _check(lib().svd_default_blocks(D, C.byref(bq), C.byref(bk)), "svd_default_blocks")
+    return bq.value, bk.value
+
+
+def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0) -> int:
+    m = _Marshalled(strategy_table, pattern_params)
+    opt = PlanOptions(block_q, block_k)
+    n = C.c_size_t()
+    _check(lib().svd_plan_workspace_bytes(C.byref(desc), _ptr(m.table), m.params, C.byref(opt), C.byref(n)),
+           "svd_plan_workspace_bytes")
+    return n.value
+
+
+def _copy(ptr, n):
+    return np.ctypeslib.as_array(ptr, shape=(n,)).copy() if n else np.zeros(0, dtype=np.int32)
+
+
+class Plan:
+    """Owner of an svd_plan* (and of the torch workspace tensor, if given)."""
+
+    def __init__(self, handle, desc, workspace):
+        self.handle, self.desc, self.workspace = handle, desc, workspace
+
+    def close(self):
+        if self.handle:
+            lib().svd_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- inspection ----
+    def groups(self):
+        L_ = lib()
+        n = C.c_int32()
+        _check(L_.svd_plan_num_groups(self.handle, C.byref(n)), "svd_plan_num_groups")
+        out = []
+        for g in range(n.value):
+            mode, nh, nl = C.c_int32(), C.c_int32(), C.c_int32()
+            heads, lid = C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)()
+            _check(L_.svd_plan_group_info(self.handle, g, C.byref(mode), C.byref(nh), C.byref(heads),
+                                          C.byref(lid), C.byref(nl)), "svd_plan_group_info")
+            out.append({"mode": mode.value, "heads": _copy(heads, nh.value).tolist(),
+                        "list_id": _copy(lid, nh.value).tolist(), "n_lists": nl.value})
+        return out
+
+    def band_list(self, group, lst):
+        nqb, nruns = C.c_int32(), C.c_int32()
+        ptrs = [C.POINTER(C.c_int32)() for _ in range(6)]
+        _check(lib().svd_plan_band_list(self.handle, group, lst, C.byref(nqb), C.byref(ptrs[0]), C.byref(ptrs[1]),
+                                        C.byref(ptrs[2]), C.byref(ptrs[3]), C.byref(ptrs[4]), C.byref(nruns),
+                                        C.byref(ptrs[5])), "svd_plan_band_list")
+        row_ptr = _copy(ptrs[0], nqb.value + 1)
+        nnz = int(row_ptr[-1])
+        return {"row_ptr": row_ptr, "kv_block_idx": _copy(ptrs[1], nnz), "flags": _copy(ptrs[2], nnz),
+                "run_first": _copy(ptrs[3], nnz), "run_count": _copy(ptrs[4], nnz),
+                "runs": _copy(ptrs[5], 2 * nruns.value).reshape(-1, 2)}
+
+    def column_list(self, group, lst):
+        n, padded = C.c_int32(), C.c_int32()
+        cols = C.POINTER(C.c_int32)()
+        _check(lib().svd_plan_column_list(self.handle, group, lst, C.byref(n), C.byref(padded), C.byref(cols)),
+               "svd_plan_column_list")
+        return {"n_cols": n.value, "cols": _copy(cols, padded.value)}
+
+    def work(self):
+        tiles, flops, pairs = C.c_int64(), C.c_double(), C.c_double()
+        _check(lib().svd_plan_work(self.handle, C.byref(tiles), C.byref(flops), C.byref(pairs)), "svd_plan_work")
+        return {"computed_tiles": tiles.value, "computed_flops": flops.value, "kept_pairs": pairs.value}
+
+
+def svd_plan_create(desc, strategy_table, pattern_params, block_q=0, block_k=0, workspace=None, stream=None) -> Plan:
+    """workspace: a torch uint8/int32 CUDA tensor of at least svd_plan_workspace_bytes
+    bytes, or None for a host-only plan (inspection, no launches)."""
+    m = _Marshalled(strategy_table, pattern_params)
+    opt = PlanOptions(block_q, block_k)
+    handle = C.c_void_p()
+    ws_ptr = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().svd_plan_create(C.byref(handle), C.byref(desc), _ptr(m.table), m.params, C.byref(opt),
+                                 ws_ptr, ws_bytes, _stream_ptr(stream)), "svd_plan_create")
+    return Plan(handle, desc, workspace)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        if torch.cuda.is_available():
+            return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        return None
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev(t):
+    return C.c_void_p(t.data_ptr())
+
+
+def svd_attn_forward_planned(plan: Plan, q, k, v, out, stream=None):
+    _check(lib().svd_attn_forward_planned(plan.handle, _dev(q), _dev(k), _dev(v), _dev(out), _stream_ptr(stream)),
+           "svd_attn_forward_planned")
+    return out
+
+
+def sparse_vdit_attn_forward(q, k, v, strategy_table, pattern_params, out, workspace, stream=None):
+    desc = desc_of(q)
+    m = _Marshalled(strategy_table, pattern_params)
+    _check(lib().sparse_vdit_attn_forward(_dev(q), _dev(k), _dev(v), _ptr(m.table), m.params, _dev(out),
+                                          C.byref(desc), _dev(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "sparse_vdit_attn_forward")
+    return out
+
+
+def svd_dense_attn_forward(q, k, v, out, stream=None):
+    desc = desc_of(q)
+    _check(lib().svd_dense_attn_forward(_dev(q), _dev(k), _dev(v), _dev(out), C.byref(desc), _stream_ptr(stream)),
+           "svd_dense_attn_forward")
+    return out

@@ -1,0 +1,364 @@
+// C ABI of the library (see include/sparse_vdit.h for the contract).
+//
+// Host logic only: argument validation, plan life cycle, the copy of the
+// compiled lists into the caller's workspace, and the per-layer launch sequence
+// of Section 4.2 (one fused launch per mode present in the layer).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "attn_kernels.h"
+#include "plan.h"
+#include "sparse_vdit.h"
+
+struct svd_plan {
+  svd::Plan p;
+};
+
+namespace {
+
+using svd::Plan;
+
+bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
+
+svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* opt, int32_t* bq,
+                          int32_t* bk, bool* native) {
+  int kq = 0, kk = 0;
+  svd::kernel_blocks(desc.D, &kq, &kk);
+  *bq = (opt && opt->block_q) ? opt->block_q : kq;
+  *bk = (opt && opt->block_k) ? opt->block_k : kk;
+  if (*bq < 1 || *bk < 1) return SVD_ERR_UNSUPPORTED;
+  *native = (*bq == kq && *bk == kk);
+  return SVD_OK;
+}
+
+svd::AttnLaunch base_launch(const svd_tensor_desc& d, const void* q, const void* k, const void* v,
+                            void* out) {
+  svd::AttnLaunch a{};
+  a.q = static_cast<const __bf16*>(q);
+  a.k = static_cast<const __bf16*>(k);
+  a.v = static_cast<const __bf16*>(v);
+  a.out = static_cast<__bf16*>(out);
+  a.B = d.B;
+  a.H = d.H;
+  a.L = d.L;
+  a.D = d.D;
+  a.stride_b = d.stride_b;
+  a.stride_h = d.stride_h;
+  a.stride_l = d.stride_l;
+  a.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(d.D)));
+  return a;
+}
+
+svd_status check_tensors(const void* q, const void* k, const void* v, const void* out) {
+  if (!q || !k || !v || !out) return SVD_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return SVD_ERR_ALIGN;
+  return SVD_OK;
+}
+
+// One-shot cache: the plan of the previous sparse_vdit_attn_forward call.
+struct OneShot {
+  std::mutex mu;
+  svd_plan* plan = nullptr;
+  svd_tensor_desc desc{};
+  std::vector<int32_t> table;
+  std::vector<int32_t> flat;   // flattened parameters
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
+};
+OneShot g_oneshot;
+
+std::vector<int32_t> flatten(const svd_tensor_desc& d, const int32_t* table, const svd_head_params* pp) {
+  std::vector<int32_t> f;
+  for (int h = 0; h < d.H; ++h) {
+    const int mode = table[h];
+    f.push_back(mode);
+    if (mode == SVD_DIAG || mode == SVD_MULTIDIAG) f.push_back(pp[h].half_width);
+    if (mode == SVD_MULTIDIAG && pp[h].offsets && pp[h].n_offsets > 0) {
+      f.push_back(pp[h].n_offsets);
+      f.insert(f.end(), pp[h].offsets, pp[h].offsets + pp[h].n_offsets);
+    }
+    if (mode == SVD_VSTRIPE && pp[h].cols && pp[h].n_cols > 0) {
+      f.push_back(pp[h].n_cols);
+      f.insert(f.end(), pp[h].cols, pp[h].cols + pp[h].n_cols);
+    }
+  }
+  return f;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* svd_status_string(svd_status s) {
+  switch (s) {
+    case SVD_OK: return "ok";
+    case SVD_ERR_NULL: return "null pointer";
+    case SVD_ERR_SHAPE: return "bad shape";
+    case SVD_ERR_DTYPE: return "bad dtype";
+    case SVD_ERR_ALIGN: return "misaligned tensor";
+    case SVD_ERR_MODE: return "mode id outside 0..4";
+    case SVD_ERR_PARAMS: return "bad pattern parameters";
+    case SVD_ERR_EMPTY_PATTERN: return "a query row keeps no key";
+    case SVD_ERR_WORKSPACE: return "workspace missing or too small";
+    case SVD_ERR_UNSUPPORTED: return "unsupported block shape";
+    case SVD_ERR_HIP: return "HIP error";
+    default: return "unknown status";
+  }
+}
+
+svd_status svd_default_blocks(int32_t D, int32_t* block_q, int32_t* block_k) {
+  if (!block_q || !block_k) return SVD_ERR_NULL;
+  if (D != 64 && D != 128) return SVD_ERR_SHAPE;
+  int q = 0, k = 0;
+  svd::kernel_blocks(D, &q, &k);
+  *block_q = q;
+  *block_k = k;
+  return SVD_OK;
+}
+
+svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* strategy_table,
+                                    const svd_head_params* pattern_params,
+                                    const svd_plan_options* options, size_t* bytes) {
+  if (!desc || !strategy_table || !pattern_params || !bytes) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  int32_t bq, bk;
+  bool native;
+  if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
+  Plan tmp;
+  if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, &tmp)) return st;
+  *bytes = tmp.ws_image.size() * sizeof(int32_t);
+  return SVD_OK;
+}
+
+svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
+                           const int32_t* strategy_table, const svd_head_params* pattern_params,
+                           const svd_plan_options* options, void* device_workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  if (!plan || !desc || !strategy_table || !pattern_params) return SVD_ERR_NULL;
+  *plan = nullptr;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  int32_t bq, bk;
+  bool native;
+  if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
+  svd_plan* sp = new (std::nothrow) svd_plan();
+  if (!sp) return SVD_ERR_HIP;
+  svd_status st = SVD_OK;
+  try {
+    st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, &sp->p);
+  } catch (...) {
+    st = SVD_ERR_UNSUPPORTED;
+  }
+  if (st != SVD_OK) {
+    delete sp;
+    return st;
+  }
+  if (device_workspace) {
+    const size_t need = sp->p.ws_image.size() * sizeof(int32_t);
+    if (workspace_bytes < need || !aligned16(device_workspace)) {
+      delete sp;
+      return SVD_ERR_WORKSPACE;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(device_workspace, sp->p.ws_image.data(), need, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
+      delete sp;
+      return SVD_ERR_HIP;
+    }
+    sp->p.device_workspace = device_workspace;
+    sp->p.launchable = native;
+  }
+  *plan = sp;
+  return SVD_OK;
+}
+
+svd_status svd_plan_destroy(svd_plan* plan) {
+  if (!plan) return SVD_ERR_NULL;
+  delete plan;
+  return SVD_OK;
+}
+
+svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups) {
+  if (!plan || !n_groups) return SVD_ERR_NULL;
+  *n_groups = static_cast<int32_t>(plan->p.groups.size());
+  return SVD_OK;
+}
+
+svd_status svd_plan_group_info(const svd_plan* plan, int32_t group, int32_t* mode, int32_t* n_heads,
+                               const int32_t** heads, const int32_t** list_id, int32_t* n_lists) {
+  if (!plan) return SVD_ERR_NULL;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  const svd::Group& g = plan->p.groups[group];
+  if (mode) *mode = g.mode;
+  if (n_heads) *n_heads = static_cast<int32_t>(g.heads.size());
+  if (heads) *heads = g.heads.data();
+  if (list_id) *list_id = g.list_id.data();
+  if (n_lists) *n_lists = static_cast<int32_t>(g.bands.size() + g.columns.size());
+  return SVD_OK;
+}
+
+svd_status svd_plan_band_list(const svd_plan* plan, int32_t group, int32_t list,
+                              int32_t* n_q_blocks, const int32_t** row_ptr,
+                              const int32_t** kv_block_idx, const int32_t** flags,
+                              const int32_t** run_first, const int32_t** run_count,
+                              int32_t* n_runs, const int32_t** runs) {
+  if (!plan) return SVD_ERR_NULL;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  const svd::Group& g = plan->p.groups[group];
+  if (list < 0 || list >= static_cast<int32_t>(g.bands.size())) return SVD_ERR_SHAPE;
+  const svd::BandList& bl = g.bands[list];
+  if (n_q_blocks) *n_q_blocks = plan->p.n_q_blocks;
+  if (row_ptr) *row_ptr = bl.row_ptr.data();
+  if (kv_block_idx) *kv_block_idx = bl.kv_block_idx.data();
+  if (flags) *flags = bl.flags.data();
+  if (run_first) *run_first = bl.run_first.data();
+  if (run_count) *run_count = bl.run_count.data();
+  if (n_runs) *n_runs = static_cast<int32_t>(bl.runs.size() / 2);
+  if (runs) *runs = bl.runs.data();
+  return SVD_OK;
+}
+
+svd_status svd_plan_column_list(const svd_plan* plan, int32_t group, int32_t list,
+                                int32_t* n_cols, int32_t* padded_len, const int32_t** cols) {
+  if (!plan) return SVD_ERR_NULL;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  const svd::Group& g = plan->p.groups[group];
+  if (list < 0 || list >= static_cast<int32_t>(g.columns.size())) return SVD_ERR_SHAPE;
+  const svd::ColumnList& cl = g.columns[list];
+  if (n_cols) *n_cols = cl.n_cols;
+  if (padded_len) *padded_len = static_cast<int32_t>(cl.cols.size());
+  if (cols) *cols = cl.cols.data();
+  return SVD_OK;
+}
+
+svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* computed_flops,
+                         double* kept_pairs) {
+  if (!plan) return SVD_ERR_NULL;
+  const Plan& p = plan->p;
+  const double L = p.desc.L;
+  int64_t tiles = 0;
+  double area = 0.0, pairs = 0.0;
+  for (const svd::Group& g : p.groups) {
+    for (size_t t = 0; t < g.heads.size(); ++t) {
+      switch (g.mode) {
+        case SVD_DENSE:
+          tiles += static_cast<int64_t>(p.n_q_blocks) * p.n_k_blocks;
+          area += L * L;
+          pairs += L * L;
+          break;
+        case SVD_DIAG:
+        case SVD_MULTIDIAG: {
+          const svd::BandList& bl = g.bands[g.list_id[t]];
+          tiles += static_cast<int64_t>(bl.kv_block_idx.size());
+          area += bl.tile_area;
+          pairs += bl.kept_pairs;
+          break;
+        }
+        case SVD_VSTRIPE: {
+          const svd::ColumnList& cl = g.columns[g.list_id[t]];
+          tiles += static_cast<int64_t>(p.n_q_blocks) * static_cast<int64_t>(cl.cols.size() / p.block_k);
+          area += L * cl.n_cols;
+          pairs += L * cl.n_cols;
+          break;
+        }
+        default:
+          break;
+      }
+    }
+  }
+  if (computed_tiles) *computed_tiles = tiles * p.desc.B;
+  if (computed_flops) *computed_flops = 4.0 * p.desc.D * area * p.desc.B;
+  if (kept_pairs) *kept_pairs = pairs * p.desc.B;
+  return SVD_OK;
+}
+
+svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
+                                    void* out, void* hip_stream) {
+  if (!plan) return SVD_ERR_NULL;
+  if (svd_status st = check_tensors(q, k, v, out)) return st;
+  const Plan& p = plan->p;
+  if (!p.device_workspace) return SVD_ERR_WORKSPACE;
+  if (!p.launchable) return SVD_ERR_UNSUPPORTED;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int* ws = static_cast<const int*>(p.device_workspace);
+  // heaviest first: dense, then the band groups, the gathers, and the zero fill
+  static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
+  for (int mode : order) {
+    for (const svd::Group& g : p.groups) {
+      if (g.mode != mode) continue;
+      svd::AttnLaunch a = base_launch(p.desc, q, k, v, out);
+      a.n_q_blocks = p.n_q_blocks;
+      a.n_heads = static_cast<int>(g.heads.size());
+      a.n_items = a.n_q_blocks * a.n_heads * a.B;
+      a.heads = ws + g.ws_heads;
+      a.list_id = ws + g.ws_list_id;
+      a.ws = ws;
+      a.list_table = static_cast<int>(g.ws_list_table);
+      hipError_t err;
+      if (mode == SVD_SKIP) {
+        err = svd::launch_zero_heads(a, stream);
+      } else {
+        const int kmode = mode == SVD_DENSE ? svd::MODE_DENSE
+                          : mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+        err = svd::launch_attention(a, kmode, stream);
+      }
+      if (err != hipSuccess) return SVD_ERR_HIP;
+    }
+  }
+  return SVD_OK;
+}
+
+svd_status svd_dense_attn_forward(const void* q, const void* k, const void* v, void* out,
+                                  const svd_tensor_desc* desc, void* hip_stream) {
+  if (!desc) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  if (svd_status st = check_tensors(q, k, v, out)) return st;
+  int bq = 0, bk = 0;
+  svd::kernel_blocks(desc->D, &bq, &bk);
+  svd::AttnLaunch a = base_launch(*desc, q, k, v, out);
+  a.n_q_blocks = (desc->L + bq - 1) / bq;
+  a.n_heads = desc->H;
+  a.n_items = a.n_q_blocks * a.n_heads * a.B;
+  if (svd::launch_attention(a, svd::MODE_DENSE, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SVD_ERR_HIP;
+  return SVD_OK;
+}
+
+svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
+                                    const int32_t* strategy_table,
+                                    const svd_head_params* pattern_params, void* out,
+                                    const svd_tensor_desc* desc, void* device_workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !strategy_table || !pattern_params) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  if (svd_status st = check_tensors(q, k, v, out)) return st;
+  if (!device_workspace) return SVD_ERR_WORKSPACE;
+  for (int h = 0; h < desc->H; ++h)
+    if (strategy_table[h] < SVD_DENSE || strategy_table[h] > SVD_VSTRIPE) return SVD_ERR_MODE;
+  std::lock_guard<std::mutex> lock(g_oneshot.mu);
+  std::vector<int32_t> table(strategy_table, strategy_table + desc->H);
+  std::vector<int32_t> flat = flatten(*desc, strategy_table, pattern_params);
+  const bool hit = g_oneshot.plan && std::memcmp(&g_oneshot.desc, desc, sizeof(*desc)) == 0 &&
+                   g_oneshot.table == table && g_oneshot.flat == flat &&
+                   g_oneshot.workspace == device_workspace && g_oneshot.workspace_bytes == workspace_bytes;
+  if (!hit) {
+    svd_plan* fresh = nullptr;
+    if (svd_status st = svd_plan_create(&fresh, desc, strategy_table, pattern_params, nullptr,
+                                        device_workspace, workspace_bytes, hip_stream))
+      return st;
+    if (g_oneshot.plan) svd_plan_destroy(g_oneshot.plan);
+    g_oneshot.plan = fresh;
+    g_oneshot.desc = *desc;
+    g_oneshot.table.swap(table);
+    g_oneshot.flat.swap(flat);
+    g_oneshot.workspace = device_workspace;
+    g_oneshot.workspace_bytes = workspace_bytes;
+  }
+  return svd_attn_forward_planned(g_oneshot.plan, q, k, v, out, hip_stream);
+}
+
+}  // extern "C"

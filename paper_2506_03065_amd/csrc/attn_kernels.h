@@ -1,0 +1,40 @@
+// Launch interface between the host API and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace svd {
+
+// Kernel-level modes: the five modes of Section 4.2 map to three loop shapes
+// (diagonal and multi-diagonal share the banded one) plus the zero fill.
+enum { MODE_DENSE = 0, MODE_BAND = 1, MODE_GATHER = 2 };
+
+// Tile shapes the kernels are instantiated for.  Query tile = NW waves x QB
+// blocks of 32 rows; key tile = BC keys.
+struct Tile128 { static constexpr int NW = 4, QB = 2, BC = 64; };   // D = 128
+struct Tile64  { static constexpr int NW = 4, QB = 2, BC = 128; };  // D = 64
+
+struct AttnLaunch {
+  const __bf16* q;
+  const __bf16* k;
+  const __bf16* v;
+  __bf16* out;
+  int B, H, L, D;
+  int64_t stride_b, stride_h, stride_l;   // elements
+  int n_q_blocks;        // query tiles per head
+  int n_heads;           // heads in this launch
+  int n_items;           // n_q_blocks * n_heads * B
+  const int* heads;      // device: head ids of the group, or nullptr = identity
+  const int* list_id;    // device: per head of the group, its list
+  const int* ws;         // device: workspace base (int32 words)
+  int list_table;        // word offset of the group's list records
+  float scale_log2e;     // log2(e) / sqrt(D)
+};
+
+void kernel_blocks(int D, int* block_q, int* block_k);
+hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream);
+hipError_t launch_zero_heads(const AttnLaunch& p, hipStream_t stream);
+
+}  // namespace svd

@@ -1,0 +1,445 @@
+// gfx950 (MI355X, CDNA4) kernels of the sparse attention forward.
+//
+// One kernel template serves the three computing modes of Section 4.2:
+//   DENSE   M_0, Eq. 1 over every key block
+//   BAND    M_2 / M_3 (Section 4.1.2 diagonal and multi-diagonal patterns):
+//           key blocks come from a CSR list, partially kept tiles are masked
+//           element-wise against the runs of kept diagonals
+//   GATHER  M_4 (vertical-stripe pattern): key rows are gathered through the
+//           head's sorted column list
+// plus a fill kernel for M_1 (skipped heads, zeros).  A launch covers all heads
+// of a group (Section 4.2: heads sharing a mode are fused).
+//
+// Per work-group: one tile of BR query rows of one head.  Online-softmax
+// recurrence over the listed key tiles; scores are computed TRANSPOSED,
+// S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a lane owns one query
+// column: the row maximum and row sum are per-lane scalars (one cross-half
+// exchange), and the exponentiated scores already sit in the operand layout of
+// the second product O^T += V^T P^T.  V^T fragments come from the row-major V
+// tile in LDS through the transposing LDS read (ds_read_b64_tr_b16).
+// Accumulation, scores and softmax are fp32; P is rounded to bf16 for the
+// second product.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "attn_kernels.h"
+
+namespace svd {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr float kNegInf = -__builtin_inff();
+
+// Exchange between the two half-waves (lanes l and l ^ 32) with
+// v_permlane32_swap: given (a, b) it returns {a.lower | b.lower moved up,
+// a.upper moved down | b.upper}; with a == b == x every lane gets the value of
+// the lower-half lane of its pair and that of the upper-half lane.
+__device__ __forceinline__ void half_pair(float x, float* own_lo, float* own_hi) {
+  const unsigned a = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+  const unsigned r0 = r[0], r1 = r[1];   // scalars first: bit_cast of a vector element misreads lane 0
+  *own_lo = __builtin_bit_cast(float, r0);
+  *own_hi = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float half_max(float x) {
+  float lo, hi;
+  half_pair(x, &lo, &hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float half_sum(float x) {
+  float lo, hi;
+  half_pair(x, &lo, &hi);
+  return lo + hi;
+}
+
+// 16-byte chunk swizzles of the LDS tiles (row = key, chunk = 8 bf16 of D).
+// K is read 16 bytes per lane with consecutive lanes on consecutive keys; V is
+// read through the transposing read, 4 keys x 64 bytes per half-wave.
+template <int D>
+__device__ __forceinline__ int swz_k(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D>
+__device__ __forceinline__ int swz_v(int row) {
+  return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+}
+
+template <int D, int NW, int QB, int BC, int MODE>
+__global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
+  constexpr int NT = NW * 64;
+  constexpr int QW = QB * 32;       // query rows per wave
+  constexpr int BR = NW * QW;       // query rows per work-group
+  constexpr int CH = D / 8;         // 16-byte chunks per row
+  constexpr int KB2 = BC / 32;      // 32-key blocks per tile
+  constexpr int KS = D / 16;        // contraction steps of S^T = K Q^T
+  constexpr int DB = D / 32;        // 32-row blocks of O^T
+  constexpr int NCH = BC * CH / NT; // chunks per thread and tile (K and V each)
+  static_assert(BC * CH % NT == 0, "tile must split evenly over the threads");
+  constexpr int TILE_BYTES = BC * D * 2;
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE_BYTES];
+  unsigned char* const sK = smem;                    // [2][BC][D] bf16, swizzled
+  unsigned char* const sV = smem + 2 * TILE_BYTES;   // [2][BC][D] bf16, swizzled
+
+  // ---- which tile of which head (XCD-aware: consecutive items share an XCD) ----
+  const int per_xcd = (p.n_items + 7) >> 3;
+  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (item >= p.n_items) return;
+  const int qblk = item % p.n_q_blocks;
+  const int hb = item / p.n_q_blocks;
+  const int hg = hb % p.n_heads;
+  const int b = hb / p.n_heads;
+  const int head = p.heads ? p.heads[hg] : hg;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l32 = lane & 31;
+  const int half = lane >> 5;
+
+  const int64_t base = (int64_t)b * p.stride_b + (int64_t)head * p.stride_h;
+  const __bf16* __restrict__ Q = p.q + base;
+  const __bf16* __restrict__ K = p.k + base;
+  const __bf16* __restrict__ V = p.v + base;
+  __bf16* __restrict__ O = p.out + base;
+  const int L = p.L;
+
+  // ---- the list this head walks ----
+  int n_tiles = 0;
+  const int2* __restrict__ entries = nullptr;  // BAND
+  const int2* __restrict__ runs = nullptr;     // BAND
+  const int* __restrict__ cols = nullptr;      // GATHER
+  int n_cols = 0;
+  if (MODE == MODE_DENSE) {
+    n_tiles = (L + BC - 1) / BC;
+  } else {
+    const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
+    if (MODE == MODE_BAND) {
+      const int* row_ptr = p.ws + rec[0];
+      const int e0 = row_ptr[qblk], e1 = row_ptr[qblk + 1];
+      entries = reinterpret_cast<const int2*>(p.ws + rec[1]) + e0;
+      runs = reinterpret_cast<const int2*>(p.ws + rec[2]);
+      n_tiles = e1 - e0;
+    } else {
+      cols = p.ws + rec[0];
+      n_tiles = rec[1] / BC;
+      n_cols = rec[2];
+    }
+  }
+
+  // ---- Q fragments: B operand of S^T = K Q^T (lane: query l32, 8 of 16 d) ----
+  const int q0 = qblk * BR + wave * QW;
+  bf16x8 qf[QB][KS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    int row = q0 + qb * 32 + l32;
+    row = row < L ? row : L - 1;
+    const __bf16* src = Q + (int64_t)row * p.stride_l + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+  }
+
+  f32x16 o[DB][QB];
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = kNegInf;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
+  }
+
+  // ---- tile loader: global -> registers -> LDS ----
+  u32x4 kreg[NCH], vreg[NCH];
+#define SVD_LOAD_TILE(T)                                                                   \
+  {                                                                                        \
+    _Pragma("unroll") for (int u = 0; u < NCH; ++u) {                                      \
+      const int g_ = u * NT + tid;                                                         \
+      const int r_ = g_ / CH, c_ = g_ % CH;                                                \
+      int row_;                                                                            \
+      if (MODE == MODE_GATHER) {                                                           \
+        row_ = cols[(T) * BC + r_];                                                        \
+        row_ = row_ < 0 ? 0 : row_;                                                        \
+      } else {                                                                             \
+        const int kb_ = MODE == MODE_BAND ? entries[(T)].x : (T);                          \
+        row_ = kb_ * BC + r_;                                                              \
+        row_ = row_ < L ? row_ : L - 1;                                                    \
+      }                                                                                    \
+      const int64_t off_ = (int64_t)row_ * p.stride_l + c_ * 8;                            \
+      kreg[u] = *reinterpret_cast<const u32x4*>(K + off_);                                 \
+      vreg[u] = *reinterpret_cast<const u32x4*>(V + off_);                                 \
+    }                                                                                      \
+  }
+#define SVD_STORE_TILE(BUF)                                                                \
+  {                                                                                        \
+    _Pragma("unroll") for (int u = 0; u < NCH; ++u) {                                      \
+      const int g_ = u * NT + tid;                                                         \
+      const int r_ = g_ / CH, c_ = g_ % CH;                                                \
+      *reinterpret_cast<u32x4*>(sK + (BUF) * TILE_BYTES + r_ * (D * 2) +                   \
+                                ((c_ ^ swz_k<D>(r_)) << 4)) = kreg[u];                     \
+      *reinterpret_cast<u32x4*>(sV + (BUF) * TILE_BYTES + r_ * (D * 2) +                   \
+                                ((c_ ^ swz_v<D>(r_)) << 4)) = vreg[u];                     \
+    }                                                                                      \
+  }
+
+  const float c_scale = p.scale_log2e;
+
+  if (n_tiles > 0) {
+    SVD_LOAD_TILE(0);
+    SVD_STORE_TILE(0);
+  }
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int buf = t & 1;
+    const bool more = t + 1 < n_tiles;
+    if (more) SVD_LOAD_TILE(t + 1);
+
+    // ---- S^T = K Q^T ----
+    f32x16 s[KB2][QB];
+#pragma unroll
+    for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb2][qb][i] = 0.f;
+    const unsigned char* kbase = sK + buf * TILE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int kb2 = 0; kb2 < KB2; ++kb2) {
+        const int r = kb2 * 32 + l32;
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + r * (D * 2) +
+                                                         (((2 * ks + half) ^ swz_k<D>(r)) << 4));
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          s[kb2][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[kb2][qb], 0, 0, 0);
+      }
+    }
+
+    // ---- masks: element (kb2, i) of lane is key kb2*32 + (i/4)*8 + half*4 + i%4 ----
+    if (MODE == MODE_BAND) {
+      const int2 ent = entries[t];
+      if (!(ent.y & 1)) {
+        const int kv0 = ent.x * BC;
+        const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
+#pragma unroll
+        for (int kb2 = 0; kb2 < KB2; ++kb2) {
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) {
+            const int iq = q0 + qb * 32 + l32;
+            const int jb = kv0 + kb2 * 32 + half * 4;   // key of element 0
+            f32x16 kept;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
+            for (int r = r0; r < r0 + rn; ++r) {
+              const int2 run = runs[r];
+              // kept iff run.x <= j - iq <= run.y and j < L
+              int hi = run.y;
+              hi = hi < L - 1 - iq ? hi : L - 1 - iq;
+              const int t0 = jb - iq - run.x;
+              const int span = hi - run.x;    // may be negative: nothing kept
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const int d = t0 + (i / 4) * 8 + (i % 4);
+                kept[i] = (d >= 0 && d <= span) ? s[kb2][qb][i] : kept[i];
+              }
+            }
+            s[kb2][qb] = kept;
+          }
+        }
+      }
+    } else {
+      // dense: keys past L in the last tile; gather: padding of the column list
+      const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
+      if (limit < BC) {
+#pragma unroll
+        for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int j = kb2 * 32 + half * 4 + (i / 4) * 8 + (i % 4);
+              s[kb2][qb][i] = j < limit ? s[kb2][qb][i] : kNegInf;
+            }
+      }
+    }
+
+    // ---- online softmax (per lane: one query column) ----
+    bf16x8 pf[KB2][2][QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float mx = kNegInf;
+#pragma unroll
+      for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[kb2][qb][i], s[kb2][qb][i + 1]));
+      mx = half_max(mx);
+      const float m_new = fmaxf(m_run[qb], mx);
+      const float m_use = m_new == kNegInf ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_use) * c_scale);
+      m_run[qb] = m_new;
+      const float mc = m_use * c_scale;
+      float rs = 0.f;
+#pragma unroll
+      for (int kb2 = 0; kb2 < KB2; ++kb2) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          bf16x8 pk;
+#pragma unroll
+          for (int i = 0; i < 8; i += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i], c_scale, -mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i + 1], c_scale, -mc));
+            rs += p0 + p1;
+            const f32x2 pp = {p0, p1};
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+            pk[i] = pb[0];
+            pk[i + 1] = pb[1];
+          }
+          pf[kb2][sub][qb] = pk;
+        }
+      }
+      l_run[qb] = l_run[qb] * alpha + rs;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T ----
+    const unsigned char* vbase = sV + buf * TILE_BYTES;
+    const int ti = lane & 15;           // lane inside its block of 16
+    const int dsel = (lane >> 4) & 1;   // which 16 of the 32 d rows
+#pragma unroll
+    for (int kb2 = 0; kb2 < KB2; ++kb2) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          // lane supplies the address of (key row, 4 d) and receives 4 keys of one d
+          const int c = db * 4 + 2 * dsel + ((ti & 3) >> 1);
+          const int hb8 = (ti & 1) << 3;
+          const int ra = kb2 * 32 + sub * 16 + half * 4 + (ti >> 2);
+          const int rb = ra + 8;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4*)(vbase + ra * (D * 2) + ((c ^ swz_v<D>(ra)) << 4) + hb8));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4*)(vbase + rb * (D * 2) + ((c ^ swz_v<D>(rb)) << 4) + hb8));
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb2][sub][qb], o[db][qb], 0, 0, 0);
+        }
+      }
+    }
+
+    if (more) SVD_STORE_TILE(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: O = O^T / l, bf16, lane owns query l32: 4 consecutive d per store ----
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float l_tot = half_sum(l_run[qb]);
+    const float inv = 1.0f / l_tot;
+    const int row = q0 + qb * 32 + l32;
+    if (row < L) {
+      __bf16* dst = O + (int64_t)row * p.stride_l;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x2 a01 = {o[db][qb][g * 4 + 0] * inv, o[db][qb][g * 4 + 1] * inv};
+          const f32x2 a23 = {o[db][qb][g * 4 + 2] * inv, o[db][qb][g * 4 + 3] * inv};
+          const bf16x2 b01 = __builtin_convertvector(a01, bf16x2);
+          const bf16x2 b23 = __builtin_convertvector(a23, bf16x2);
+          const bf16x4 out4 = {b01[0], b01[1], b23[0], b23[1]};
+          *reinterpret_cast<bf16x4*>(dst + db * 32 + g * 8 + half * 4) = out4;
+        }
+      }
+    }
+  }
+}
+
+#undef SVD_LOAD_TILE
+#undef SVD_STORE_TILE
+
+// M_1 (Section 4.2): the output of a skipped head is zero.
+__global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
+  const int hg = blockIdx.y % p.n_heads;
+  const int b = blockIdx.y / p.n_heads;
+  const int head = p.heads ? p.heads[hg] : hg;
+  __bf16* O = p.out + (int64_t)b * p.stride_b + (int64_t)head * p.stride_h;
+  const int chunks = p.D / 8;
+  const int64_t total = (int64_t)p.L * chunks;
+  for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < total;
+       g += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = g / chunks;
+    const int c = (int)(g % chunks);
+    *reinterpret_cast<uint4*>(O + row * p.stride_l + c * 8) = make_uint4(0, 0, 0, 0);
+  }
+}
+
+template <int D, int NW, int QB, int BC>
+hipError_t launch_mode(const AttnLaunch& p, int mode, hipStream_t stream) {
+  const int per_xcd = (p.n_items + 7) / 8;
+  const dim3 grid(per_xcd * 8), block(NW * 64);
+  switch (mode) {
+    case MODE_DENSE:
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, MODE_DENSE>), grid, block, 0, stream, p);
+      break;
+    case MODE_BAND:
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, MODE_BAND>), grid, block, 0, stream, p);
+      break;
+    case MODE_GATHER:
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, MODE_GATHER>), grid, block, 0, stream, p);
+      break;
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+void kernel_blocks(int D, int* block_q, int* block_k) {
+  if (D == 128) {
+    *block_q = Tile128::NW * Tile128::QB * 32;
+    *block_k = Tile128::BC;
+  } else {
+    *block_q = Tile64::NW * Tile64::QB * 32;
+    *block_k = Tile64::BC;
+  }
+}
+
+hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream) {
+  if (p.n_items <= 0) return hipSuccess;
+  if (p.D == 128) return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC>(p, mode, stream);
+  if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC>(p, mode, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_zero_heads(const AttnLaunch& p, hipStream_t stream) {
+  if (p.n_heads <= 0) return hipSuccess;
+  const int64_t total = (int64_t)p.L * (p.D / 8);
+  int bx = (int)((total + 255) / 256);
+  if (bx > 2048) bx = 2048;
+  const dim3 grid(bx, p.n_heads * p.B), block(256);
+  hipLaunchKernelGGL(zero_heads_kernel, grid, block, 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace svd

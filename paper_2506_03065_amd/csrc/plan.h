@@ -1,0 +1,73 @@
+// Host-side data model of a compiled layer plan (pattern compiler output).
+//
+// Section 4.2 of the paper fixes, per layer, one mode per head and fuses heads
+// that share a mode.  A plan is that grouping plus, for the sparse modes, the
+// block-level description of the kept region of the attention map that the
+// kernels iterate over.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "sparse_vdit.h"
+
+namespace svd {
+
+// One distinct band pattern (modes 2, 3): kept diagonals delta = j - i.
+struct BandList {
+  int32_t half_width = 0;
+  std::vector<int32_t> offsets;       // sorted, unique
+  std::vector<int32_t> runs;          // 2 * n_runs: inclusive [lo, hi] of merged kept diagonals
+  std::vector<int32_t> row_ptr;       // n_q_blocks + 1
+  std::vector<int32_t> kv_block_idx;  // per entry
+  std::vector<int32_t> flags;         // per entry: 1 = tile needs no mask
+  std::vector<int32_t> run_first;     // per entry
+  std::vector<int32_t> run_count;     // per entry
+  double kept_pairs = 0.0;            // element-level count for one head
+  double tile_area = 0.0;             // sum over entries of in-range rows * in-range keys
+};
+
+// One distinct column set (mode 4).
+struct ColumnList {
+  int32_t n_cols = 0;
+  std::vector<int32_t> cols;          // sorted, padded with -1 to a multiple of block_k
+};
+
+struct Group {
+  int32_t mode = 0;
+  std::vector<int32_t> heads;         // ascending
+  std::vector<int32_t> list_id;       // per head of the group
+  std::vector<BandList> bands;        // modes 2, 3
+  std::vector<ColumnList> columns;    // mode 4
+  // word offsets into the device workspace (valid when the plan is launchable)
+  size_t ws_heads = 0, ws_list_id = 0, ws_list_table = 0;
+};
+
+// Per-list record in the device workspace, 4 int32 words.
+//   band list:   {row_ptr offset, entries offset, runs offset, n_runs}
+//   column list: {cols offset, padded_len, n_cols, 0}
+// Offsets are in int32 words from the workspace base.  A band entry is two
+// words {kv_block_idx, meta}, meta = flag | run_first << 1 | run_count << 16.
+constexpr int kListRecordWords = 4;
+constexpr int32_t kMaxRuns = 32767;
+
+struct Plan {
+  svd_tensor_desc desc{};
+  int32_t block_q = 0, block_k = 0;
+  int32_t n_q_blocks = 0, n_k_blocks = 0;
+  std::vector<Group> groups;          // ascending mode id
+  std::vector<int32_t> ws_image;      // host image of the device workspace
+  void* device_workspace = nullptr;   // nullptr: host-only plan
+  bool launchable = false;            // block shape matches the kernels and workspace present
+};
+
+// Validates the table and parameters and fills plan->groups (lists included)
+// and plan->ws_image.  Pure host code, no HIP.
+svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
+                        const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
+                        Plan* plan);
+
+svd_status validate_desc(const svd_tensor_desc* desc);
+
+}  // namespace svd

@@ -1,0 +1,155 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sparse_attention as O
+from paper_2506_03065_amd import binding as svd
+from paper_2506_03065_amd import workloads as W
+from parity_util import assert_close, check_layer, f64, run_planned
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _cuda(ts):
+    return [t.to(DEV) for t in ts]
+
+
+def test_tiny_all_rows():
+    wl = W.tiny()
+    q, k, v = _cuda(W.make_qkv(wl))
+    out = run_planned(wl, q, k, v)
+    check_layer(wl, q, k, v, out)
+
+
+@pytest.mark.parametrize("L,D,H,seed,B", [(333, 64, 5, 7, 1), (200, 128, 5, 11, 1), (1000, 64, 5, 3, 1),
+                                           (1000, 128, 5, 4, 1), (77, 128, 4, 5, 1), (31, 64, 4, 6, 1),
+                                           (520, 128, 10, 8, 2), (700, 64, 5, 9, 2)])
+def test_small_ragged_all_rows(L, D, H, seed, B):
+    wl = W.small(L=L, D=D, H=H, seed=seed, B=B)
+    q, k, v = _cuda(W.make_qkv(wl))
+    out = run_planned(wl, q, k, v)
+    check_layer(wl, q, k, v, out)
+    skipped = [h for h in range(wl.H) if wl.strategy_table[h] == W.SKIP]
+    for h in skipped:
+        assert not out[:, h].view(torch.int16).any(), "skipped head must be exact zeros"
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_dense_entry_point(D):
+    wl = W.small(L=777, D=D, H=3, seed=21)
+    wl.strategy_table[:] = W.DENSE
+    q, k, v = _cuda(W.make_qkv(wl))
+    out = torch.full_like(q, float("nan"))
+    svd.svd_dense_attn_forward(q, k, v, out)
+    torch.cuda.synchronize()
+    check_layer(wl, q, k, v, out)
+
+
+def test_one_shot_entry_point_and_plan_reuse():
+    wl = W.small(L=600, D=128, H=5, seed=31)
+    q, k, v = _cuda(W.make_qkv(wl))
+    nbytes = svd.svd_plan_workspace_bytes(svd.desc_of(q), wl.strategy_table, wl.pattern_params)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    out = torch.full_like(q, float("nan"))
+    for _ in range(2):   # second call reuses the compiled plan
+        out.fill_(float("nan"))
+        svd.sparse_vdit_attn_forward(q, k, v, wl.strategy_table, wl.pattern_params, out, ws)
+        torch.cuda.synchronize()
+        check_layer(wl, q, k, v, out)
+    # a different table through the same workspace recompiles
+    wl2 = W.small(L=600, D=128, H=5, seed=32)
+    wl2.strategy_table = wl.strategy_table[::-1].copy()
+    wl2.pattern_params = wl.pattern_params[::-1]
+    svd.sparse_vdit_attn_forward(q, k, v, wl2.strategy_table, wl2.pattern_params, out, ws)
+    torch.cuda.synchronize()
+    check_layer(wl2, q, k, v, out)
+
+
+def test_strided_token_major_layout():
+    """[B, L, H, D] storage viewed as [B, H, L, D] (the merged-head layout)."""
+    wl = W.small(L=450, D=64, H=5, seed=41)
+    q, k, v = _cuda(W.make_qkv(wl))
+    qs, ks, vs = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    assert not qs.is_contiguous()
+    out = torch.full_like(qs, float("nan"))
+    assert out.stride() == qs.stride()
+    run_planned(wl, qs, ks, vs, out)
+    check_layer(wl, q, k, v, out)
+
+
+def test_wide_patterns_equal_dense_and_edge_parameters():
+    L, D = 500, 64
+    table = np.asarray([W.DENSE, W.DIAG, W.MULTIDIAG, W.VSTRIPE, W.DIAG, W.MULTIDIAG, W.VSTRIPE], dtype=np.int32)
+    params = [{}, {"half_width": L - 1}, {"half_width": 60, "offsets": tuple(range(-480, 481, 120))},
+              {"cols": tuple(range(L))}, {"half_width": 0}, {"half_width": 1, "offsets": (0, 3, 7, 200, -200)},
+              {"cols": (499,)}]
+    wl = W.Workload("edges", -1, 1, len(table), L, D, 100, 5, 0, table, params, 51)
+    q, k, v = W.make_qkv(wl)
+    for t in (q, k, v):          # same inputs for the heads compared with the dense one
+        t[:, 1:4] = t[:, 0:1]
+    q, k, v = _cuda((q, k, v))
+    out = run_planned(wl, q, k, v)
+    check_layer(wl, q, k, v, out)
+    for h in (1, 2, 3):
+        assert_close(f64(out[0, h]), f64(out[0, 0]), f"full-width head {h} vs dense")
+
+
+def test_closed_forms_constant_v_and_zero_q():
+    wl = W.small(L=900, D=128, H=5, seed=61)
+    q, k, v = _cuda(W.make_qkv(wl))
+    vc = torch.full_like(v, 0.625)
+    out = run_planned(wl, q, k, vc)
+    for h in range(wl.H):
+        want = 0.0 if wl.strategy_table[h] == W.SKIP else 0.625
+        assert torch.allclose(out[0, h].float(), torch.full_like(out[0, h].float(), want), atol=4e-3)
+    out = run_planned(wl, torch.zeros_like(q), k, v)
+    vf = f64(v[0])
+    for h in range(wl.H):
+        mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+        if mode == W.SKIP:
+            continue
+        prefix = np.concatenate([np.zeros((1, wl.D)), np.cumsum(vf[h], axis=0)])
+        want = np.zeros((wl.L, wl.D))
+        if mode == W.DENSE:
+            want[:] = vf[h].mean(axis=0)
+        elif mode == W.VSTRIPE:
+            want[:] = vf[h][list(p["cols"])].mean(axis=0)
+        else:
+            w = p["half_width"]
+            for i in range(wl.L):
+                tot, cnt = 0.0, 0
+                for o in p["offsets"]:
+                    lo, hi = max(0, i + o - w), min(wl.L, i + o + w + 1)
+                    if hi > lo:
+                        tot, cnt = tot + prefix[hi] - prefix[lo], cnt + hi - lo
+                want[i] = tot / cnt
+        assert_close(f64(out[0, h]), want, f"zero-q mean, head {h}")
+
+
+def test_errors_leave_output_untouched():
+    wl = W.small(L=300, D=64, H=5, seed=71)
+    q, k, v = _cuda(W.make_qkv(wl))
+    out = torch.full_like(q, 3.0)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=DEV)
+    bad = wl.strategy_table.copy()
+    bad[0] = 9
+    with pytest.raises(svd.SvdError) as e:
+        svd.sparse_vdit_attn_forward(q, k, v, bad, wl.pattern_params, out, ws)
+    assert e.value.status == 5
+    with pytest.raises(svd.SvdError) as e:
+        svd.sparse_vdit_attn_forward(q, k, v, wl.strategy_table, wl.pattern_params, out, ws[:16])
+    assert e.value.status == 8
+    with pytest.raises(svd.SvdError) as e:   # misaligned base pointer
+        svd.svd_dense_attn_forward(q.view(-1)[4:4 + 64 * 64].view(1, 1, 64, 64), k, v, out)
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+    assert (out == 3.0).all()
+    # a plan compiled for another block shape can be inspected but not launched
+    desc = svd.desc_of(q)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, 32, 32, workspace=ws)
+    with pytest.raises(svd.SvdError) as e:
+        svd.svd_attn_forward_planned(plan, q, k, v, out)
+    assert e.value.status == 9
+    assert (out == 3.0).all()

@@ -1,0 +1,188 @@
+"""Host-side checks of the C-ABI library that need no GPU: the shared library
+loads and exports what the header declares, argument validation, and the pattern
+compiler's lists bit-exact against the oracle's explicit-mask lists."""
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import sparse_attention as O
+from paper_2506_03065_amd import binding as svd
+from paper_2506_03065_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = json.load(open(os.path.join(ROOT, "tests", "golden", "pattern_counts.json")))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "sparse_vdit.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(svd_[a-z_]+|sparse_vdit_attn_forward)\s*\(", header))
+    assert declared == set(svd.EXPORTS)
+    lib = svd.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert svd.status_string(0) == "ok"
+    assert svd.svd_default_blocks(64)[0] > 0 and svd.svd_default_blocks(128)[1] > 0
+
+
+def _compile(wl, bq, bk):
+    desc = svd.tensor_desc(wl.B, wl.H, wl.L, wl.D)
+    return svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, bq, bk)
+
+
+def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
+    plan = _compile(wl, bq, bk)
+    got_groups = plan.groups()
+    want_groups = O.head_groups(wl.strategy_table, wl.pattern_params)
+    assert [(g["mode"], g["heads"], g["list_id"]) for g in got_groups] == \
+           [(g["mode"], g["heads"], g["list_id"]) for g in want_groups]
+    for gi, g in enumerate(got_groups):
+        if g["mode"] in (svd.SVD_DENSE, svd.SVD_SKIP):
+            assert g["n_lists"] == 0
+            continue
+        assert g["n_lists"] == want_groups[gi]["n_lists"]
+        for lst in range(g["n_lists"]):
+            head = g["heads"][g["list_id"].index(lst)]
+            p = wl.pattern_params[head]
+            if g["mode"] == svd.SVD_VSTRIPE:
+                got = plan.column_list(gi, lst)
+                want = O.column_list(p, wl.L, bk)
+                assert got["n_cols"] == len(p["cols"])
+                assert got["cols"].dtype == np.int32 and np.array_equal(got["cols"], want)
+                continue
+            got = plan.band_list(gi, lst)
+            if q_blocks is None:
+                want = O.block_lists(g["mode"], p, wl.L, bq, bk)
+                for key in ("row_ptr", "kv_block_idx", "flags", "run_first", "run_count", "runs"):
+                    assert got[key].dtype == np.int32
+                    assert np.array_equal(got[key], want[key]), (wl.name, g["mode"], key)
+            else:
+                runs = O.delta_runs(g["mode"], p, wl.L)
+                assert np.array_equal(got["runs"], runs)
+                for qb in q_blocks:
+                    kb, fl, rf, rc = O.query_block_entries(g["mode"], p, wl.L, bq, bk, qb, runs)
+                    s, e = got["row_ptr"][qb], got["row_ptr"][qb + 1]
+                    assert np.array_equal(got["kv_block_idx"][s:e], kb), (wl.name, qb)
+                    assert np.array_equal(got["flags"][s:e], fl), (wl.name, qb)
+                    assert np.array_equal(got["run_first"][s:e], rf)
+                    assert np.array_equal(got["run_count"][s:e], rc)
+    plan.close()
+
+
+@pytest.mark.parametrize("bq,bk", [(128, 128), (64, 64), (256, 64), (256, 128), (32, 16)])
+def test_tiny_lists_bit_exact(bq, bk):
+    _assert_plan_matches_oracle(W.tiny(), bq, bk)
+
+
+@pytest.mark.parametrize("L,D,seed", [(333, 64, 7), (200, 128, 11), (1000, 64, 3), (77, 128, 5)])
+@pytest.mark.parametrize("bq,bk", [(256, 64), (256, 128), (16, 8), (7, 5)])
+def test_small_ragged_lists_bit_exact(L, D, seed, bq, bk):
+    _assert_plan_matches_oracle(W.small(L=L, D=D, seed=seed), bq, bk)
+
+
+def _one_head(mode, p, L):
+    from paper_2506_03065_amd.workloads import Workload
+    base = {"half_width": 0, "offsets": (), "cols": ()}
+    base.update(p)
+    return Workload("adhoc", -1, 1, 1, L, 64, L, 1, 0, np.asarray([mode], dtype=np.int32), [base], 1)
+
+
+@pytest.mark.parametrize("mode,p,L,bq,bk", [
+    (O.MODE_MULTIDIAG, {"half_width": 3, "offsets": (0, 7, -7, 30)}, 47, 16, 4),     # touching bands merge
+    (O.MODE_MULTIDIAG, {"half_width": 1, "offsets": (0, 4, 9)}, 40, 8, 16),          # several runs per tile
+    (O.MODE_MULTIDIAG, {"half_width": 2, "offsets": (0, 5, 11, 17, 23)}, 90, 32, 32),
+    (O.MODE_MULTIDIAG, {"half_width": 0, "offsets": (0, -100, 100)}, 33, 4, 8),      # bands off the map
+    (O.MODE_MULTIDIAG, {"half_width": 4, "offsets": (-20, 20, 0)}, 64, 64, 64),      # one tile in all
+    (O.MODE_DIAG, {"half_width": 1000}, 130, 64, 32),                                # wider than the map
+    (O.MODE_DIAG, {"half_width": 0}, 130, 64, 32),
+])
+def test_band_edge_cases_bit_exact(mode, p, L, bq, bk):
+    _assert_plan_matches_oracle(_one_head(mode, p, L), bq, bk)
+
+
+@pytest.mark.parametrize("name", ["cogvideox1.5", "hunyuanvideo", "wan2.1"])
+def test_full_size_counts_and_sampled_blocks(name):
+    """At the benchmark shapes: listed-tile counts equal the stored counts, the
+    element counts equal the closed form, and sampled query blocks (first, last,
+    around a frame boundary) equal the oracle's explicit-mask entries."""
+    wl = W.BY_NAME[name]()
+    g = GOLDEN[name]
+    for bs, key in ((128, "tiles128"), (64, "tiles64")):
+        plan = _compile(wl, bs, bs)
+        for gi, grp in enumerate(plan.groups()):
+            if grp["mode"] == svd.SVD_DIAG:
+                assert plan.band_list(gi, 0)["kv_block_idx"].size == g[key]["diag"]
+            if grp["mode"] == svd.SVD_MULTIDIAG:
+                assert plan.band_list(gi, 0)["kv_block_idx"].size == g[key]["multi"]
+        plan.close()
+    bq, bk = svd.svd_default_blocks(wl.D)
+    plan = _compile(wl, bq, bk)
+    counts = {int(m): int((wl.strategy_table == m).sum()) for m in range(5)}
+    want_pairs = (counts[0] * wl.L ** 2 + counts[2] * g["diag"]["pairs"] + counts[3] * g["multi"]["pairs"] +
+                  counts[4] * g["vertical"]["pairs"])
+    assert plan.work()["kept_pairs"] == float(want_pairs)
+    plan.close()
+    n_qb = -(-wl.L // bq)
+    frame_edge = (wl.text_tokens + 3 * wl.frame_tokens) // bq
+    _assert_plan_matches_oracle(wl, bq, bk, q_blocks=[0, frame_edge, n_qb - 1])
+
+
+def test_work_counts_tiny():
+    wl = W.tiny()
+    plan = _compile(wl, 128, 128)
+    w = plan.work()
+    g = GOLDEN["tiny"]
+    assert w["kept_pairs"] == 1024 * 1024 + g["diag"]["pairs"] + g["multi"]["pairs"] + g["vertical"]["pairs"]
+    assert w["computed_tiles"] == 64 + g["tiles128"]["diag"] + g["tiles128"]["multi"] + 8 * 1
+    assert w["computed_flops"] == 4.0 * 64 * (1024 * 1024 + (22 + 44) * 128 * 128 + 1024 * 64)
+
+
+def _status(fn, *a, **kw):
+    try:
+        fn(*a, **kw)
+    except svd.SvdError as e:
+        return e.status
+    return 0
+
+
+def test_validation_errors():
+    d = svd.tensor_desc(1, 2, 100, 64)
+    ok = [{"half_width": 3}, {"cols": (1, 2)}]
+    mk = lambda table, params, desc=d: _status(svd.svd_plan_create, desc, table, params)
+    assert mk([2, 4], ok) == 0
+    assert mk([2, 5], ok) == 5                                              # mode id
+    assert mk([2, -1], ok) == 5
+    assert mk([2, 4], [{"half_width": -1}, ok[1]]) == 6                    # negative width
+    assert mk([3, 4], [{"half_width": 1, "offsets": ()}, ok[1]]) == 6      # no offsets
+    assert mk([3, 4], [{"half_width": 1, "offsets": (0, 5, 5)}, ok[1]]) == 6   # duplicate offsets
+    assert mk([3, 4], [{"half_width": 1, "offsets": (6,)}, ok[1]]) == 7    # first rows keep nothing
+    assert mk([3, 4], [{"half_width": 1, "offsets": (-6, 6)}, ok[1]]) == 0     # every row keeps a key
+    assert mk([2, 4], [ok[0], {"cols": ()}]) == 7                          # no columns
+    assert mk([2, 4], [ok[0], {"cols": (1, 1)}]) == 6                      # duplicate column
+    assert mk([2, 4], [ok[0], {"cols": (100,)}]) == 6                      # column out of range
+    assert mk([2, 4], [ok[0], {"cols": (-1,)}]) == 6
+    assert mk([0, 0], ok, svd.tensor_desc(1, 2, 100, 96)) == 2             # head dim
+    assert mk([0, 0], ok, svd.tensor_desc(1, 2, 0, 64)) == 2               # empty sequence
+    assert mk([0, 0], ok, svd.tensor_desc(1, 2, 100, 64, stride_l=68)) == 4   # row alignment
+    assert mk([0, 0], ok, svd.tensor_desc(1, 2, 100, 64, stride_l=32)) == 2
+    assert _status(svd.svd_plan_workspace_bytes, d, [2, 9], ok) == 5
+    assert svd.svd_plan_workspace_bytes(d, [2, 4], ok) > 0
+    with pytest.raises(svd.SvdError):
+        svd.svd_default_blocks(96)
+
+
+def test_host_only_plan_refuses_to_launch():
+    wl = W.tiny()
+    plan = _compile(wl, 0, 0)
+    import ctypes
+    st = svd.lib().svd_attn_forward_planned(plan.handle, ctypes.c_void_p(16), ctypes.c_void_p(16),
+                                            ctypes.c_void_p(16), ctypes.c_void_p(16), None)
+    assert st == 8
+    st = svd.lib().svd_attn_forward_planned(plan.handle, None, None, None, None, None)
+    assert st == 1
+    st = svd.lib().svd_attn_forward_planned(plan.handle, ctypes.c_void_p(8), ctypes.c_void_p(16),
+                                            ctypes.c_void_p(16), ctypes.c_void_p(16), None)
+    assert st == 4
