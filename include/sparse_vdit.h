@@ -143,11 +143,21 @@ svd_status svd_plan_column_list(const svd_plan* plan, int32_t group, int32_t lis
 svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* computed_flops,
                          double* kept_pairs);
 
+/* The same figures for one group (all its heads, all batch entries). */
+svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* computed_tiles,
+                               double* computed_flops, double* kept_pairs);
+
 /* Forward pass of one layer with a compiled plan (Section 4.2: one fused launch
  * per mode present in the table, heaviest group first, plus a zero fill for
  * skipped heads).  The tensors must match the plan's descriptor. */
 svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
                                     void* out, void* hip_stream);
+
+/* The launch of a single group of the plan (Section 4.2: the fused kernel of one
+ * mode).  Writes only the heads of that group.  For callers that place groups
+ * on different streams or time them one by one. */
+svd_status svd_attn_forward_group(const svd_plan* plan, int32_t group, const void* q, const void* k,
+                                  const void* v, void* out, void* hip_stream);
 
 /* One-shot form: compiles the table (or reuses the plan compiled by the previous
  * call with identical arguments and workspace) and launches.  workspace_bytes

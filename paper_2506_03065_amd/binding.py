@@ -24,7 +24,7 @@ SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
            "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_band_list", "svd_plan_column_list",
-           "svd_plan_work", "svd_attn_forward_planned", "sparse_vdit_attn_forward",
+           "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
            "svd_dense_attn_forward", "svd_status_string"]
 
 
@@ -72,7 +72,9 @@ def lib():
             "svd_plan_band_list": [vp, C.c_int32, C.c_int32, i32p, i32pp, i32pp, i32pp, i32pp, i32pp, i32p, i32pp],
             "svd_plan_column_list": [vp, C.c_int32, C.c_int32, i32p, i32p, i32pp],
             "svd_plan_work": [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
+            "svd_plan_group_work": [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
             "svd_attn_forward_planned": [vp, vp, vp, vp, vp, vp],
+            "svd_attn_forward_group": [vp, C.c_int32, vp, vp, vp, vp, vp],
             "sparse_vdit_attn_forward": [vp, vp, vp, i32p, hpp, vp, descp, vp, C.c_size_t, vp],
             "svd_dense_attn_forward": [vp, vp, vp, vp, descp, vp],
         }
@@ -209,9 +211,13 @@ class Plan:
                "svd_plan_column_list")
         return {"n_cols": n.value, "cols": _copy(cols, padded.value)}
 
-    def work(self):
+    def work(self, group=None):
         tiles, flops, pairs = C.c_int64(), C.c_double(), C.c_double()
-        _check(lib().svd_plan_work(self.handle, C.byref(tiles), C.byref(flops), C.byref(pairs)), "svd_plan_work")
+        if group is None:
+            _check(lib().svd_plan_work(self.handle, C.byref(tiles), C.byref(flops), C.byref(pairs)), "svd_plan_work")
+        else:
+            _check(lib().svd_plan_group_work(self.handle, group, C.byref(tiles), C.byref(flops), C.byref(pairs)),
+                   "svd_plan_group_work")
         return {"computed_tiles": tiles.value, "computed_flops": flops.value, "kept_pairs": pairs.value}
 
 
@@ -244,6 +250,12 @@ def _dev(t):
 def svd_attn_forward_planned(plan: Plan, q, k, v, out, stream=None):
     _check(lib().svd_attn_forward_planned(plan.handle, _dev(q), _dev(k), _dev(v), _dev(out), _stream_ptr(stream)),
            "svd_attn_forward_planned")
+    return out
+
+
+def svd_attn_forward_group(plan: Plan, group: int, q, k, v, out, stream=None):
+    _check(lib().svd_attn_forward_group(plan.handle, group, _dev(q), _dev(k), _dev(v), _dev(out),
+                                        _stream_ptr(stream)), "svd_attn_forward_group")
     return out
 
 

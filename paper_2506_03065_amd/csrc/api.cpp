@@ -235,81 +235,113 @@ svd_status svd_plan_column_list(const svd_plan* plan, int32_t group, int32_t lis
   return SVD_OK;
 }
 
+static void group_work(const Plan& p, const svd::Group& g, int64_t* tiles, double* area, double* pairs) {
+  const double L = p.desc.L;
+  for (size_t t = 0; t < g.heads.size(); ++t) {
+    switch (g.mode) {
+      case SVD_DENSE:
+        *tiles += static_cast<int64_t>(p.n_q_blocks) * p.n_k_blocks;
+        *area += L * L;
+        *pairs += L * L;
+        break;
+      case SVD_DIAG:
+      case SVD_MULTIDIAG: {
+        const svd::BandList& bl = g.bands[g.list_id[t]];
+        *tiles += static_cast<int64_t>(bl.kv_block_idx.size());
+        *area += bl.tile_area;
+        *pairs += bl.kept_pairs;
+        break;
+      }
+      case SVD_VSTRIPE: {
+        const svd::ColumnList& cl = g.columns[g.list_id[t]];
+        *tiles += static_cast<int64_t>(p.n_q_blocks) * static_cast<int64_t>(cl.cols.size() / p.block_k);
+        *area += L * cl.n_cols;
+        *pairs += L * cl.n_cols;
+        break;
+      }
+      default:
+        break;
+    }
+  }
+}
+
 svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* computed_flops,
                          double* kept_pairs) {
   if (!plan) return SVD_ERR_NULL;
   const Plan& p = plan->p;
-  const double L = p.desc.L;
   int64_t tiles = 0;
   double area = 0.0, pairs = 0.0;
-  for (const svd::Group& g : p.groups) {
-    for (size_t t = 0; t < g.heads.size(); ++t) {
-      switch (g.mode) {
-        case SVD_DENSE:
-          tiles += static_cast<int64_t>(p.n_q_blocks) * p.n_k_blocks;
-          area += L * L;
-          pairs += L * L;
-          break;
-        case SVD_DIAG:
-        case SVD_MULTIDIAG: {
-          const svd::BandList& bl = g.bands[g.list_id[t]];
-          tiles += static_cast<int64_t>(bl.kv_block_idx.size());
-          area += bl.tile_area;
-          pairs += bl.kept_pairs;
-          break;
-        }
-        case SVD_VSTRIPE: {
-          const svd::ColumnList& cl = g.columns[g.list_id[t]];
-          tiles += static_cast<int64_t>(p.n_q_blocks) * static_cast<int64_t>(cl.cols.size() / p.block_k);
-          area += L * cl.n_cols;
-          pairs += L * cl.n_cols;
-          break;
-        }
-        default:
-          break;
-      }
-    }
-  }
+  for (const svd::Group& g : p.groups) group_work(p, g, &tiles, &area, &pairs);
   if (computed_tiles) *computed_tiles = tiles * p.desc.B;
   if (computed_flops) *computed_flops = 4.0 * p.desc.D * area * p.desc.B;
   if (kept_pairs) *kept_pairs = pairs * p.desc.B;
   return SVD_OK;
 }
 
-svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
-                                    void* out, void* hip_stream) {
+svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* computed_tiles,
+                               double* computed_flops, double* kept_pairs) {
+  if (!plan) return SVD_ERR_NULL;
+  const Plan& p = plan->p;
+  if (group < 0 || group >= static_cast<int32_t>(p.groups.size())) return SVD_ERR_SHAPE;
+  int64_t tiles = 0;
+  double area = 0.0, pairs = 0.0;
+  group_work(p, p.groups[group], &tiles, &area, &pairs);
+  if (computed_tiles) *computed_tiles = tiles * p.desc.B;
+  if (computed_flops) *computed_flops = 4.0 * p.desc.D * area * p.desc.B;
+  if (kept_pairs) *kept_pairs = pairs * p.desc.B;
+  return SVD_OK;
+}
+
+static svd_status launch_group(const Plan& p, const svd::Group& g, const void* q, const void* k,
+                               const void* v, void* out, hipStream_t stream) {
+  const int* ws = static_cast<const int*>(p.device_workspace);
+  svd::AttnLaunch a = base_launch(p.desc, q, k, v, out);
+  a.n_q_blocks = p.n_q_blocks;
+  a.n_heads = static_cast<int>(g.heads.size());
+  a.n_items = a.n_q_blocks * a.n_heads * a.B;
+  a.heads = ws + g.ws_heads;
+  a.list_id = ws + g.ws_list_id;
+  a.ws = ws;
+  a.list_table = static_cast<int>(g.ws_list_table);
+  hipError_t err;
+  if (g.mode == SVD_SKIP) {
+    err = svd::launch_zero_heads(a, stream);
+  } else {
+    const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
+                      : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+    err = svd::launch_attention(a, kmode, stream);
+  }
+  return err == hipSuccess ? SVD_OK : SVD_ERR_HIP;
+}
+
+static svd_status check_launchable(const svd_plan* plan, const void* q, const void* k, const void* v,
+                                   const void* out) {
   if (!plan) return SVD_ERR_NULL;
   if (svd_status st = check_tensors(q, k, v, out)) return st;
+  if (!plan->p.device_workspace) return SVD_ERR_WORKSPACE;
+  if (!plan->p.launchable) return SVD_ERR_UNSUPPORTED;
+  return SVD_OK;
+}
+
+svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
+                                    void* out, void* hip_stream) {
+  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
   const Plan& p = plan->p;
-  if (!p.device_workspace) return SVD_ERR_WORKSPACE;
-  if (!p.launchable) return SVD_ERR_UNSUPPORTED;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int* ws = static_cast<const int*>(p.device_workspace);
   // heaviest first: dense, then the band groups, the gathers, and the zero fill
   static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
-  for (int mode : order) {
-    for (const svd::Group& g : p.groups) {
-      if (g.mode != mode) continue;
-      svd::AttnLaunch a = base_launch(p.desc, q, k, v, out);
-      a.n_q_blocks = p.n_q_blocks;
-      a.n_heads = static_cast<int>(g.heads.size());
-      a.n_items = a.n_q_blocks * a.n_heads * a.B;
-      a.heads = ws + g.ws_heads;
-      a.list_id = ws + g.ws_list_id;
-      a.ws = ws;
-      a.list_table = static_cast<int>(g.ws_list_table);
-      hipError_t err;
-      if (mode == SVD_SKIP) {
-        err = svd::launch_zero_heads(a, stream);
-      } else {
-        const int kmode = mode == SVD_DENSE ? svd::MODE_DENSE
-                          : mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
-        err = svd::launch_attention(a, kmode, stream);
-      }
-      if (err != hipSuccess) return SVD_ERR_HIP;
-    }
-  }
+  for (int mode : order)
+    for (const svd::Group& g : p.groups)
+      if (g.mode == mode)
+        if (svd_status st = launch_group(p, g, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
   return SVD_OK;
+}
+
+svd_status svd_attn_forward_group(const svd_plan* plan, int32_t group, const void* q, const void* k,
+                                  const void* v, void* out, void* hip_stream) {
+  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  const Plan& p = plan->p;
+  if (group < 0 || group >= static_cast<int32_t>(p.groups.size())) return SVD_ERR_SHAPE;
+  return launch_group(p, p.groups[group], q, k, v, out, static_cast<hipStream_t>(hip_stream));
 }
 
 svd_status svd_dense_attn_forward(const void* q, const void* k, const void* v, void* out,
