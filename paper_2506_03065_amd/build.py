@@ -29,6 +29,8 @@ def hipcc_path() -> str:
 def build_library(verbose: bool = True) -> str:
     cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-x", "hip",
+           # NaNs need no special care in fmax chains (infinities stay honoured: masks use -inf)
+           "-fno-honor-nans",
            # packed fp32 VALU forms are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]

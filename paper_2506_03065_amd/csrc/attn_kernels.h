@@ -13,8 +13,17 @@ enum { MODE_DENSE = 0, MODE_BAND = 1, MODE_GATHER = 2 };
 
 // Tile shapes the kernels are instantiated for.  Query tile = NW waves x QB
 // blocks of 32 rows; key tile = BC keys.
-struct Tile128 { static constexpr int NW = 4, QB = 2, BC = 64; };   // D = 128
-struct Tile64  { static constexpr int NW = 4, QB = 2, BC = 128; };  // D = 64
+// OCC = waves per SIMD the kernel is compiled for (register budget 512 / OCC).
+#ifndef SVD_T128
+#define SVD_T128 8, 1, 64, 2
+#endif
+#ifndef SVD_T64
+#define SVD_T64 8, 1, 128, 2
+#endif
+template <int NW_, int QB_, int BC_, int OCC_>
+struct TileShape { static constexpr int NW = NW_, QB = QB_, BC = BC_, OCC = OCC_; };
+using Tile128 = TileShape<SVD_T128>;   // D = 128
+using Tile64 = TileShape<SVD_T64>;     // D = 64
 
 struct AttnLaunch {
   const __bf16* q;

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "attn_kernels.h"
 
@@ -74,8 +75,8 @@ __device__ __forceinline__ int swz_v(int row) {
   return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
-template <int D, int NW, int QB, int BC, int MODE>
-__global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
+template <int D, int NW, int QB, int BC, int OCC, int MODE>
+__global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch p) {
   constexpr int NT = NW * 64;
   constexpr int QW = QB * 32;       // query rows per wave
   constexpr int BR = NW * QW;       // query rows per work-group
@@ -195,17 +196,34 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
   }
 
   const float c_scale = p.scale_log2e;
+  // The running maximum is only raised when a tile exceeds it by more than
+  // kLazyLog2 in the exponent (2^8 = 256x): until then P keeps the stale
+  // reference, which changes no result (any reference cancels in O / l) but
+  // saves the rescale of O and l on most tiles.
+  constexpr float kLazyLog2 = 8.0f;
+  const float tau = kLazyLog2 / c_scale;
 
-  if (n_tiles > 0) {
-    SVD_LOAD_TILE(0);
-    SVD_STORE_TILE(0);
+  // per-lane LDS offsets that do not depend on the tile
+  int k_off[KB2][2];   // K fragment of 32-key block kb2, chunk parity (2*ks + half) -> xor applied per ks
+#pragma unroll
+  for (int kb2 = 0; kb2 < KB2; ++kb2) {
+    const int r = kb2 * 32 + l32;
+    k_off[kb2][0] = r * (D * 2);
+    k_off[kb2][1] = swz_k<D>(r);
   }
-  __syncthreads();
+  const int ti = lane & 15;           // lane inside its block of 16
+  const int dsel = (lane >> 4) & 1;   // which 16 of the 32 d rows
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    const bool more = t + 1 < n_tiles;
-    if (more) SVD_LOAD_TILE(t + 1);
+  // One key tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.  BUF is the
+  // LDS buffer that holds the tile; t its position in the head's list.
+  // MASK: 0 = the tile is wholly kept, 1 = mask it, 2 = decided per tile (band lists).
+  auto tile = [&](auto buf_tag, auto mask_tag, const int t) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    constexpr int MASK = decltype(mask_tag)::value;
+    bool masked = MASK == 1;
+    if (MASK == 2) masked = !(entries[t].y & 1);
+    const unsigned char* kbase = sK + BUF * TILE_BYTES;
+    const unsigned char* vbase = sV + BUF * TILE_BYTES;
 
     // ---- S^T = K Q^T ----
     f32x16 s[KB2][QB];
@@ -215,14 +233,12 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[kb2][qb][i] = 0.f;
-    const unsigned char* kbase = sK + buf * TILE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2) {
-        const int r = kb2 * 32 + l32;
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + r * (D * 2) +
-                                                         (((2 * ks + half) ^ swz_k<D>(r)) << 4));
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + k_off[kb2][0] +
+                                                         (((2 * ks + half) ^ k_off[kb2][1]) << 4));
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
           s[kb2][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[kb2][qb], 0, 0, 0);
@@ -230,9 +246,9 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
     }
 
     // ---- masks: element (kb2, i) of lane is key kb2*32 + (i/4)*8 + half*4 + i%4 ----
-    if (MODE == MODE_BAND) {
-      const int2 ent = entries[t];
-      if (!(ent.y & 1)) {
+    if (masked) {
+      if (MODE == MODE_BAND) {
+        const int2 ent = entries[t];
         const int kv0 = ent.x * BC;
         const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
 #pragma unroll
@@ -260,11 +276,9 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
             s[kb2][qb] = kept;
           }
         }
-      }
-    } else {
-      // dense: keys past L in the last tile; gather: padding of the column list
-      const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
-      if (limit < BC) {
+      } else {
+        // dense: keys past L in the last tile; gather: padding of the column list
+        const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
 #pragma unroll
         for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
@@ -287,12 +301,19 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
 #pragma unroll
         for (int i = 0; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[kb2][qb][i], s[kb2][qb][i + 1]));
       mx = half_max(mx);
-      const float m_new = fmaxf(m_run[qb], mx);
-      const float m_use = m_new == kNegInf ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_use) * c_scale);
-      m_run[qb] = m_new;
-      const float mc = m_use * c_scale;
+      const bool grow = mx > m_run[qb] + tau;   // false when the lane's tile is fully masked
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        const float alpha = grow ? __builtin_amdgcn_exp2f((m_run[qb] - mx) * c_scale) : 1.0f;
+        m_run[qb] = grow ? mx : m_run[qb];
+        l_run[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+      }
+      const float mc = (m_run[qb] == kNegInf ? 0.f : m_run[qb]) * c_scale;
       float rs = 0.f;
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
@@ -302,26 +323,19 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
           for (int i = 0; i < 8; i += 2) {
             const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i], c_scale, -mc));
             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i + 1], c_scale, -mc));
-            rs += p0 + p1;
             const f32x2 pp = {p0, p1};
             const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+            rs = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs, false);   // row sum of the rounded P
             pk[i] = pb[0];
             pk[i + 1] = pb[1];
           }
           pf[kb2][sub][qb] = pk;
         }
       }
-      l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+      l_run[qb] += rs;
     }
 
     // ---- O^T += V^T P^T ----
-    const unsigned char* vbase = sV + buf * TILE_BYTES;
-    const int ti = lane & 15;           // lane inside its block of 16
-    const int dsel = (lane >> 4) & 1;   // which 16 of the 32 d rows
 #pragma unroll
     for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
@@ -345,9 +359,44 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnLaunch p) {
         }
       }
     }
+  };
 
-    if (more) SVD_STORE_TILE(buf ^ 1);
+  if (n_tiles > 0) {
+    SVD_LOAD_TILE(0);
+    SVD_STORE_TILE(0);
+  }
+  __syncthreads();
+
+  // Tile t is computed from LDS buffer t & 1 while tile t + 1 travels global ->
+  // registers -> the other buffer.  Two tiles per trip keep the buffer index a
+  // compile-time constant.  Band lists decide per entry whether to mask; the
+  // dense and gather loops can only meet a partly valid tile at the very end,
+  // which is peeled off and always masked.
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
+  using MainMask = std::integral_constant<int, MODE == MODE_BAND ? 2 : 0>;
+  using LastMask = std::integral_constant<int, 1>;
+  auto step = [&](auto buf_tag, auto mask_tag, const int t) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const bool more = t + 1 < n_tiles;
+    if (more) SVD_LOAD_TILE(t + 1);
+    tile(buf_tag, mask_tag, t);
+    if (more) SVD_STORE_TILE(BUF ^ 1);
     __syncthreads();
+  };
+  const int n_main = MODE == MODE_BAND ? n_tiles : n_tiles - 1;
+  int t = 0;
+  for (; t + 1 < n_main; t += 2) {
+    step(B0{}, MainMask{}, t);
+    step(B1{}, MainMask{}, t + 1);
+  }
+  if (t < n_main) {
+    step(B0{}, MainMask{}, t);
+    ++t;
+  }
+  if (MODE != MODE_BAND && t < n_tiles) {
+    if (t & 1) step(B1{}, LastMask{}, t);
+    else step(B0{}, LastMask{}, t);
   }
 
   // ---- epilogue: O = O^T / l, bf16, lane owns query l32: 4 consecutive d per store ----
@@ -393,19 +442,19 @@ __global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
   }
 }
 
-template <int D, int NW, int QB, int BC>
+template <int D, int NW, int QB, int BC, int OCC>
 hipError_t launch_mode(const AttnLaunch& p, int mode, hipStream_t stream) {
   const int per_xcd = (p.n_items + 7) / 8;
   const dim3 grid(per_xcd * 8), block(NW * 64);
   switch (mode) {
     case MODE_DENSE:
-      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, MODE_DENSE>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_DENSE>), grid, block, 0, stream, p);
       break;
     case MODE_BAND:
-      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, MODE_BAND>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_BAND>), grid, block, 0, stream, p);
       break;
     case MODE_GATHER:
-      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, MODE_GATHER>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_GATHER>), grid, block, 0, stream, p);
       break;
     default:
       return hipErrorInvalidValue;
@@ -427,8 +476,8 @@ void kernel_blocks(int D, int* block_q, int* block_k) {
 
 hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream) {
   if (p.n_items <= 0) return hipSuccess;
-  if (p.D == 128) return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC>(p, mode, stream);
-  if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC>(p, mode, stream);
+  if (p.D == 128) return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC, Tile128::OCC>(p, mode, stream);
+  if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC, Tile64::OCC>(p, mode, stream);
   return hipErrorInvalidValue;
 }
 
