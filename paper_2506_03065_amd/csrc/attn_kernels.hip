@@ -19,6 +19,10 @@
 // tile in LDS through the transposing LDS read (ds_read_b64_tr_b16).
 // Accumulation, scores and softmax are fp32; P is rounded to bf16 for the
 // second product.
+//
+// The loop is software-pipelined inside each wave: while the VALU turns the
+// scores of tile t into P, the matrix pipe already computes the scores of tile
+// t + 1; K therefore runs one tile ahead of V through the LDS buffers.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -65,7 +69,8 @@ __device__ __forceinline__ float half_sum(float x) {
 
 // 16-byte chunk swizzles of the LDS tiles (row = key, chunk = 8 bf16 of D).
 // K is read 16 bytes per lane with consecutive lanes on consecutive keys; V is
-// read through the transposing read, 4 keys x 64 bytes per half-wave.
+// read through the transposing read, 4 keys x 64 bytes per half-wave.  Both
+// depend only on row bits that are lane bits at the reading side.
 template <int D>
 __device__ __forceinline__ int swz_k(int row) {
   return D == 128 ? (row & 15) : ((row >> 1) & 7);
@@ -74,6 +79,9 @@ template <int D>
 __device__ __forceinline__ int swz_v(int row) {
   return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
+
+template <int N>
+using Int = std::integral_constant<int, N>;
 
 template <int D, int NW, int QB, int BC, int OCC, int MODE>
 __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch p) {
@@ -87,6 +95,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   constexpr int NCH = BC * CH / NT; // chunks per thread and tile (K and V each)
   static_assert(BC * CH % NT == 0, "tile must split evenly over the threads");
   constexpr int TILE_BYTES = BC * D * 2;
+  constexpr int ROW_BYTES = D * 2;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE_BYTES];
   unsigned char* const sK = smem;                    // [2][BC][D] bf16, swizzled
@@ -162,38 +171,34 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
       for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
   }
 
-  // ---- tile loader: global -> registers -> LDS ----
+  // ---- tile loaders: global -> registers -> LDS, K and V separately ----
   u32x4 kreg[NCH], vreg[NCH];
-#define SVD_LOAD_TILE(T)                                                                   \
-  {                                                                                        \
-    _Pragma("unroll") for (int u = 0; u < NCH; ++u) {                                      \
-      const int g_ = u * NT + tid;                                                         \
-      const int r_ = g_ / CH, c_ = g_ % CH;                                                \
-      int row_;                                                                            \
-      if (MODE == MODE_GATHER) {                                                           \
-        row_ = cols[(T) * BC + r_];                                                        \
-        row_ = row_ < 0 ? 0 : row_;                                                        \
-      } else {                                                                             \
-        const int kb_ = MODE == MODE_BAND ? entries[(T)].x : (T);                          \
-        row_ = kb_ * BC + r_;                                                              \
-        row_ = row_ < L ? row_ : L - 1;                                                    \
-      }                                                                                    \
-      const int64_t off_ = (int64_t)row_ * p.stride_l + c_ * 8;                            \
-      kreg[u] = *reinterpret_cast<const u32x4*>(K + off_);                                 \
-      vreg[u] = *reinterpret_cast<const u32x4*>(V + off_);                                 \
-    }                                                                                      \
+  int st_off_k[NCH], st_off_v[NCH], ld_row[NCH], ld_col[NCH];
+#pragma unroll
+  for (int u = 0; u < NCH; ++u) {
+    const int g = u * NT + tid;
+    const int r = g / CH, c = g % CH;
+    ld_row[u] = r;
+    ld_col[u] = c * 8;
+    st_off_k[u] = r * ROW_BYTES + ((c ^ swz_k<D>(r)) << 4);
+    st_off_v[u] = r * ROW_BYTES + ((c ^ swz_v<D>(r)) << 4);
   }
-#define SVD_STORE_TILE(BUF)                                                                \
-  {                                                                                        \
-    _Pragma("unroll") for (int u = 0; u < NCH; ++u) {                                      \
-      const int g_ = u * NT + tid;                                                         \
-      const int r_ = g_ / CH, c_ = g_ % CH;                                                \
-      *reinterpret_cast<u32x4*>(sK + (BUF) * TILE_BYTES + r_ * (D * 2) +                   \
-                                ((c_ ^ swz_k<D>(r_)) << 4)) = kreg[u];                     \
-      *reinterpret_cast<u32x4*>(sV + (BUF) * TILE_BYTES + r_ * (D * 2) +                   \
-                                ((c_ ^ swz_v<D>(r_)) << 4)) = vreg[u];                     \
-    }                                                                                      \
-  }
+  // global row of key slot r of tile t
+  auto key_row = [&](const int t, const int r) -> int {
+    if (MODE == MODE_GATHER) {
+      const int c = cols[t * BC + r];
+      return c < 0 ? 0 : c;
+    }
+    const int kb = MODE == MODE_BAND ? entries[t].x : t;
+    const int j = kb * BC + r;
+    return j < L ? j : L - 1;
+  };
+#define SVD_LOAD(REG, PTR, T)                                                             \
+  _Pragma("unroll") for (int u = 0; u < NCH; ++u)                                         \
+    REG[u] = *reinterpret_cast<const u32x4*>(PTR + (int64_t)key_row((T), ld_row[u]) * p.stride_l + ld_col[u]);
+#define SVD_STORE(REG, SBASE, OFF, BUF)                                                   \
+  _Pragma("unroll") for (int u = 0; u < NCH; ++u)                                         \
+    *reinterpret_cast<u32x4*>(SBASE + (BUF) * TILE_BYTES + OFF[u]) = REG[u];
 
   const float c_scale = p.scale_log2e;
   // The running maximum is only raised when a tile exceeds it by more than
@@ -203,30 +208,24 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   constexpr float kLazyLog2 = 8.0f;
   const float tau = kLazyLog2 / c_scale;
 
-  // per-lane LDS offsets that do not depend on the tile
-  int k_off[KB2][2];   // K fragment of 32-key block kb2, chunk parity (2*ks + half) -> xor applied per ks
+  // per-lane LDS read offsets (everything else is an immediate)
+  int k_off[KS];   // K fragment: key l32 of a 32-key block, chunk 2 * ks + half
 #pragma unroll
-  for (int kb2 = 0; kb2 < KB2; ++kb2) {
-    const int r = kb2 * 32 + l32;
-    k_off[kb2][0] = r * (D * 2);
-    k_off[kb2][1] = swz_k<D>(r);
-  }
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = l32 * ROW_BYTES + (((2 * ks + half) ^ swz_k<D>(l32)) << 4);
   const int ti = lane & 15;           // lane inside its block of 16
   const int dsel = (lane >> 4) & 1;   // which 16 of the 32 d rows
+  int v_off[DB];   // V^T fragment: key row half*4 + ti/4 of a 16-key step, 4 d from db*32 + dsel*16 + (ti%4)*4
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    const int r = half * 4 + (ti >> 2);
+    const int c = db * 4 + 2 * dsel + ((ti & 3) >> 1);
+    v_off[db] = r * ROW_BYTES + ((c ^ swz_v<D>(r)) << 4) + ((ti & 1) << 3);
+  }
 
-  // One key tile: S^T = K Q^T, mask, online softmax, O^T += V^T P^T.  BUF is the
-  // LDS buffer that holds the tile; t its position in the head's list.
-  // MASK: 0 = the tile is wholly kept, 1 = mask it, 2 = decided per tile (band lists).
-  auto tile = [&](auto buf_tag, auto mask_tag, const int t) {
+  // ---- S^T = K Q^T for the tile held in K buffer BUF ----
+  auto scores = [&](auto buf_tag, f32x16 (&s)[KB2][QB]) {
     constexpr int BUF = decltype(buf_tag)::value;
-    constexpr int MASK = decltype(mask_tag)::value;
-    bool masked = MASK == 1;
-    if (MASK == 2) masked = !(entries[t].y & 1);
     const unsigned char* kbase = sK + BUF * TILE_BYTES;
-    const unsigned char* vbase = sV + BUF * TILE_BYTES;
-
-    // ---- S^T = K Q^T ----
-    f32x16 s[KB2][QB];
 #pragma unroll
     for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
@@ -237,83 +236,98 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + k_off[kb2][0] +
-                                                         (((2 * ks + half) ^ k_off[kb2][1]) << 4));
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb2 * 32 * ROW_BYTES + k_off[ks]);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
           s[kb2][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[kb2][qb], 0, 0, 0);
       }
     }
+  };
 
-    // ---- masks: element (kb2, i) of lane is key kb2*32 + (i/4)*8 + half*4 + i%4 ----
-    if (masked) {
-      if (MODE == MODE_BAND) {
-        const int2 ent = entries[t];
-        const int kv0 = ent.x * BC;
-        const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
+  // ---- masks: element (kb2, i) of a lane is key kb2*32 + (i/4)*8 + half*4 + i%4 ----
+  auto apply_mask = [&](f32x16 (&s)[KB2][QB], const int t) {
+    if (MODE == MODE_BAND) {
+      const int2 ent = entries[t];
+      const int kv0 = ent.x * BC;
+      const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
 #pragma unroll
-        for (int kb2 = 0; kb2 < KB2; ++kb2) {
+      for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) {
-            const int iq = q0 + qb * 32 + l32;
-            const int jb = kv0 + kb2 * 32 + half * 4;   // key of element 0
-            f32x16 kept;
+        for (int qb = 0; qb < QB; ++qb) {
+          const int iq = q0 + qb * 32 + l32;
+          const int jb = kv0 + kb2 * 32 + half * 4;   // key of element 0
+          f32x16 kept;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
-            for (int r = r0; r < r0 + rn; ++r) {
-              const int2 run = runs[r];
-              // kept iff run.x <= j - iq <= run.y and j < L
-              int hi = run.y;
-              hi = hi < L - 1 - iq ? hi : L - 1 - iq;
-              const int t0 = jb - iq - run.x;
-              const int span = hi - run.x;    // may be negative: nothing kept
-#pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int d = t0 + (i / 4) * 8 + (i % 4);
-                kept[i] = (d >= 0 && d <= span) ? s[kb2][qb][i] : kept[i];
-              }
-            }
-            s[kb2][qb] = kept;
-          }
-        }
-      } else {
-        // dense: keys past L in the last tile; gather: padding of the column list
-        const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
-#pragma unroll
-        for (int kb2 = 0; kb2 < KB2; ++kb2)
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
+          for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
+          for (int r = r0; r < r0 + rn; ++r) {
+            const int2 run = runs[r];
+            // kept iff run.x <= j - iq <= run.y and j < L
+            int hi = run.y;
+            hi = hi < L - 1 - iq ? hi : L - 1 - iq;
+            const int t0 = jb - iq - run.x;
+            const int span = hi - run.x;    // may be negative: nothing kept
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              const int j = kb2 * 32 + half * 4 + (i / 4) * 8 + (i % 4);
-              s[kb2][qb][i] = j < limit ? s[kb2][qb][i] : kNegInf;
+              const int d = t0 + (i / 4) * 8 + (i % 4);
+              kept[i] = (d >= 0 && d <= span) ? s[kb2][qb][i] : kept[i];
             }
+          }
+          s[kb2][qb] = kept;
+        }
       }
-    }
-
-    // ---- online softmax (per lane: one query column) ----
-    bf16x8 pf[KB2][2][QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float mx = kNegInf;
+    } else {
+      // dense: keys past L in the last tile; gather: padding of the column list
+      const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[kb2][qb][i], s[kb2][qb][i + 1]));
-      mx = half_max(mx);
-      const bool grow = mx > m_run[qb] + tau;   // false when the lane's tile is fully masked
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int j = kb2 * 32 + half * 4 + (i / 4) * 8 + (i % 4);
+            s[kb2][qb][i] = j < limit ? s[kb2][qb][i] : kNegInf;
+          }
+    }
+  };
+
+  // ---- maximum of a tile per query column (lane), both half-waves combined ----
+  auto tile_max = [&](const f32x16 (&s)[KB2][QB], float (&mx)[QB]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float m = kNegInf;
+#pragma unroll
+      for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) m = fmaxf(m, fmaxf(s[kb2][qb][i], s[kb2][qb][i + 1]));
+      mx[qb] = half_max(m);
+    }
+  };
+
+  // ---- lazy update of the reference maximum; rescales O and l when it moves ----
+  float mc[QB];   // reference maximum times the scale, per 32-row block
+  auto raise_max = [&](const float (&mx)[QB]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const bool grow = mx[qb] > m_run[qb] + tau;   // false when the lane's tile is fully masked
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-        const float alpha = grow ? __builtin_amdgcn_exp2f((m_run[qb] - mx) * c_scale) : 1.0f;
-        m_run[qb] = grow ? mx : m_run[qb];
+        const float alpha = grow ? __builtin_amdgcn_exp2f((m_run[qb] - mx[qb]) * c_scale) : 1.0f;
+        m_run[qb] = grow ? mx[qb] : m_run[qb];
         l_run[qb] *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+        mc[qb] = (m_run[qb] == kNegInf ? 0.f : m_run[qb]) * c_scale;
       }
-      const float mc = (m_run[qb] == kNegInf ? 0.f : m_run[qb]) * c_scale;
+    }
+  };
+
+  // ---- P = exp2(S * c - m * c), rounded to bf16 in the B-operand layout; row sums ----
+  auto exponentiate = [&](const f32x16 (&s)[KB2][QB], bf16x8 (&pf)[KB2][2][QB]) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
       float rs = 0.f;
-      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
@@ -321,8 +335,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
           bf16x8 pk;
 #pragma unroll
           for (int i = 0; i < 8; i += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i], c_scale, -mc));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i + 1], c_scale, -mc));
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i], c_scale, -mc[qb]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i + 1], c_scale, -mc[qb]));
             const f32x2 pp = {p0, p1};
             const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
             rs = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs, false);   // row sum of the rounded P
@@ -333,24 +347,26 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         }
       }
       l_run[qb] += rs;
+      // pins the row-sum chain to this block (the compiler would sink it past the
+      // MFMAs it is meant to hide behind)
+      asm volatile("" : "+v"(l_run[qb]));
     }
+  };
 
-    // ---- O^T += V^T P^T ----
+  // ---- O^T += V^T P^T for the tile held in V buffer BUF ----
+  auto accumulate = [&](auto buf_tag, const bf16x8 (&pf)[KB2][2][QB]) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const unsigned char* vbase = sV + BUF * TILE_BYTES;
 #pragma unroll
     for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          // lane supplies the address of (key row, 4 d) and receives 4 keys of one d
-          const int c = db * 4 + 2 * dsel + ((ti & 3) >> 1);
-          const int hb8 = (ti & 1) << 3;
-          const int ra = kb2 * 32 + sub * 16 + half * 4 + (ti >> 2);
-          const int rb = ra + 8;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4*)(vbase + ra * (D * 2) + ((c ^ swz_v<D>(ra)) << 4) + hb8));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4*)(vbase + rb * (D * 2) + ((c ^ swz_v<D>(rb)) << 4) + hb8));
+          // a lane supplies the address of (key row, 4 d) and receives 4 keys of one d
+          const unsigned char* src = vbase + (kb2 * 32 + sub * 16) * ROW_BYTES + v_off[db];
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * ROW_BYTES));
           const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           const bf16x8 a = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
@@ -361,42 +377,240 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     }
   };
 
+  // ---- the steady-state block of the pipeline, in explicit issue order ----
+  // Matrix pipe: S_next = K(t+1) Q^T (NQ slots of one K fragment each), then
+  // O += P V(t) (NP slots of one V^T fragment each).  Vector pipe, in the
+  // shadow of the MFMAs: P = exp2(S_cur c - m c) pair by pair in the order the
+  // second product consumes it, the row sums, and the maximum of S_next.
+  // LDS fragments are requested PF slots ahead of their use.
+  auto fused = [&](auto par_tag, const f32x16 (&s_cur)[KB2][QB], f32x16 (&s_next)[KB2][QB],
+                   float (&mx_out)[QB]) {
+    constexpr int PAR = decltype(par_tag)::value;
+    const unsigned char* kbase = sK + (PAR ^ 1) * TILE_BYTES;   // K(t+1)
+    const unsigned char* vbase = sV + PAR * TILE_BYTES;         // V(t)
+    constexpr int NQ = KS * KB2, NP = KB2 * 2 * DB, PF = 4;
+    constexpr int PAIRS = KB2 * 2 * 4 * QB;                 // pairs of P elements per lane
+    constexpr int PQ = QB;                                  // pairs per QK slot
+    constexpr int IN_QK = NQ * PQ < PAIRS ? NQ * PQ : PAIRS;
+    constexpr int PP = (PAIRS - IN_QK + NP / 2 - 1) / (NP / 2);   // pairs per early PV slot
+    constexpr int NMAX = KB2 * QB * 8;                      // max3 steps for S_next
+    constexpr int MP = (NMAX + NP / 2 - 1) / (NP / 2);      // per late PV slot
+    static_assert(IN_QK >= 4 * QB + PQ, "the first P group must be packed before the second product starts");
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    bf16x8 kfr[NQ], vfr[NP];
+    bf16x8 pf[KB2][2][QB];
+    float rs[QB], mxa[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      rs[qb] = 0.f;
+      mxa[qb] = kNegInf;
+    }
+    auto read_k = [&](const int slot) {
+      const int ks = slot / KB2, kb2 = slot % KB2;
+#ifdef SVD_PROBE_NOLDS
+      kfr[slot] = qf[0][ks];
+#else
+      kfr[slot] = *reinterpret_cast<const bf16x8*>(kbase + kb2 * 32 * ROW_BYTES + k_off[ks]);
+#endif
+    };
+    auto read_v = [&](const int slot) {
+      const int kb2 = slot / (2 * DB), sub = (slot / DB) % 2, db = slot % DB;
+#ifdef SVD_PROBE_NOLDS
+      vfr[slot] = qf[0][(kb2 + sub + db) % KS];
+#else
+      const unsigned char* src = vbase + (kb2 * 32 + sub * 16) * ROW_BYTES + v_off[db];
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * ROW_BYTES));
+      const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      vfr[slot] = __builtin_bit_cast(bf16x8, both);
+#endif
+    };
+    // pair n (in consumption order): group g = n / (4 QB) = kb2 * 2 + sub, then qb, then i.
+    // Two steps a slot apart, so that the conversion never waits for the exp unit.
+    float e0[PAIRS], e1[PAIRS];
+    auto expo = [&](const int n) {
+      const int g = n / (4 * QB), kb2 = g / 2, sub = g % 2, qb = (n / 4) % QB, i = (n % 4) * 2;
+#ifdef SVD_PROBE_NOVALU
+      e0[n] = s_cur[kb2][qb][sub * 8 + i];
+      e1[n] = s_cur[kb2][qb][sub * 8 + i + 1];
+#else
+      e0[n] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb2][qb][sub * 8 + i], c_scale, -mc[qb]));
+      e1[n] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb2][qb][sub * 8 + i + 1], c_scale, -mc[qb]));
+#endif
+    };
+    auto pack = [&](const int n) {
+      const int g = n / (4 * QB), kb2 = g / 2, sub = g % 2, qb = (n / 4) % QB, i = (n % 4) * 2;
+#ifdef SVD_PROBE_NOVALU
+      const unsigned raw = __builtin_bit_cast(unsigned, e0[n]) ^ __builtin_bit_cast(unsigned, e1[n]);
+      const bf16x2 pb = __builtin_bit_cast(bf16x2, raw);
+#else
+      const f32x2 pp = {e0[n], e1[n]};
+      const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+      rs[qb] = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs[qb], false);   // row sum of the rounded P
+#endif
+      pf[kb2][sub][qb][i] = pb[0];
+      pf[kb2][sub][qb][i + 1] = pb[1];
+    };
+    // pairs exponentiated before slot k (QK slots 0..NQ-1, then PV slots)
+    auto cursor = [&](const int k) -> int {
+      if (k <= 0) return 0;
+      if (k <= NQ) return k * PQ < IN_QK ? k * PQ : IN_QK;
+      const int c = IN_QK + (k - NQ) * PP;
+      return c < PAIRS ? c : PAIRS;
+    };
+    auto softmax_steps = [&](const int k) {
+#pragma unroll
+      for (int n = cursor(k - 1); n < cursor(k); ++n) pack(n);      // what the previous slot exponentiated
+#pragma unroll
+      for (int n = cursor(k); n < cursor(k + 1); ++n) expo(n);
+    };
+    // max step n of S_next: elements 2n, 2n+1 of (kb2, qb)
+    auto do_max = [&](const int n) {
+      const int kb2 = n / (8 * QB), qb = (n / 8) % QB, i = (n % 8) * 2;
+#ifndef SVD_PROBE_NOVALU
+      mxa[qb] = fmaxf(mxa[qb], fmaxf(s_next[kb2][qb][i], s_next[kb2][qb][i + 1]));
+#else
+      if (n == 0) mxa[qb] = s_next[kb2][qb][i];
+#endif
+    };
+
+    // The row-sum and maximum chains feed nothing inside the block, so the
+    // compiler would sink them below the MFMAs they are meant to hide behind; an
+    // empty volatile asm per slot keeps each step in its slot.
+    auto anchor = [&]() {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+v"(rs[qb]), "+v"(mxa[qb]));
+    };
+
+#pragma unroll
+    for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_next[kb2][qb][i] = 0.f;
+#pragma unroll
+    for (int f = 0; f < PF; ++f) read_k(f);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int slot = 0; slot < NQ; ++slot) {
+      const int ks = slot / KB2, kb2 = slot % KB2;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        s_next[kb2][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[slot], qf[qb][ks], s_next[kb2][qb], 0, 0, 0);
+      if (slot + PF < NQ) read_k(slot + PF);
+      else read_v(slot + PF - NQ);
+      softmax_steps(slot);
+      anchor();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int slot = 0; slot < NP; ++slot) {
+      const int kb2 = slot / (2 * DB), sub = (slot / DB) % 2, db = slot % DB;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[slot], pf[kb2][sub][qb], o[db][qb], 0, 0, 0);
+      if (slot + PF < NP) read_v(slot + PF);
+      softmax_steps(NQ + slot);
+      if (slot >= NP / 2) {
+#pragma unroll
+        for (int n = (slot - NP / 2) * MP; n < (slot - NP / 2 + 1) * MP && n < NMAX; ++n) do_max(n);
+      }
+      anchor();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      l_run[qb] += rs[qb];
+      mx_out[qb] = half_max(mxa[qb]);
+    }
+  };
+
+  // does tile t need element masks?  band lists say so per entry; the dense and
+  // gather loops can only meet a partly valid tile at the very end
+  const bool tail_ragged = MODE == MODE_DENSE ? (L % BC != 0) : (n_cols % BC != 0);
+  auto needs_mask = [&](const int t) -> bool {
+    if (MODE == MODE_BAND) return !(entries[t].y & 1);
+    return tail_ragged && t == n_tiles - 1;
+  };
+
+  // ---- prologue: K(0), V(0), K(1) into LDS, scores of tile 0 ----
+  f32x16 s_a[KB2][QB], s_b[KB2][QB];
+  float mx[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) mc[qb] = 0.f;
   if (n_tiles > 0) {
-    SVD_LOAD_TILE(0);
-    SVD_STORE_TILE(0);
+    SVD_LOAD(kreg, K, 0);
+    SVD_LOAD(vreg, V, 0);
+    SVD_STORE(kreg, sK, st_off_k, 0);
+    SVD_STORE(vreg, sV, st_off_v, 0);
+    if (n_tiles > 1) {
+      SVD_LOAD(kreg, K, 1);
+      SVD_STORE(kreg, sK, st_off_k, 1);
+    }
   }
   __syncthreads();
+  if (n_tiles > 0) {
+    scores(Int<0>{}, s_a);
+    if (needs_mask(0)) apply_mask(s_a, 0);
+    tile_max(s_a, mx);
+    raise_max(mx);
+  }
 
-  // Tile t is computed from LDS buffer t & 1 while tile t + 1 travels global ->
-  // registers -> the other buffer.  Two tiles per trip keep the buffer index a
-  // compile-time constant.  Band lists decide per entry whether to mask; the
-  // dense and gather loops can only meet a partly valid tile at the very end,
-  // which is peeled off and always masked.
-  using B0 = std::integral_constant<int, 0>;
-  using B1 = std::integral_constant<int, 1>;
-  using MainMask = std::integral_constant<int, MODE == MODE_BAND ? 2 : 0>;
-  using LastMask = std::integral_constant<int, 1>;
-  auto step = [&](auto buf_tag, auto mask_tag, const int t) {
-    constexpr int BUF = decltype(buf_tag)::value;
-    const bool more = t + 1 < n_tiles;
-    if (more) SVD_LOAD_TILE(t + 1);
-    tile(buf_tag, mask_tag, t);
-    if (more) SVD_STORE_TILE(BUF ^ 1);
+  // One pipeline stage.  On entry s_cur holds the masked scores of tile t and the
+  // reference maximum already covers them; LDS holds K(t+1) in K buffer (t+1)&1
+  // and V(t) in V buffer t&1.  NEXT: 1 = a tile t + 1 is known to exist, 0 =
+  // tile t is the last one.  With NEXT the two products and the softmax
+  // arithmetic sit in one basic block: the matrix pipe computes the scores of
+  // tile t + 1 and then O += P V of tile t, while the vector pipe turns the
+  // scores of tile t into P and then takes the maximum of the new scores.
+  auto stage = [&](auto par_tag, auto next_tag, const int t, f32x16 (&s_cur)[KB2][QB],
+                   f32x16 (&s_next)[KB2][QB]) {
+    constexpr int PAR = decltype(par_tag)::value;     // t & 1
+    constexpr bool has1 = decltype(next_tag)::value != 0;
+#ifdef SVD_PROBE_NOLOAD
+    const bool has2 = false;
+#else
+    const bool has2 = t + 2 < n_tiles;
+#endif
+    if (has2) SVD_LOAD(kreg, K, t + 2);
+#ifndef SVD_PROBE_NOLOAD
+    if (has1) SVD_LOAD(vreg, V, t + 1);
+#endif
+    if (has1) {
+      fused(par_tag, s_cur, s_next, mx);   // mx: of the unmasked scores, redone below if tile t+1 needs masks
+    } else {
+      bf16x8 pf[KB2][2][QB];
+      exponentiate(s_cur, pf);
+      accumulate(Int<PAR>{}, pf);
+    }
+    if (has2) SVD_STORE(kreg, sK, st_off_k, PAR);
+#ifndef SVD_PROBE_NOLOAD
+    if (has1) SVD_STORE(vreg, sV, st_off_v, PAR ^ 1);
+#endif
+#ifndef SVD_PROBE_NOBAR
     __syncthreads();
+#endif
+    if (has1) {
+      if (needs_mask(t + 1)) {
+        asm volatile("" ::: "memory");   // keeps this a branch (the selects must not run on full tiles)
+        apply_mask(s_next, t + 1);
+        tile_max(s_next, mx);
+      }
+      raise_max(mx);
+    }
   };
-  const int n_main = MODE == MODE_BAND ? n_tiles : n_tiles - 1;
+
+  // Two stages per trip keep buffer indices and the score registers static.
   int t = 0;
-  for (; t + 1 < n_main; t += 2) {
-    step(B0{}, MainMask{}, t);
-    step(B1{}, MainMask{}, t + 1);
+  for (; t + 2 < n_tiles; t += 2) {
+    stage(Int<0>{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<1>{}, t + 1, s_b, s_a);
   }
-  if (t < n_main) {
-    step(B0{}, MainMask{}, t);
-    ++t;
-  }
-  if (MODE != MODE_BAND && t < n_tiles) {
-    if (t & 1) step(B1{}, LastMask{}, t);
-    else step(B0{}, LastMask{}, t);
+  if (t + 1 < n_tiles) {
+    stage(Int<0>{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<0>{}, t + 1, s_b, s_a);
+  } else if (t < n_tiles) {
+    stage(Int<0>{}, Int<0>{}, t, s_a, s_b);
   }
 
   // ---- epilogue: O = O^T / l, bf16, lane owns query l32: 4 consecutive d per store ----
@@ -423,8 +637,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   }
 }
 
-#undef SVD_LOAD_TILE
-#undef SVD_STORE_TILE
+#undef SVD_LOAD
+#undef SVD_STORE
 
 // M_1 (Section 4.2): the output of a skipped head is zero.
 __global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
@@ -476,7 +690,8 @@ void kernel_blocks(int D, int* block_q, int* block_k) {
 
 hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream) {
   if (p.n_items <= 0) return hipSuccess;
-  if (p.D == 128) return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC, Tile128::OCC>(p, mode, stream);
+  if (p.D == 128)
+    return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC, Tile128::OCC>(p, mode, stream);
   if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC, Tile64::OCC>(p, mode, stream);
   return hipErrorInvalidValue;
 }
