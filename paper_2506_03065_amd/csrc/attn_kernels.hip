@@ -222,289 +222,153 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     v_off[db] = r * ROW_BYTES + ((c ^ swz_v<D>(r)) << 4) + ((ti & 1) << 3);
   }
 
-  // The pipeline unit is a block of 32 keys (one 32x32 score block per 32 query
-  // rows); a key tile of BC keys in LDS holds KB2 of them.  Score registers of
-  // one block: s[qb], element i of a lane is key (i/4)*8 + half*4 + i%4.
-
-  // ---- S^T = K Q^T of block kb2 of the tile in K buffer buf (prologue only) ----
-  auto scores = [&](const int buf, const int kb2, f32x16 (&s)[QB]) {
-    const unsigned char* kbase = sK + buf * TILE_BYTES + kb2 * 32 * ROW_BYTES;
+  // ---- S^T = K Q^T for the tile held in K buffer BUF ----
+  auto scores = [&](auto buf_tag, f32x16 (&s)[KB2][QB]) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const unsigned char* kbase = sK + BUF * TILE_BYTES;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[qb][i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + k_off[ks]);
+    for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
-        s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[qb], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[kb2][qb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int kb2 = 0; kb2 < KB2; ++kb2) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb2 * 32 * ROW_BYTES + k_off[ks]);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          s[kb2][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], s[kb2][qb], 0, 0, 0);
+      }
     }
   };
 
-  // ---- element masks of block kb2 of tile t ----
-  auto apply_mask = [&](f32x16 (&s)[QB], const int t, const int kb2) {
+  // ---- masks: element (kb2, i) of a lane is key kb2*32 + (i/4)*8 + half*4 + i%4 ----
+  auto apply_mask = [&](f32x16 (&s)[KB2][QB], const int t) {
     if (MODE == MODE_BAND) {
       const int2 ent = entries[t];
       const int kv0 = ent.x * BC;
       const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int iq = q0 + qb * 32 + l32;
-        const int jb = kv0 + kb2 * 32 + half * 4;   // key of element 0
-        f32x16 kept;
+      for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
-        for (int r = r0; r < r0 + rn; ++r) {
-          const int2 run = runs[r];
-          // kept iff run.x <= j - iq <= run.y and j < L
-          int hi = run.y;
-          hi = hi < L - 1 - iq ? hi : L - 1 - iq;
-          const int t0 = jb - iq - run.x;
-          const int span = hi - run.x;    // may be negative: nothing kept
+        for (int qb = 0; qb < QB; ++qb) {
+          const int iq = q0 + qb * 32 + l32;
+          const int jb = kv0 + kb2 * 32 + half * 4;   // key of element 0
+          f32x16 kept;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int d = t0 + (i / 4) * 8 + (i % 4);
-            kept[i] = (d >= 0 && d <= span) ? s[qb][i] : kept[i];
+          for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
+          for (int r = r0; r < r0 + rn; ++r) {
+            const int2 run = runs[r];
+            // kept iff run.x <= j - iq <= run.y and j < L
+            int hi = run.y;
+            hi = hi < L - 1 - iq ? hi : L - 1 - iq;
+            const int t0 = jb - iq - run.x;
+            const int span = hi - run.x;    // may be negative: nothing kept
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int d = t0 + (i / 4) * 8 + (i % 4);
+              kept[i] = (d >= 0 && d <= span) ? s[kb2][qb][i] : kept[i];
+            }
           }
+          s[kb2][qb] = kept;
         }
-        s[qb] = kept;
       }
     } else {
       // dense: keys past L in the last tile; gather: padding of the column list
-      const int limit = (MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC) - kb2 * 32 - half * 4;
+      const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
+      for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[qb][i] = (i / 4) * 8 + (i % 4) < limit ? s[qb][i] : kNegInf;
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int j = kb2 * 32 + half * 4 + (i / 4) * 8 + (i % 4);
+            s[kb2][qb][i] = j < limit ? s[kb2][qb][i] : kNegInf;
+          }
     }
   };
 
-  // ---- maximum of a block per query column (lane), both half-waves combined ----
-  auto block_max = [&](const f32x16 (&s)[QB], float (&mx)[QB]) {
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float m = kNegInf;
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) m = fmaxf(m, fmaxf(s[qb][i], s[qb][i + 1]));
-      mx[qb] = half_max(m);
-    }
-  };
-
-  // ---- lazy update of the reference maximum; rescales O and l when it moves ----
+  // ---- running maximum of the tile (per lane: one query column), lazy rescale ----
   float mc[QB];   // reference maximum times the scale, per 32-row block
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) mc[qb] = 0.f;
-  auto raise_max = [&](const float (&mx)[QB]) {
+  auto update_max = [&](const f32x16 (&s)[KB2][QB]) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const bool grow = mx[qb] > m_run[qb] + tau;   // false when the lane's block is fully masked
+      float mx = kNegInf;
+#pragma unroll
+      for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[kb2][qb][i], s[kb2][qb][i + 1]));
+      mx = half_max(mx);
+      const bool grow = mx > m_run[qb] + tau;   // false when the lane's tile is fully masked
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-        const float alpha = grow ? __builtin_amdgcn_exp2f((m_run[qb] - mx[qb]) * c_scale) : 1.0f;
-        m_run[qb] = grow ? mx[qb] : m_run[qb];
+        const float alpha = grow ? __builtin_amdgcn_exp2f((m_run[qb] - mx) * c_scale) : 1.0f;
+        m_run[qb] = grow ? mx : m_run[qb];
         l_run[qb] *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
-        mc[qb] = (m_run[qb] == kNegInf ? 0.f : m_run[qb]) * c_scale;
       }
+      mc[qb] = (m_run[qb] == kNegInf ? 0.f : m_run[qb]) * c_scale;
     }
   };
 
-  // ---- one block without a successor: P = exp2(S c - m c), O^T += V^T P^T ----
-  auto finish_block = [&](const int vbuf, const int kb2, const f32x16 (&s)[QB]) {
-    const unsigned char* vbase = sV + vbuf * TILE_BYTES + kb2 * 32 * ROW_BYTES;
-    bf16x8 pf[2][QB];
+  // ---- P = exp2(S * c - m * c), rounded to bf16 in the B-operand layout; row sums ----
+  auto exponentiate = [&](const f32x16 (&s)[KB2][QB], bf16x8 (&pf)[KB2][2][QB]) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       float rs = 0.f;
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
+      for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-          const f32x2 pp = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][sub * 8 + i], c_scale, -mc[qb])),
-                            __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][sub * 8 + i + 1], c_scale, -mc[qb]))};
-          const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-          rs += pp[0] + pp[1];
-          pf[sub][qb][i] = pb[0];
-          pf[sub][qb][i + 1] = pb[1];
+        for (int sub = 0; sub < 2; ++sub) {
+          bf16x8 pk;
+#pragma unroll
+          for (int i = 0; i < 8; i += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i], c_scale, -mc[qb]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i + 1], c_scale, -mc[qb]));
+            const f32x2 pp = {p0, p1};
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+            rs = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs, false);   // row sum of the rounded P
+            pk[i] = pb[0];
+            pk[i + 1] = pb[1];
+          }
+          pf[kb2][sub][qb] = pk;
         }
+      }
       l_run[qb] += rs;
     }
+  };
+
+  // ---- O^T += V^T P^T for the tile held in V buffer BUF ----
+  auto accumulate = [&](auto buf_tag, const bf16x8 (&pf)[KB2][2][QB]) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const unsigned char* vbase = sV + BUF * TILE_BYTES;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const unsigned char* src = vbase + sub * 16 * ROW_BYTES + v_off[db];
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * ROW_BYTES));
-        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+      for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[sub][qb], o[db][qb], 0, 0, 0);
+        for (int db = 0; db < DB; ++db) {
+          // a lane supplies the address of (key row, 4 d) and receives 4 keys of one d
+          const unsigned char* src = vbase + (kb2 * 32 + sub * 16) * ROW_BYTES + v_off[db];
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * ROW_BYTES));
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb2][sub][qb], o[db][qb], 0, 0, 0);
+        }
       }
-  };
-
-  // ---- the steady-state step of the pipeline, in explicit issue order ----
-  // Matrix pipe: S_next = K Q^T of the next block (KS slots of one K fragment
-  // and QB MFMAs each), then O += P V of the current block (2 DB slots of one
-  // V^T fragment and QB MFMAs each).  Vector pipe, in the shadow of the MFMAs:
-  // P = exp2(S_cur c - m c) pair by pair in the order the second product
-  // consumes it (the bf16 packing one slot after the exponentials, so that it
-  // never waits for the exp unit), the row sums, and the maximum of S_next.
-  // LDS fragments are requested PF slots ahead of their use.
-  //   kn_buf/kn_blk: K buffer and block of the next block; v_buf/v_blk: V of the current one.
-  auto fused = [&](auto kn_buf_tag, auto kn_blk_tag, auto v_buf_tag, auto v_blk_tag,
-                   const f32x16 (&s_cur)[QB], f32x16 (&s_next)[QB], float (&mx_out)[QB]) {
-    const unsigned char* kbase =
-        sK + decltype(kn_buf_tag)::value * TILE_BYTES + decltype(kn_blk_tag)::value * 32 * ROW_BYTES;
-    const unsigned char* vbase =
-        sV + decltype(v_buf_tag)::value * TILE_BYTES + decltype(v_blk_tag)::value * 32 * ROW_BYTES;
-    constexpr int NQ = KS, NP = 2 * DB;
-    constexpr int PFK = NQ < 4 ? NQ : 4, PFV = NP < 4 ? NP : 4;
-    constexpr int PAIRS = 2 * 4 * QB;                       // pairs of P elements per lane
-    constexpr int PQ = (PAIRS + NQ - 1) / NQ;               // pairs exponentiated per QK slot
-    constexpr int NMAX = 8 * QB;                            // max steps for S_next
-    constexpr int MP = (NMAX + NP - 1) / NP;                // per PV slot
-    constexpr int SP = (PAIRS + NP - 1) / NP;               // row-sum steps per PV slot
-    static_assert(NQ * PQ >= PAIRS, "all of P is exponentiated under the first product");
-    bf16x8 kfr[NQ], vfr[NP];
-    bf16x8 pf[2][QB];
-    float e0[PAIRS], e1[PAIRS];
-    float rs[QB], mxa[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      rs[qb] = 0.f;
-      mxa[qb] = kNegInf;
-    }
-    auto read_k = [&](const int slot) {
-#ifdef SVD_PROBE_NOLDS
-      kfr[slot] = qf[0][slot];
-#else
-      kfr[slot] = *reinterpret_cast<const bf16x8*>(kbase + k_off[slot]);
-#endif
-    };
-    auto read_v = [&](const int slot) {
-      const int sub = slot / DB, db = slot % DB;
-#ifdef SVD_PROBE_NOLDS
-      vfr[slot] = qf[0][(sub + db) % KS];
-#else
-      const unsigned char* src = vbase + sub * 16 * ROW_BYTES + v_off[db];
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + 8 * ROW_BYTES));
-      const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      vfr[slot] = __builtin_bit_cast(bf16x8, both);
-#endif
-    };
-    // pair n in consumption order: sub = n / (4 QB), then qb, then i
-    auto expo = [&](const int n) {
-      const int sub = n / (4 * QB), qb = (n / 4) % QB, i = (n % 4) * 2;
-#ifdef SVD_PROBE_NOVALU
-      e0[n] = s_cur[qb][sub * 8 + i];
-      e1[n] = s_cur[qb][sub * 8 + i + 1];
-#else
-      e0[n] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][sub * 8 + i], c_scale, -mc[qb]));
-      e1[n] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[qb][sub * 8 + i + 1], c_scale, -mc[qb]));
-#endif
-    };
-    auto pack = [&](const int n) {
-      const int sub = n / (4 * QB), qb = (n / 4) % QB, i = (n % 4) * 2;
-#ifdef SVD_PROBE_NOVALU
-      const unsigned raw = __builtin_bit_cast(unsigned, e0[n]) ^ __builtin_bit_cast(unsigned, e1[n]);
-      const bf16x2 pb = __builtin_bit_cast(bf16x2, raw);
-#else
-      const f32x2 pp = {e0[n], e1[n]};
-      const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-#endif
-      pf[sub][qb][i] = pb[0];
-      pf[sub][qb][i + 1] = pb[1];
-    };
-    // row sums with plain adds, under the second product (the dot instructions
-    // run on the matrix pipe and would serialise with the MFMAs)
-    auto sum_pair = [&](const int n) {
-      const int qb = (n / 4) % QB;
-#ifndef SVD_PROBE_NOVALU
-      rs[qb] += e0[n] + e1[n];
-#endif
-    };
-    auto do_max = [&](const int n) {   // elements 2n, 2n+1 of S_next[qb]
-      const int qb = n / 8, i = (n % 8) * 2;
-#ifndef SVD_PROBE_NOVALU
-      mxa[qb] = fmaxf(mxa[qb], fmaxf(s_next[qb][i], s_next[qb][i + 1]));
-#else
-      if (n % 8 == 0) mxa[qb] = s_next[qb][i];
-#endif
-    };
-    auto pairs_before = [&](const int k) -> int {   // pairs exponentiated before slot k
-      if (k <= 0) return 0;
-      return k * PQ < PAIRS ? k * PQ : PAIRS;
-    };
-    // The row-sum and maximum chains feed nothing inside the block, so the
-    // compiler would sink them below the MFMAs they are meant to hide behind; an
-    // empty volatile asm per slot keeps each step in its slot.
-    auto anchor = [&]() {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+v"(rs[qb]), "+v"(mxa[qb]));
-    };
-
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_next[qb][i] = 0.f;
-#pragma unroll
-    for (int f = 0; f < PFK; ++f) read_k(f);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int slot = 0; slot < NQ; ++slot) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-        s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[slot], qf[qb][slot], s_next[qb], 0, 0, 0);
-      if (slot + PFK < NQ) read_k(slot + PFK);
-      else if (slot + PFK - NQ < PFV) read_v(slot + PFK - NQ);
-#pragma unroll
-      for (int n = pairs_before(slot - 1); n < pairs_before(slot); ++n) pack(n);
-#pragma unroll
-      for (int n = pairs_before(slot); n < pairs_before(slot + 1); ++n) expo(n);
-      anchor();
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int n = pairs_before(NQ - 1); n < PAIRS; ++n) pack(n);
-#pragma unroll
-    for (int slot = 0; slot < NP; ++slot) {
-      const int sub = slot / DB, db = slot % DB;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-        o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[slot], pf[sub][qb], o[db][qb], 0, 0, 0);
-      if (slot + PFV < NP) read_v(slot + PFV);
-#pragma unroll
-      for (int n = slot * MP; n < (slot + 1) * MP && n < NMAX; ++n) do_max(n);
-#pragma unroll
-      for (int n = slot * SP; n < (slot + 1) * SP && n < PAIRS; ++n) sum_pair(n);
-      anchor();
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      l_run[qb] += rs[qb];
-      mx_out[qb] = half_max(mxa[qb]);
     }
   };
 
-  // does tile t need element masks?  band lists say so per entry; the dense and
-  // gather loops can only meet a partly valid tile at the very end
-  const bool tail_ragged = MODE == MODE_DENSE ? (L % BC != 0) : (n_cols % BC != 0);
-  auto needs_mask = [&](const int t) -> bool {
-    if (MODE == MODE_BAND) return !(entries[t].y & 1);
-    return tail_ragged && t == n_tiles - 1;
-  };
-
-  // ---- prologue: K(0), V(0), K(1) into LDS, scores of block 0 ----
-  static_assert(KB2 % 2 == 0, "an even number of 32-key blocks per tile keeps the score registers static");
-  f32x16 s_a[QB], s_b[QB];
-  float mx[QB];
+  // ---- prologue: K(0), V(0), K(1) into LDS, scores of tile 0 ----
+  f32x16 s_a[KB2][QB], s_b[KB2][QB];
   if (n_tiles > 0) {
     SVD_LOAD(kreg, K, 0);
     SVD_LOAD(vreg, V, 0);
@@ -516,81 +380,75 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     }
   }
   __syncthreads();
-  if (n_tiles > 0) {
-    scores(0, 0, s_a);
-    if (needs_mask(0)) apply_mask(s_a, 0, 0);
-    block_max(s_a, mx);
-    raise_max(mx);
-  }
+  if (n_tiles > 0) scores(Int<0>{}, s_a);
 
-  // After the fused step of block (t, kb2): mask and reference maximum of the
-  // block whose scores it produced.
-  auto settle = [&](f32x16 (&s_next)[QB], const int t_next, const int kb2_next) {
-#ifdef SVD_PROBE_NOSETTLE
-    return;
-#endif
-    if (needs_mask(t_next)) {
-      asm volatile("" ::: "memory");   // keeps this a branch (the selects must not run on full tiles)
-      apply_mask(s_next, t_next, kb2_next);
-      block_max(s_next, mx);
-    }
-    raise_max(mx);
-  };
-
-  // One key tile: KB2 pipeline steps.  On entry s_a holds the settled scores of
-  // block 0 of tile t; LDS holds K(t), V(t) in buffers t & 1 and K(t+1) in K
-  // buffer (t+1) & 1.  K(t+2) and V(t+1) travel global -> registers -> LDS
-  // meanwhile.  LAST: tile t is the last one (its last block has no successor).
-  auto tile_steps = [&](auto par_tag, auto last_tag, const int t) {
+  // One pipeline stage.  On entry s_cur holds the raw scores of tile t; LDS holds
+  // K(t+1) in K buffer (t+1)&1 and V(t) in V buffer t&1, while K(t+2) and V(t+1)
+  // travel global -> registers -> LDS.  MASK: 0 = tile t is wholly kept, 1 =
+  // mask it, 2 = decided per tile (band lists).  NEXT: 1 = a tile t + 1 is known
+  // to exist, 0 = tile t is the last one.  With NEXT the two products and the
+  // exponentials sit in one basic block: the matrix pipe computes the scores of
+  // tile t + 1 and then O += P V of tile t while the vector pipe turns the
+  // scores of tile t into P.
+  auto stage = [&](auto par_tag, auto mask_tag, auto next_tag, const int t, f32x16 (&s_cur)[KB2][QB],
+                   f32x16 (&s_next)[KB2][QB]) {
     constexpr int PAR = decltype(par_tag)::value;     // t & 1
-    constexpr bool LAST = decltype(last_tag)::value != 0;
-#ifdef SVD_PROBE_NOLOAD
-    const bool has2 = false, has1 = false;
-#else
-    const bool has2 = t + 2 < n_tiles, has1 = !LAST;
-#endif
+    constexpr int MASK = decltype(mask_tag)::value;
+    constexpr bool has1 = decltype(next_tag)::value != 0;
+    const bool has2 = t + 2 < n_tiles;
     if (has2) SVD_LOAD(kreg, K, t + 2);
     if (has1) SVD_LOAD(vreg, V, t + 1);
-#define SVD_STEP(KB, CUR, NXT)                                                              \
-    if (KB + 1 < KB2) {                                                                     \
-      fused(Int<PAR>{}, Int<(KB + 1) % KB2>{}, Int<PAR>{}, Int<KB>{}, CUR, NXT, mx);        \
-      settle(NXT, t, KB + 1);                                                               \
-    } else if (!LAST) {                                                                     \
-      fused(Int<PAR ^ 1>{}, Int<0>{}, Int<PAR>{}, Int<KB>{}, CUR, NXT, mx);                 \
-      settle(NXT, t + 1, 0);                                                                \
-    } else {                                                                                \
-      finish_block(PAR, KB, CUR);                                                           \
+    bool masked = MASK == 1;
+    if (MASK == 2) masked = !(entries[t].y & 1);
+    if (masked) apply_mask(s_cur, t);
+    update_max(s_cur);
+    bf16x8 pf[KB2][2][QB];
+    if (has1) scores(Int<PAR ^ 1>{}, s_next);
+    exponentiate(s_cur, pf);
+    accumulate(Int<PAR>{}, pf);
+    if (has1) {
+      // Issue order for the block above: one MFMA, then the LDS reads that feed
+      // the MFMAs a few steps later, then a handful of VALU ops that hide behind
+      // the MFMA's passes (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
+      constexpr int N_QK = KS * KB2 * QB, N_PV = KB2 * 2 * DB * QB;
+      constexpr int N_KRD = KS * KB2, N_VRD = KB2 * 2 * DB * 2;
+      constexpr int VALU_PER = (KB2 * QB * 16 * 7 / 2 + N_QK + N_PV - 1) / (N_QK + N_PV);
+      constexpr int K_AHEAD = 4, V_AHEAD = 8;
+      __builtin_amdgcn_sched_group_barrier(0x100, K_AHEAD, 0);
+#pragma unroll
+      for (int i = 0; i < N_QK; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i * N_KRD / N_QK + K_AHEAD < N_KRD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        else if (i >= N_QK - V_AHEAD / 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < N_PV; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i * (N_VRD / N_PV) + V_AHEAD < N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, N_VRD / N_PV, 0);
+        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+      }
     }
-    SVD_STEP(0, s_a, s_b)
-    SVD_STEP(1, s_b, s_a)
-    if (KB2 > 2) {
-      SVD_STEP(2, s_a, s_b)
-      SVD_STEP(3, s_b, s_a)
-    }
-#undef SVD_STEP
-    // K(t) (this tile's own K buffer) was still being read by the steps above:
-    // every wave must be past them before K(t+2) may overwrite it
-#ifndef SVD_PROBE_NOBAR
-    if (has2) __syncthreads();
-#endif
     if (has2) SVD_STORE(kreg, sK, st_off_k, PAR);
     if (has1) SVD_STORE(vreg, sV, st_off_v, PAR ^ 1);
-#ifndef SVD_PROBE_NOBAR
     __syncthreads();
-#endif
   };
 
-  // two tiles per trip keep the buffer indices static
+  // Two stages per trip keep buffer indices and the score registers static.
+  // Band lists decide per entry whether to mask; the dense and gather loops can
+  // only meet a partly valid tile at the very end.
+  using MainMask = Int<MODE == MODE_BAND ? 2 : 0>;
+  using TailMask = Int<MODE == MODE_BAND ? 2 : 1>;
   int t = 0;
   for (; t + 2 < n_tiles; t += 2) {
-    tile_steps(Int<0>{}, Int<0>{}, t);
-    tile_steps(Int<1>{}, Int<0>{}, t + 1);
+    stage(Int<0>{}, MainMask{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, MainMask{}, Int<1>{}, t + 1, s_b, s_a);
   }
   if (t + 1 < n_tiles) {
-    tile_steps(Int<0>{}, Int<0>{}, t);
-    tile_steps(Int<1>{}, Int<1>{}, t + 1);
+    stage(Int<0>{}, MainMask{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, TailMask{}, Int<0>{}, t + 1, s_b, s_a);
   } else if (t < n_tiles) {
-    tile_steps(Int<0>{}, Int<1>{}, t);
+    stage(Int<0>{}, TailMask{}, Int<0>{}, t, s_a, s_b);
   }
 
   // ---- epilogue: O = O^T / l, bf16, lane owns query l32: 4 consecutive d per store ----

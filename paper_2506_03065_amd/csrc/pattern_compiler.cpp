@@ -145,6 +145,9 @@ svd_status validate_desc(const svd_tensor_desc* desc) {
   if (desc->D != 64 && desc->D != 128) return SVD_ERR_SHAPE;
   if (desc->stride_l < desc->D || desc->stride_b < 1 || desc->stride_h < 1) return SVD_ERR_SHAPE;
   if (desc->stride_b % 8 || desc->stride_h % 8 || desc->stride_l % 8) return SVD_ERR_ALIGN;
+  // the kernels address the rows of one head with 32-bit byte offsets
+  if (static_cast<double>(desc->L) * static_cast<double>(desc->stride_l) * 2.0 >= 4294967296.0)
+    return SVD_ERR_UNSUPPORTED;
   return SVD_OK;
 }
 
