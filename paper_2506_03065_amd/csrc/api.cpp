@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -15,8 +16,26 @@
 #include "plan.h"
 #include "sparse_vdit.h"
 
+// A launchable plan owns a few side streams and events: the groups of a layer
+// are independent (they write different heads), so the forward pass forks them
+// onto side streams and joins them again on the caller's stream.  The GPU then
+// runs the group kernels concurrently and the work-groups of the lighter groups
+// fill the compute units that the last, partial round of a heavy group leaves
+// idle.  Streams keep the default priority.
+constexpr int kSideStreams = 3;
 struct svd_plan {
   svd::Plan p;
+  hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
+  hipEvent_t fork = nullptr;
+  hipEvent_t join[kSideStreams] = {nullptr, nullptr, nullptr};
+  bool concurrent = false;
+  ~svd_plan() {
+    for (int i = 0; i < kSideStreams; ++i) {
+      if (side[i]) (void)hipStreamDestroy(side[i]);
+      if (join[i]) (void)hipEventDestroy(join[i]);
+    }
+    if (fork) (void)hipEventDestroy(fork);
+  }
 };
 
 namespace {
@@ -171,6 +190,32 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
     }
     sp->p.device_workspace = device_workspace;
     sp->p.launchable = native;
+    // SVD_NO_FORK=1 in the environment keeps every group on the caller's stream
+    const char* no_fork = std::getenv("SVD_NO_FORK");
+    if (native && !(no_fork && no_fork[0] == '1')) {
+      bool ok = hipEventCreateWithFlags(&sp->fork, hipEventDisableTiming) == hipSuccess;
+      for (int i = 0; ok && i < kSideStreams; ++i)
+        ok = hipStreamCreateWithFlags(&sp->side[i], hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&sp->join[i], hipEventDisableTiming) == hipSuccess;
+      // Forking pays when the last round of the heaviest group leaves most compute
+      // units idle (one work-group occupies a whole unit); otherwise the groups
+      // run one after the other, which keeps one head's K/V hot in L2 at a time.
+      int dev = 0, n_cu = 0;
+      if (ok && hipGetDevice(&dev) == hipSuccess &&
+          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0) {
+        const svd::Group* heavy = nullptr;
+        static const int order[4] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE};
+        for (int mode : order) {
+          for (const svd::Group& g : sp->p.groups)
+            if (g.mode == mode && !heavy) heavy = &g;
+        }
+        if (heavy) {
+          const long long items = static_cast<long long>(sp->p.n_q_blocks) * heavy->heads.size() * desc->B;
+          const long long tail = items % n_cu;
+          sp->concurrent = tail != 0 && 2 * tail < n_cu;
+        }
+      }
+    }
   }
   *plan = sp;
   return SVD_OK;
@@ -327,12 +372,41 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
                                     void* out, void* hip_stream) {
   if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
   const Plan& p = plan->p;
+  hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
   // heaviest first: dense, then the band groups, the gathers, and the zero fill
   static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
+  const svd::Group* seq[5];
+  int n = 0;
   for (int mode : order)
     for (const svd::Group& g : p.groups)
-      if (g.mode == mode)
-        if (svd_status st = launch_group(p, g, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
+      if (g.mode == mode && n < 5) seq[n++] = &g;
+  if (!plan->concurrent || n < 2) {
+    for (int i = 0; i < n; ++i)
+      if (svd_status st = launch_group(p, *seq[i], q, k, v, out, main_stream)) return st;
+    return SVD_OK;
+  }
+  // fork: the first group stays on the caller's stream, the others go round-robin
+  // to the side streams; join: the caller's stream waits for every side stream
+  if (hipEventRecord(plan->fork, main_stream) != hipSuccess) return SVD_ERR_HIP;
+  bool used[kSideStreams] = {false, false, false};
+  for (int i = 0; i < n; ++i) {
+    hipStream_t s = main_stream;
+    if (i > 0) {
+      const int k_side = (i - 1) % kSideStreams;
+      s = plan->side[k_side];
+      if (!used[k_side]) {
+        if (hipStreamWaitEvent(s, plan->fork, 0) != hipSuccess) return SVD_ERR_HIP;
+        used[k_side] = true;
+      }
+    }
+    if (svd_status st = launch_group(p, *seq[i], q, k, v, out, s)) return st;
+  }
+  for (int i = 0; i < kSideStreams; ++i) {
+    if (!used[i]) continue;
+    if (hipEventRecord(plan->join[i], plan->side[i]) != hipSuccess ||
+        hipStreamWaitEvent(main_stream, plan->join[i], 0) != hipSuccess)
+      return SVD_ERR_HIP;
+  }
   return SVD_OK;
 }
 
