@@ -18,6 +18,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc passes
+# summarised under profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: the
+# factors a 1 GiB streaming kernel in the same runs gives).  Counters cannot be
+# read from inside this process, so the figure is carried here per workload.
+PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 280909 + 21600) * 1024}}
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
@@ -45,7 +50,7 @@ def cpu_baseline(wl, q, k, v, out, budget_s, torch, np):
     except Exception:
         threads = os.cpu_count() or 1
     gen = np.random.default_rng(wl.seed)
-    n_rows = 256
+    n_rows = 512
     rows = np.sort(gen.choice(wl.L, size=n_rows, replace=False))
     spent, heads_done, max_err, sum_err, n_err = 0.0, 0, 0.0, 0.0, 0
     f64 = lambda t: t.cpu().to(torch.float64).numpy()
@@ -77,7 +82,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cogvideox1.5")
     ap.add_argument("--dense-reps", type=int, default=2, help="timed passes of the all-heads dense baseline (0 = skip)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="budget of the CPU-oracle leg (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain streaming kernel (1 GiB read, 1 GiB written) so that a rocprofv3 "
+                         "--pmc run of this command holds a dispatch of known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -140,7 +148,7 @@ def main():
     dom = max(compute_groups, key=lambda g: g["ms"])
     roofline = {"bound": "mfma", "kernel": f"attn_fwd_kernel[{dom['mode']} group]", "achieved": dom["tflops"],
                 "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(dom["tflops"] / BF16_MFMA_PEAK_TFLOPS, 4),
-                "traffic": None}
+                "traffic": PMC_TRAFFIC_BYTES.get(wl.name, {}).get(dom["mode"])}
 
     # ---- in-house dense kernel on all heads: the speed-up baseline ----
     dense_ms = None
@@ -150,6 +158,14 @@ def main():
         del dense_out
     step()
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 2.0, out=dst)      # vectorized elementwise kernel: reads 2^30 B, writes 2^30 B
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu, max_err, mean_err = (None, None, None)
     if args.cpu_seconds > 0:
