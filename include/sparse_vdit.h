@@ -150,11 +150,15 @@ svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* com
 /* Forward pass of one layer with a compiled plan (Section 4.2: one fused launch
  * per mode present in the table, heaviest group first, plus a zero fill for
  * skipped heads).  The tensors must match the plan's descriptor.  The group
- * kernels are independent; they are forked from hip_stream onto streams owned
- * by the plan and joined on hip_stream again before the call returns, so for
- * the caller everything is ordered on hip_stream.  One forward pass per plan
- * may be in flight at a time (calls with the same plan on one stream are
- * fine; concurrent calls on different streams need different plans). */
+ * kernels are independent.  Normally they are enqueued one after the other on
+ * hip_stream.  When the last round of work-groups of the heaviest group would
+ * leave more than half of the compute units idle, the groups are instead forked
+ * from hip_stream onto streams owned by the plan, run concurrently, and are
+ * joined on hip_stream before the call returns; either way everything is
+ * ordered on hip_stream for the caller.  One forward pass per plan may be in
+ * flight at a time (calls with the same plan on one stream are fine; concurrent
+ * calls on different streams need different plans).  SVD_NO_FORK=1 in the
+ * environment at plan creation disables the fork. */
 svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
                                     void* out, void* hip_stream);
 
