@@ -38,6 +38,8 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -148,6 +150,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   }
 
   // ---- Q fragments: B operand of S^T = K Q^T (lane: query l32, 8 of 16 d) ----
+  // Q is multiplied by log2(e) / sqrt(D) here, once, and rounded back to bf16:
+  // the scores then come out of the matrix pipe in the exponent domain of exp2
+  // and need no per-element scaling.
+  const float c_scale = p.scale_log2e;
   const int q0 = qblk * BR + wave * QW;
   bf16x8 qf[QB][KS];
 #pragma unroll
@@ -156,57 +162,101 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     row = row < L ? row : L - 1;
     const __bf16* src = Q + (int64_t)row * p.stride_l + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+      const f32x8 scaled = __builtin_convertvector(raw, f32x8) * c_scale;
+      qf[qb][ks] = __builtin_convertvector(scaled, bf16x8);
+    }
   }
 
-  f32x16 o[DB][QB];
-  float m_run[QB], l_run[QB];
+  // Softmax state per 32-row block.  Scores are kept RELATIVE to a reference
+  // exponent: the score accumulators start from nm = -reference (16 copies, the
+  // C operand of the first MFMA of a block), so exp2 applies to the MFMA result
+  // as it is.  thr is the excess over the reference that makes the lane move
+  // it: -inf until the lane has seen its first kept key, kLazyLog2 afterwards.
+  // The row sums accumulate in element 0 of l4 through a small MFMA.
+  constexpr float kLazyLog2 = 8.0f;
+  f32x16 o[DB][QB], nm[QB];
+  f32x4 l4[QB];
+  float thr[QB], mx_raw[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = kNegInf;
-    l_run[qb] = 0.f;
+    thr[qb] = kNegInf;
+    mx_raw[qb] = kNegInf;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) l4[qb][i] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) nm[qb][i] = 0.f;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
   }
+  // A operand of the row-sum MFMA (16x16x32): fed with a P fragment laid out for
+  // the 32x32x16 product (lane: query l32, 8 keys of half `half`), the 16x16x32
+  // unit sees query l%16 + 16*((l/16)&1) and keys 8*(l/32).. in lane l.  Rows 0
+  // and 8 of A select the lanes of the even 16-lane blocks, rows 4 and 12 those
+  // of the odd ones, all other rows are zero: element 0 of the result (row
+  // 4*(l/16), column l%16) is then the sum over the 16 keys of the lane's own
+  // query, in every lane.
+  bf16x8 sum_a;
+  {
+    const int m16 = lane & 15, g16 = lane >> 4;
+    const bool on = ((m16 & 7) == 0 && (g16 & 1) == 0) || ((m16 & 7) == 4 && (g16 & 1) == 1);
+    const __bf16 v = on ? (__bf16)1.0f : (__bf16)0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum_a[i] = v;
+  }
 
   // ---- tile loaders: global -> registers -> LDS, K and V separately ----
+  // Thread `tid` moves chunks g = u * NT + tid: row g / CH = r0 + u * (NT / CH),
+  // 16-byte chunk c0 = tid % CH (the same for every u).  A tile is addressed as a
+  // uniform base (scalar registers) plus a per-thread 32-bit byte offset; rows
+  // past L - 1 (ragged last tile) are bent back onto row L - 1 by clamping that
+  // offset, and masked later.
+  static_assert(NT % CH == 0, "a thread keeps its chunk column");
+  constexpr int RSTEP = NT / CH;   // rows between consecutive chunks of a thread
+  const unsigned stride_bytes = (unsigned)p.stride_l * 2u;
+  const int ld_r0 = tid / CH, ld_c0 = tid % CH;
   u32x4 kreg[NCH], vreg[NCH];
-  int st_off_k[NCH], st_off_v[NCH], ld_row[NCH], ld_col[NCH];
+  int st_off_k[NCH], st_off_v[NCH];
 #pragma unroll
   for (int u = 0; u < NCH; ++u) {
-    const int g = u * NT + tid;
-    const int r = g / CH, c = g % CH;
-    ld_row[u] = r;
-    ld_col[u] = c * 8;
-    st_off_k[u] = r * ROW_BYTES + ((c ^ swz_k<D>(r)) << 4);
-    st_off_v[u] = r * ROW_BYTES + ((c ^ swz_v<D>(r)) << 4);
+    const int r = ld_r0 + u * RSTEP;
+    st_off_k[u] = r * ROW_BYTES + ((ld_c0 ^ swz_k<D>(r)) << 4);
+    st_off_v[u] = r * ROW_BYTES + ((ld_c0 ^ swz_v<D>(r)) << 4);
   }
-  // global row of key slot r of tile t
-  auto key_row = [&](const int t, const int r) -> int {
+  const unsigned g_off0 = MODE == MODE_GATHER ? (unsigned)ld_r0 * 4u
+                                              : (unsigned)ld_r0 * stride_bytes + (unsigned)ld_c0 * 16u;
+  const unsigned g_last = (unsigned)(L - 1) * stride_bytes + (unsigned)ld_c0 * 16u;   // same chunk of row L - 1
+  auto load_tile = [&](u32x4 (&reg)[NCH], const __bf16* __restrict__ src, const int t) {
+    const char* src_b = reinterpret_cast<const char*>(src);
     if (MODE == MODE_GATHER) {
-      const int c = cols[t * BC + r];
-      return c < 0 ? 0 : c;
+      // key rows come from the head's column list (-1 = padding: any valid row, masked later)
+      const char* list = reinterpret_cast<const char*>(cols + t * BC);
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        int c = *reinterpret_cast<const int*>(list + (g_off0 + (unsigned)(u * RSTEP * 4)));
+        c = c < 0 ? 0 : c;
+        const unsigned off = __umul24((unsigned)c, stride_bytes) + (unsigned)ld_c0 * 16u;
+        reg[u] = *reinterpret_cast<const u32x4*>(src_b + off);
+      }
+    } else {
+      const unsigned tile_off = (unsigned)((MODE == MODE_BAND ? entries[t].x : t) * BC) * stride_bytes;
+      const char* base_b = src_b + tile_off;
+      const unsigned lim = g_last - tile_off;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        unsigned off = g_off0 + (unsigned)(u * RSTEP) * stride_bytes;
+        off = off < lim ? off : lim;
+        reg[u] = *reinterpret_cast<const u32x4*>(base_b + off);
+      }
     }
-    const int kb = MODE == MODE_BAND ? entries[t].x : t;
-    const int j = kb * BC + r;
-    return j < L ? j : L - 1;
   };
-#define SVD_LOAD(REG, PTR, T)                                                             \
-  _Pragma("unroll") for (int u = 0; u < NCH; ++u)                                         \
-    REG[u] = *reinterpret_cast<const u32x4*>(PTR + (int64_t)key_row((T), ld_row[u]) * p.stride_l + ld_col[u]);
+#define SVD_LOAD(REG, PTR, T) load_tile(REG, PTR, (T));
 #define SVD_STORE(REG, SBASE, OFF, BUF)                                                   \
   _Pragma("unroll") for (int u = 0; u < NCH; ++u)                                         \
     *reinterpret_cast<u32x4*>(SBASE + (BUF) * TILE_BYTES + OFF[u]) = REG[u];
-
-  const float c_scale = p.scale_log2e;
-  // The running maximum is only raised when a tile exceeds it by more than
-  // kLazyLog2 in the exponent (2^8 = 256x): until then P keeps the stale
-  // reference, which changes no result (any reference cancels in O / l) but
-  // saves the rescale of O and l on most tiles.
-  constexpr float kLazyLog2 = 8.0f;
-  const float tau = kLazyLog2 / c_scale;
 
   // per-lane LDS read offsets (everything else is an immediate)
   int k_off[KS];   // K fragment: key l32 of a 32-key block, chunk 2 * ks + half
@@ -229,9 +279,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 #pragma unroll
     for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[kb2][qb][i] = 0.f;
+      for (int qb = 0; qb < QB; ++qb) s[kb2][qb] = nm[qb];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
@@ -290,37 +338,55 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     }
   };
 
-  // ---- running maximum of the tile (per lane: one query column), lazy rescale ----
-  float mc[QB];   // reference maximum times the scale, per 32-row block
-  auto update_max = [&](const f32x16 (&s)[KB2][QB]) {
+  // ---- maximum of a tile's relative scores (per lane: the keys of its half) ----
+  auto tile_max = [&](const f32x16 (&s)[KB2][QB]) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float mx = kNegInf;
+      float a = kNegInf, b = kNegInf;   // two chains of v_max3
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
-        for (int i = 0; i < 16; i += 2) mx = fmaxf(mx, fmaxf(s[kb2][qb][i], s[kb2][qb][i + 1]));
-      mx = half_max(mx);
-      const bool grow = mx > m_run[qb] + tau;   // false when the lane's tile is fully masked
+        for (int i = 0; i < 8; i += 2) {
+          a = fmaxf(fmaxf(a, s[kb2][qb][i]), s[kb2][qb][i + 1]);
+          b = fmaxf(fmaxf(b, s[kb2][qb][8 + i]), s[kb2][qb][8 + i + 1]);
+        }
+      mx_raw[qb] = fmaxf(a, b);
+    }
+  };
+
+  // ---- lazy reference update.  The reference is only moved when a tile exceeds
+  // it by more than kLazyLog2 in the exponent (2^8): until then P keeps the
+  // stale reference, which changes no result (any reference cancels in O / l).
+  // Moving it shifts the scores already computed and the accumulator seed nm,
+  // and rescales l and O; the branch is wave-uniform and rarely taken. ----
+  auto settle_max = [&](f32x16 (&s)[KB2][QB]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float mx = half_max(mx_raw[qb]);
+      const bool grow = mx > thr[qb];   // false when the lane's tile is fully masked
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-        const float alpha = grow ? __builtin_amdgcn_exp2f((m_run[qb] - mx) * c_scale) : 1.0f;
-        m_run[qb] = grow ? mx : m_run[qb];
-        l_run[qb] *= alpha;
+        const float delta = grow ? mx : 0.f;
+        const float alpha = (grow && thr[qb] != kNegInf) ? __builtin_amdgcn_exp2f(-mx) : 1.0f;
+        thr[qb] = grow ? kLazyLog2 : thr[qb];
+#pragma unroll
+        for (int kb2 = 0; kb2 < KB2; ++kb2)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[kb2][qb][i] -= delta;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) nm[qb][i] -= delta;
+        l4[qb][0] *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
       }
-      mc[qb] = (m_run[qb] == kNegInf ? 0.f : m_run[qb]) * c_scale;
     }
   };
 
-  // ---- P = exp2(S * c - m * c), rounded to bf16 in the B-operand layout; row sums ----
+  // ---- P = exp2(relative score), rounded to bf16 in the B-operand layout ----
   auto exponentiate = [&](const f32x16 (&s)[KB2][QB], bf16x8 (&pf)[KB2][2][QB]) {
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float rs = 0.f;
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
@@ -328,22 +394,20 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
           bf16x8 pk;
 #pragma unroll
           for (int i = 0; i < 8; i += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i], c_scale, -mc[qb]));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb2][qb][sub * 8 + i + 1], c_scale, -mc[qb]));
+            const float p0 = __builtin_amdgcn_exp2f(s[kb2][qb][sub * 8 + i]);
+            const float p1 = __builtin_amdgcn_exp2f(s[kb2][qb][sub * 8 + i + 1]);
             const f32x2 pp = {p0, p1};
             const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-            rs = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs, false);   // row sum of the rounded P
             pk[i] = pb[0];
             pk[i + 1] = pb[1];
           }
           pf[kb2][sub][qb] = pk;
         }
       }
-      l_run[qb] += rs;
     }
   };
 
-  // ---- O^T += V^T P^T for the tile held in V buffer BUF ----
+  // ---- O^T += V^T P^T and l += rowsum(P) for the tile held in V buffer BUF ----
   auto accumulate = [&](auto buf_tag, const bf16x8 (&pf)[KB2][2][QB]) {
     constexpr int BUF = decltype(buf_tag)::value;
     const unsigned char* vbase = sV + BUF * TILE_BYTES;
@@ -363,6 +427,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
           for (int qb = 0; qb < QB; ++qb)
             o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb2][sub][qb], o[db][qb], 0, 0, 0);
         }
+        // row sums of the rounded P (numerator and denominator see the same values)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          l4[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sum_a, pf[kb2][sub][qb], l4[qb], 0, 0, 0);
       }
     }
   };
@@ -380,7 +448,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     }
   }
   __syncthreads();
-  if (n_tiles > 0) scores(Int<0>{}, s_a);
+  if (n_tiles > 0) {
+    scores(Int<0>{}, s_a);
+    tile_max(s_a);
+  }
 
   // One pipeline stage.  On entry s_cur holds the raw scores of tile t; LDS holds
   // K(t+1) in K buffer (t+1)&1 and V(t) in V buffer t&1, while K(t+2) and V(t+1)
@@ -400,20 +471,34 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     if (has1) SVD_LOAD(vreg, V, t + 1);
     bool masked = MASK == 1;
     if (MASK == 2) masked = !(entries[t].y & 1);
-    if (masked) apply_mask(s_cur, t);
-    update_max(s_cur);
+    if (masked) {
+      apply_mask(s_cur, t);
+      tile_max(s_cur);     // the maximum taken before masking may belong to a dropped key
+    }
+    settle_max(s_cur);
     bf16x8 pf[KB2][2][QB];
     if (has1) scores(Int<PAR ^ 1>{}, s_next);
     exponentiate(s_cur, pf);
+    if (has1) tile_max(s_next);
     accumulate(Int<PAR>{}, pf);
     if (has1) {
       // Issue order for the block above: one MFMA, then the LDS reads that feed
       // the MFMAs a few steps later, then a handful of VALU ops that hide behind
       // the MFMA's passes (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
-      constexpr int N_QK = KS * KB2 * QB, N_PV = KB2 * 2 * DB * QB;
-      constexpr int N_KRD = KS * KB2, N_VRD = KB2 * 2 * DB * 2;
-      constexpr int VALU_PER = (KB2 * QB * 16 * 7 / 2 + N_QK + N_PV - 1) / (N_QK + N_PV);
-      constexpr int K_AHEAD = 4, V_AHEAD = 8;
+      constexpr int N_QK = KS * KB2 * QB, N_PVG = KB2 * 2, N_PV = N_PVG * DB * QB, N_SUM = N_PVG * QB;
+      constexpr int N_KRD = KS * KB2, N_VRD = N_PVG * DB * 2;
+      // per score element: one exp2, half a conversion, half a max3
+#ifndef SVD_VALU_EXTRA
+#define SVD_VALU_EXTRA 0
+#endif
+#ifndef SVD_K_AHEAD
+#define SVD_K_AHEAD 4
+#endif
+#ifndef SVD_V_AHEAD
+#define SVD_V_AHEAD 8
+#endif
+      constexpr int VALU_PER = (KB2 * QB * 16 * 2 + N_QK + N_PV + N_SUM - 1) / (N_QK + N_PV + N_SUM) + SVD_VALU_EXTRA;
+      constexpr int K_AHEAD = SVD_K_AHEAD, V_AHEAD = SVD_V_AHEAD;
       __builtin_amdgcn_sched_group_barrier(0x100, K_AHEAD, 0);
 #pragma unroll
       for (int i = 0; i < N_QK; ++i) {
@@ -423,10 +508,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
       }
 #pragma unroll
-      for (int i = 0; i < N_PV; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i * (N_VRD / N_PV) + V_AHEAD < N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, N_VRD / N_PV, 0);
-        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+      for (int g = 0; g < N_PVG; ++g) {
+#pragma unroll
+        for (int j = 0; j < DB * QB; ++j) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if ((g * DB * QB + j) * 2 + V_AHEAD < N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < QB; ++j) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+        }
       }
     }
     if (has2) SVD_STORE(kreg, sK, st_off_k, PAR);
@@ -454,8 +547,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   // ---- epilogue: O = O^T / l, bf16, lane owns query l32: 4 consecutive d per store ----
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const float l_tot = half_sum(l_run[qb]);
-    const float inv = 1.0f / l_tot;
+    const float inv = 1.0f / l4[qb][0];   // every lane holds the complete sum of its query
     const int row = q0 + qb * 32 + l32;
     if (row < L) {
       __bf16* dst = O + (int64_t)row * p.stride_l;
