@@ -153,3 +153,35 @@ def test_errors_leave_output_untouched():
         svd.svd_attn_forward_planned(plan, q, k, v, out)
     assert e.value.status == 9
     assert (out == 3.0).all()
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("profile", ["rising", "falling", "late_outlier", "very_negative"])
+def test_peaked_scores_move_the_softmax_reference(D, profile):
+    """Score profiles along the key axis that make the running reference of the
+    online softmax move many times (rising), never after the first tile
+    (falling), once by a large jump near the end (late_outlier), or that sit
+    far below zero everywhere (very_negative: an unset reference must not be
+    taken for zero).  Logits reach 50 to 180 in magnitude, far beyond what
+    N(0,1) inputs give."""
+    L, H = 1500, 5
+    wl = W.small(L=L, D=D, H=H, seed=41)
+    q, k, v = W.make_qkv(wl)
+    j = torch.arange(L, dtype=torch.float32)
+    if profile == "rising":
+        gain = 0.25 + 2.75 * j / L
+    elif profile == "falling":
+        gain = 3.0 - 2.75 * j / L
+    elif profile == "late_outlier":
+        gain = torch.ones(L)
+        gain[L - 37] = 5.0
+    else:
+        gain = torch.full((L,), 8.0)
+    # every query looks along +u; key j looks along gain[j] * u (minus for very_negative)
+    u = torch.nn.functional.normalize(torch.ones(D), dim=0) * (D ** 0.5)
+    sign = -1.0 if profile == "very_negative" else 1.0
+    q = (0.3 * q.float() + 2.0 * u).to(torch.bfloat16)
+    k = (0.3 * k.float() + sign * gain[None, None, :, None] * u).to(torch.bfloat16)
+    q, k, v = _cuda([q, k, v])
+    out = run_planned(wl, q, k, v)
+    check_layer(wl, q, k, v, out)
