@@ -293,17 +293,36 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   };
 
   // ---- masks: element (kb2, i) of a lane is key kb2*32 + (i/4)*8 + half*4 + i%4 ----
-  auto apply_mask = [&](f32x16 (&s)[KB2][QB], const int t) {
+  // Returns false when nothing was changed (the wave's part of the tile is kept
+  // as a whole).  Band tiles: a wave first classifies each of its 32 x 32 blocks
+  // against the run with wave-uniform arithmetic; only blocks that a band edge
+  // (or the end of the sequence) actually crosses are masked element by element.
+  auto apply_mask = [&](f32x16 (&s)[KB2][QB], const int t) -> bool {
+    bool changed = false;
     if (MODE == MODE_BAND) {
       const int2 ent = entries[t];
       const int kv0 = ent.x * BC;
       const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
+      const int qw0 = __builtin_amdgcn_readfirstlane(q0);
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
+          const int jb0 = kv0 + kb2 * 32;                      // first key of the block
+          const int dmin = jb0 - (qw0 + qb * 32) - 31, dmax = dmin + 62;   // diagonals the block touches
+          if (rn == 1) {
+            const int2 run = runs[r0];
+            if (dmin >= run.x && dmax <= run.y && jb0 + 31 < L) continue;   // kept as a whole
+            changed = true;
+            if (dmax < run.x || dmin > run.y || jb0 >= L) {                    // dropped as a whole
+#pragma unroll
+              for (int i = 0; i < 16; ++i) s[kb2][qb][i] = kNegInf;
+              continue;
+            }
+          }
+          changed = true;
           const int iq = q0 + qb * 32 + l32;
-          const int jb = kv0 + kb2 * 32 + half * 4;   // key of element 0
+          const int jb = jb0 + half * 4;   // key of element 0
           f32x16 kept;
 #pragma unroll
           for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
@@ -313,11 +332,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
             int hi = run.y;
             hi = hi < L - 1 - iq ? hi : L - 1 - iq;
             const int t0 = jb - iq - run.x;
-            const int span = hi - run.x;    // may be negative: nothing kept
+            const unsigned span = (unsigned)(hi - run.x);    // wraps when nothing is kept: tested below
+            if (hi >= run.x) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int d = t0 + (i / 4) * 8 + (i % 4);
-              kept[i] = (d >= 0 && d <= span) ? s[kb2][qb][i] : kept[i];
+              for (int i = 0; i < 16; ++i) {
+                const unsigned d = (unsigned)(t0 + (i / 4) * 8 + (i % 4));
+                kept[i] = d <= span ? s[kb2][qb][i] : kept[i];
+              }
             }
           }
           s[kb2][qb] = kept;
@@ -326,6 +347,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     } else {
       // dense: keys past L in the last tile; gather: padding of the column list
       const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
+      changed = true;
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
@@ -336,6 +358,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
             s[kb2][qb][i] = j < limit ? s[kb2][qb][i] : kNegInf;
           }
     }
+    return changed;
   };
 
   // ---- maximum of a tile's relative scores (per lane: the keys of its half) ----
@@ -471,10 +494,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     if (has1) SVD_LOAD(vreg, V, t + 1);
     bool masked = MASK == 1;
     if (MASK == 2) masked = !(entries[t].y & 1);
-    if (masked) {
-      apply_mask(s_cur, t);
-      tile_max(s_cur);     // the maximum taken before masking may belong to a dropped key
-    }
+    if (masked && apply_mask(s_cur, t)) tile_max(s_cur);   // the maximum taken before masking may belong to a dropped key
     settle_max(s_cur);
     bf16x8 pf[KB2][2][QB];
     if (has1) scores(Int<PAR ^ 1>{}, s_next);
@@ -488,17 +508,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
       constexpr int N_QK = KS * KB2 * QB, N_PVG = KB2 * 2, N_PV = N_PVG * DB * QB, N_SUM = N_PVG * QB;
       constexpr int N_KRD = KS * KB2, N_VRD = N_PVG * DB * 2;
       // per score element: one exp2, half a conversion, half a max3
-#ifndef SVD_VALU_EXTRA
-#define SVD_VALU_EXTRA 0
-#endif
-#ifndef SVD_K_AHEAD
-#define SVD_K_AHEAD 4
-#endif
-#ifndef SVD_V_AHEAD
-#define SVD_V_AHEAD 8
-#endif
-      constexpr int VALU_PER = (KB2 * QB * 16 * 2 + N_QK + N_PV + N_SUM - 1) / (N_QK + N_PV + N_SUM) + SVD_VALU_EXTRA;
-      constexpr int K_AHEAD = SVD_K_AHEAD, V_AHEAD = SVD_V_AHEAD;
+      constexpr int VALU_PER = (KB2 * QB * 16 * 2 + N_QK + N_PV + N_SUM - 1) / (N_QK + N_PV + N_SUM);
+      constexpr int K_AHEAD = 4, V_AHEAD = 8;
       __builtin_amdgcn_sched_group_barrier(0x100, K_AHEAD, 0);
 #pragma unroll
       for (int i = 0; i < N_QK; ++i) {
@@ -522,6 +533,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         }
       }
     }
+    // Nothing may move across this point: the LDS stores below wait for the
+    // global loads issued at the top of the stage, and must not be hoisted
+    // into the block above (that would expose the whole load latency).
+    __builtin_amdgcn_sched_barrier(0);
     if (has2) SVD_STORE(kreg, sK, st_off_k, PAR);
     if (has1) SVD_STORE(vreg, sV, st_off_v, PAR ^ 1);
     __syncthreads();
