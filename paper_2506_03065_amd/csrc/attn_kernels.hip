@@ -63,11 +63,6 @@ __device__ __forceinline__ float half_max(float x) {
   half_pair(x, &lo, &hi);
   return fmaxf(lo, hi);
 }
-__device__ __forceinline__ float half_sum(float x) {
-  float lo, hi;
-  half_pair(x, &lo, &hi);
-  return lo + hi;
-}
 
 // 16-byte chunk swizzles of the LDS tiles (row = key, chunk = 8 bf16 of D).
 // K is read 16 bytes per lane with consecutive lanes on consecutive keys; V is
