@@ -83,10 +83,17 @@ typedef struct {
   const int32_t* cols;       /* mode 4: key columns in [0, L), any order, no duplicates, host */
 } svd_head_params;
 
-/* Block shape of the key-block lists: block_q query rows by block_k keys.
- * 0 selects the shape the kernels run for the given D.  A plan compiled with
- * another shape can be inspected but not launched. */
-typedef struct { int32_t block_q, block_k; } svd_plan_options;
+/* Plan options (a NULL pointer or zeros select the defaults).
+ * block_q x block_k: block shape of the key-block lists, block_q query rows by
+ * block_k keys; 0 selects the shape the kernels run for the given D.  A plan
+ * compiled with another shape can be inspected but not launched.
+ * dense_split: key-range chunks per query tile of the dense heads.  A work-group
+ * occupies a whole compute unit, so few long dense items leave the last round
+ * of work-groups partly empty; splitting the key range makes the rounds shorter
+ * at the price of a merge pass over partial results kept in the workspace.
+ * 0 = chosen from the shape and the device's compute-unit count, 1 = off,
+ * 2..8 = forced (capped at the number of key tiles). */
+typedef struct { int32_t block_q, block_k, dense_split; } svd_plan_options;
 
 typedef struct svd_plan svd_plan;
 
@@ -94,7 +101,10 @@ typedef struct svd_plan svd_plan;
  * options).  D must be 64 or 128. */
 svd_status svd_default_blocks(int32_t D, int32_t* block_q, int32_t* block_k);
 
-/* Bytes of device workspace a plan for this layer needs.  Host only. */
+/* Bytes of device workspace a plan for this layer needs: the compiled lists plus,
+ * when the dense heads are split, the scratch of their partial results.  Reads
+ * the current device's compute-unit count when dense_split is 0 (no device: no
+ * split); touches no device memory. */
 svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* strategy_table,
                                     const svd_head_params* pattern_params,
                                     const svd_plan_options* options, size_t* bytes);
@@ -111,6 +121,10 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
                            const svd_plan_options* options, void* device_workspace,
                            size_t workspace_bytes, void* hip_stream);
 svd_status svd_plan_destroy(svd_plan* plan);
+
+/* Key-range chunks per dense query tile this plan launches (1 = no split; always
+ * 1 for host-only plans). */
+svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split);
 
 /* Inspection of a compiled plan (host copies owned by the plan, valid until
  * svd_plan_destroy).  Groups are ordered by ascending mode id. */

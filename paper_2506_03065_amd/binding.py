@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SVD_OK", 1: "SVD_ERR_NULL", 2: "SVD_ERR_SHAPE", 3: "SVD_ERR_
 SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
-           "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_band_list", "svd_plan_column_list",
+           "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_band_list", "svd_plan_column_list",
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
            "svd_dense_attn_forward", "svd_status_string"]
 
@@ -45,7 +45,7 @@ class HeadParams(C.Structure):
 
 
 class PlanOptions(C.Structure):
-    _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32)]
+    _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32), ("dense_split", C.c_int32)]
 
 
 _lib = None
@@ -67,6 +67,7 @@ def lib():
             "svd_plan_workspace_bytes": [descp, i32p, hpp, optp, C.POINTER(C.c_size_t)],
             "svd_plan_create": [C.POINTER(vp), descp, i32p, hpp, optp, vp, C.c_size_t, vp],
             "svd_plan_destroy": [vp],
+            "svd_plan_dense_split": [vp, i32p],
             "svd_plan_num_groups": [vp, i32p],
             "svd_plan_group_info": [vp, C.c_int32, i32p, i32p, i32pp, i32pp, i32p],
             "svd_plan_band_list": [vp, C.c_int32, C.c_int32, i32p, i32pp, i32pp, i32pp, i32pp, i32pp, i32p, i32pp],
@@ -147,9 +148,9 @@ def svd_default_blocks(D: int):
     return bq.value, bk.value
 
 
-def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0) -> int:
+def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0, dense_split=0) -> int:
     m = _Marshalled(strategy_table, pattern_params)
-    opt = PlanOptions(block_q, block_k)
+    opt = PlanOptions(block_q, block_k, dense_split)
     n = C.c_size_t()
     _check(lib().svd_plan_workspace_bytes(C.byref(desc), _ptr(m.table), m.params, C.byref(opt), C.byref(n)),
            "svd_plan_workspace_bytes")
@@ -178,6 +179,11 @@ class Plan:
             pass
 
     # ---- inspection ----
+    def dense_split(self) -> int:
+        n = C.c_int32()
+        _check(lib().svd_plan_dense_split(self.handle, C.byref(n)), "svd_plan_dense_split")
+        return n.value
+
     def groups(self):
         L_ = lib()
         n = C.c_int32()
@@ -221,11 +227,12 @@ class Plan:
         return {"computed_tiles": tiles.value, "computed_flops": flops.value, "kept_pairs": pairs.value}
 
 
-def svd_plan_create(desc, strategy_table, pattern_params, block_q=0, block_k=0, workspace=None, stream=None) -> Plan:
+def svd_plan_create(desc, strategy_table, pattern_params, block_q=0, block_k=0, workspace=None, stream=None,
+                    dense_split=0) -> Plan:
     """workspace: a torch uint8/int32 CUDA tensor of at least svd_plan_workspace_bytes
     bytes, or None for a host-only plan (inspection, no launches)."""
     m = _Marshalled(strategy_table, pattern_params)
-    opt = PlanOptions(block_q, block_k)
+    opt = PlanOptions(block_q, block_k, dense_split)
     handle = C.c_void_p()
     ws_ptr = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0

@@ -29,6 +29,8 @@ struct svd_plan {
   hipEvent_t fork = nullptr;
   hipEvent_t join[kSideStreams] = {nullptr, nullptr, nullptr};
   bool concurrent = false;
+  int dense_split = 1;          // key-range chunks per dense item
+  size_t partial_offset = 0;    // byte offset of the split scratch in the workspace
   ~svd_plan() {
     for (int i = 0; i < kSideStreams; ++i) {
       if (side[i]) (void)hipStreamDestroy(side[i]);
@@ -51,8 +53,66 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
   *bq = (opt && opt->block_q) ? opt->block_q : kq;
   *bk = (opt && opt->block_k) ? opt->block_k : kk;
   if (*bq < 1 || *bk < 1) return SVD_ERR_UNSUPPORTED;
+  if (opt && opt->dense_split < 0) return SVD_ERR_UNSUPPORTED;
   *native = (*bq == kq && *bk == kk);
   return SVD_OK;
+}
+
+// Compute units of the current device, 0 when there is none (host-only use).
+int device_compute_units() {
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return n_cu > 0 ? n_cu : 0;
+}
+
+constexpr int kMaxDenseSplit = 8;
+
+// Key-range split of the dense group.  A work-group occupies a whole compute
+// unit, so n items run in ceil(n / n_cu) rounds and the last round is paid in
+// full however few items it holds; with s chunks per item the rounds get s
+// times shorter and the last one fuller.  The price is the merge pass over the
+// partial results.  Picks the s that minimises a rough time estimate, 1 when
+// the gain is small.
+int choose_dense_split(const svd_tensor_desc& d, int block_q, int block_k, int n_dense_heads, int n_cu,
+                       const svd_plan_options* opt) {
+  if (n_dense_heads < 1) return 1;
+  const int n_key_tiles = (d.L + block_k - 1) / block_k;
+  const int cap = n_key_tiles < kMaxDenseSplit ? n_key_tiles : kMaxDenseSplit;
+  if (opt && opt->dense_split > 0) return opt->dense_split < cap ? opt->dense_split : cap;
+  if (n_cu < 1) return 1;
+  const double n = static_cast<double>((d.L + block_q - 1) / block_q) * n_dense_heads * d.B;
+  const double t_item = 4.0 * block_q * d.L * d.D / (d.D == 128 ? 4.6e12 : 4.0e12);   // seconds on one unit
+  double best_t = 0.0;
+  int best = 1;
+  for (int sp = 1; sp <= cap; ++sp) {
+    double t = std::ceil(n * sp / n_cu) / sp * t_item * (1.0 + 0.01 * (sp - 1));
+    if (sp > 1) t += 15e-6 + 2.0 * 4.0 * static_cast<double>(svd::partial_floats(d.D, static_cast<int>(n) * sp)) / 2.5e12;
+    if (sp == 1 || t < best_t * (best == 1 ? 0.97 : 1.0)) {
+      best_t = t;
+      best = sp;
+    }
+  }
+  return best;
+}
+
+int count_dense_heads(const Plan& p) {
+  for (const svd::Group& g : p.groups)
+    if (g.mode == SVD_DENSE) return static_cast<int>(g.heads.size());
+  return 0;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace = [compiled lists | padding to 256 bytes | scratch of the dense split].
+size_t workspace_need(const Plan& p, int dense_split, size_t* partial_offset) {
+  const size_t lists = p.ws_image.size() * sizeof(int32_t);
+  if (partial_offset) *partial_offset = 0;
+  if (dense_split <= 1) return lists;
+  const size_t off = align_up(lists, 256);
+  if (partial_offset) *partial_offset = off;
+  const int items = p.n_q_blocks * count_dense_heads(p) * p.desc.B * dense_split;
+  return off + svd::partial_floats(p.desc.D, items) * sizeof(float);
 }
 
 svd::AttnLaunch base_launch(const svd_tensor_desc& d, const void* q, const void* k, const void* v,
@@ -70,6 +130,7 @@ svd::AttnLaunch base_launch(const svd_tensor_desc& d, const void* q, const void*
   a.stride_h = d.stride_h;
   a.stride_l = d.stride_l;
   a.scale_log2e = static_cast<float>(1.4426950408889634 / std::sqrt(static_cast<double>(d.D)));
+  a.split = 1;
   return a;
 }
 
@@ -150,7 +211,9 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
   Plan tmp;
   if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, &tmp)) return st;
-  *bytes = tmp.ws_image.size() * sizeof(int32_t);
+  const int split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), device_compute_units(), options)
+                           : 1;
+  *bytes = workspace_need(tmp, split, nullptr);
   return SVD_OK;
 }
 
@@ -177,13 +240,16 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
     return st;
   }
   if (device_workspace) {
-    const size_t need = sp->p.ws_image.size() * sizeof(int32_t);
+    sp->dense_split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), device_compute_units(), options)
+                             : 1;
+    const size_t need = workspace_need(sp->p, sp->dense_split, &sp->partial_offset);
     if (workspace_bytes < need || !aligned16(device_workspace)) {
       delete sp;
       return SVD_ERR_WORKSPACE;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (hipMemcpyAsync(device_workspace, sp->p.ws_image.data(), need, hipMemcpyHostToDevice, stream) != hipSuccess ||
+    if (hipMemcpyAsync(device_workspace, sp->p.ws_image.data(), sp->p.ws_image.size() * sizeof(int32_t),
+                       hipMemcpyHostToDevice, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) {
       delete sp;
       return SVD_ERR_HIP;
@@ -210,7 +276,8 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
             if (g.mode == mode && !heavy) heavy = &g;
         }
         if (heavy) {
-          const long long items = static_cast<long long>(sp->p.n_q_blocks) * heavy->heads.size() * desc->B;
+          const long long items = static_cast<long long>(sp->p.n_q_blocks) * heavy->heads.size() * desc->B *
+                                  (heavy->mode == SVD_DENSE ? sp->dense_split : 1);
           const long long tail = items % n_cu;
           sp->concurrent = tail != 0 && 2 * tail < n_cu;
         }
@@ -224,6 +291,12 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
 svd_status svd_plan_destroy(svd_plan* plan) {
   if (!plan) return SVD_ERR_NULL;
   delete plan;
+  return SVD_OK;
+}
+
+svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split) {
+  if (!plan || !dense_split) return SVD_ERR_NULL;
+  *dense_split = plan->dense_split;
   return SVD_OK;
 }
 
@@ -337,8 +410,9 @@ svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* com
   return SVD_OK;
 }
 
-static svd_status launch_group(const Plan& p, const svd::Group& g, const void* q, const void* k,
+static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const void* q, const void* k,
                                const void* v, void* out, hipStream_t stream) {
+  const Plan& p = sp.p;
   const int* ws = static_cast<const int*>(p.device_workspace);
   svd::AttnLaunch a = base_launch(p.desc, q, k, v, out);
   a.n_q_blocks = p.n_q_blocks;
@@ -354,7 +428,13 @@ static svd_status launch_group(const Plan& p, const svd::Group& g, const void* q
   } else {
     const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
                       : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+    if (g.mode == SVD_DENSE && sp.dense_split > 1) {
+      a.split = sp.dense_split;
+      a.n_items *= a.split;
+      a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.partial_offset);
+    }
     err = svd::launch_attention(a, kmode, stream);
+    if (err == hipSuccess && a.split > 1) err = svd::launch_combine(a, stream);
   }
   return err == hipSuccess ? SVD_OK : SVD_ERR_HIP;
 }
@@ -382,7 +462,7 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
       if (g.mode == mode && n < 5) seq[n++] = &g;
   if (!plan->concurrent || n < 2) {
     for (int i = 0; i < n; ++i)
-      if (svd_status st = launch_group(p, *seq[i], q, k, v, out, main_stream)) return st;
+      if (svd_status st = launch_group(*plan, *seq[i], q, k, v, out, main_stream)) return st;
     return SVD_OK;
   }
   // fork: the first group stays on the caller's stream, the others go round-robin
@@ -399,7 +479,7 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
         used[k_side] = true;
       }
     }
-    if (svd_status st = launch_group(p, *seq[i], q, k, v, out, s)) return st;
+    if (svd_status st = launch_group(*plan, *seq[i], q, k, v, out, s)) return st;
   }
   for (int i = 0; i < kSideStreams; ++i) {
     if (!used[i]) continue;
@@ -415,7 +495,7 @@ svd_status svd_attn_forward_group(const svd_plan* plan, int32_t group, const voi
   if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
   const Plan& p = plan->p;
   if (group < 0 || group >= static_cast<int32_t>(p.groups.size())) return SVD_ERR_SHAPE;
-  return launch_group(p, p.groups[group], q, k, v, out, static_cast<hipStream_t>(hip_stream));
+  return launch_group(*plan, p.groups[group], q, k, v, out, static_cast<hipStream_t>(hip_stream));
 }
 
 svd_status svd_dense_attn_forward(const void* q, const void* k, const void* v, void* out,

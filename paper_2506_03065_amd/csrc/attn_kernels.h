@@ -40,10 +40,21 @@ struct AttnLaunch {
   const int* ws;         // device: workspace base (int32 words)
   int list_table;        // word offset of the group's list records
   float scale_log2e;     // log2(e) / sqrt(D)
+  // Key-range split of dense items (split > 1): an item is (query tile, head,
+  // batch entry, chunk); chunk c covers key tiles [c*n/split, (c+1)*n/split) and
+  // leaves its unnormalised accumulators, reference exponent and row sums in
+  // `partial`; a second kernel merges the chunks and writes out.
+  int split;             // 1 = off; n_items counts chunks
+  float* partial;        // device: partial_floats(...) floats, or nullptr
 };
+
+// Floats of scratch one split launch needs (n_items counts chunks).
+size_t partial_floats(int D, int n_items);
 
 void kernel_blocks(int D, int* block_q, int* block_k);
 hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream);
 hipError_t launch_zero_heads(const AttnLaunch& p, hipStream_t stream);
+// Merges the chunks of a split dense launch (same AttnLaunch) into `out`.
+hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream);
 
 }  // namespace svd

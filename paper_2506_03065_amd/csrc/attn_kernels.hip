@@ -103,7 +103,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (item >= p.n_items) return;
   const int qblk = item % p.n_q_blocks;
-  const int hb = item / p.n_q_blocks;
+  const int chunk = (item / p.n_q_blocks) % p.split;   // key-range chunk (dense launches only)
+  const int hb = item / p.n_q_blocks / p.split;
   const int hg = hb % p.n_heads;
   const int b = hb / p.n_heads;
   const int head = p.heads ? p.heads[hg] : hg;
@@ -123,12 +124,15 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 
   // ---- the list this head walks ----
   int n_tiles = 0;
+  int t_base = 0;                               // DENSE: first key tile of this item's chunk
   const int2* __restrict__ entries = nullptr;  // BAND
   const int2* __restrict__ runs = nullptr;     // BAND
   const int* __restrict__ cols = nullptr;      // GATHER
   int n_cols = 0;
   if (MODE == MODE_DENSE) {
-    n_tiles = (L + BC - 1) / BC;
+    const int n_all = (L + BC - 1) / BC;
+    t_base = chunk * n_all / p.split;
+    n_tiles = (chunk + 1) * n_all / p.split - t_base;
   } else {
     const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
     if (MODE == MODE_BAND) {
@@ -237,7 +241,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         reg[u] = *reinterpret_cast<const u32x4*>(src_b + off);
       }
     } else {
-      const unsigned tile_off = (unsigned)((MODE == MODE_BAND ? entries[t].x : t) * BC) * stride_bytes;
+      const unsigned tile_off = (unsigned)((MODE == MODE_BAND ? entries[t].x : t + t_base) * BC) * stride_bytes;
       const char* base_b = src_b + tile_off;
       const unsigned lim = g_last - tile_off;
 #pragma unroll
@@ -341,7 +345,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
       }
     } else {
       // dense: keys past L in the last tile; gather: padding of the column list
-      const int limit = MODE == MODE_DENSE ? L - t * BC : n_cols - t * BC;
+      const int limit = MODE == MODE_DENSE ? L - (t + t_base) * BC : n_cols - t * BC;
       changed = true;
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2)
@@ -554,6 +558,20 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     stage(Int<0>{}, TailMask{}, Int<0>{}, t, s_a, s_b);
   }
 
+  // ---- split launch: leave the chunk's state for the merge kernel, register by
+  // register (each a coalesced 256-byte row of the wave) ----
+  if (MODE == MODE_DENSE && p.split > 1) {
+    static_assert(MODE != MODE_DENSE || QB == 1, "the split path keeps one 32-row block per wave");
+    float* dst = p.partial + ((size_t)item * NW + wave) * ((DB * 16 + 2) * 64) + lane;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dst[(db * 16 + i) * 64] = o[db][0][i];
+    dst[(DB * 16) * 64] = -nm[0][0];      // reference exponent of this chunk
+    dst[(DB * 16 + 1) * 64] = l4[0][0];   // row sum relative to it
+    return;
+  }
+
   // ---- epilogue: O = O^T / l, bf16, lane owns query l32: 4 consecutive d per store ----
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -579,6 +597,54 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 
 #undef SVD_LOAD
 #undef SVD_STORE
+
+// Merge of a split dense launch: work-group = (query tile, head, batch entry),
+// same thread-to-element mapping as attn_fwd_kernel.  Chunks are folded one by
+// one with the online-softmax rule: O = O * 2^(m - m') + O_c * 2^(m_c - m').
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64) combine_partials_kernel(const AttnLaunch p) {
+  constexpr int DB = D / 32;
+  constexpr int BR = NW * 32;
+  const int qblk = blockIdx.x % p.n_q_blocks;
+  const int hb = blockIdx.x / p.n_q_blocks;
+  const int hg = hb % p.n_heads;
+  const int b = hb / p.n_heads;
+  const int head = p.heads ? p.heads[hg] : hg;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  float o[DB * 16];
+#pragma unroll
+  for (int r = 0; r < DB * 16; ++r) o[r] = 0.f;
+  float m = kNegInf, l = 0.f;
+  for (int c = 0; c < p.split; ++c) {
+    const size_t item = ((size_t)hb * p.split + c) * p.n_q_blocks + qblk;
+    const float* src = p.partial + (item * NW + wave) * ((DB * 16 + 2) * 64) + lane;
+    const float mc = src[(DB * 16) * 64], lc = src[(DB * 16 + 1) * 64];
+    const float m_new = fmaxf(m, mc);
+    const float wa = __builtin_amdgcn_exp2f(m - m_new), wc = __builtin_amdgcn_exp2f(mc - m_new);
+    l = l * wa + lc * wc;
+#pragma unroll
+    for (int r = 0; r < DB * 16; ++r) o[r] = o[r] * wa + src[r * 64] * wc;
+    m = m_new;
+  }
+  const float inv = 1.0f / l;
+  const int row = qblk * BR + wave * 32 + l32;
+  if (row < p.L) {
+    __bf16* dst = p.out + (int64_t)b * p.stride_b + (int64_t)head * p.stride_h + (int64_t)row * p.stride_l;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x2 a01 = {o[db * 16 + g * 4 + 0] * inv, o[db * 16 + g * 4 + 1] * inv};
+        const f32x2 a23 = {o[db * 16 + g * 4 + 2] * inv, o[db * 16 + g * 4 + 3] * inv};
+        const bf16x2 b01 = __builtin_convertvector(a01, bf16x2);
+        const bf16x2 b23 = __builtin_convertvector(a23, bf16x2);
+        const bf16x4 out4 = {b01[0], b01[1], b23[0], b23[1]};
+        *reinterpret_cast<bf16x4*>(dst + db * 32 + g * 8 + half * 4) = out4;
+      }
+    }
+  }
+}
 
 // M_1 (Section 4.2): the output of a skipped head is zero.
 __global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
@@ -630,10 +696,30 @@ void kernel_blocks(int D, int* block_q, int* block_k) {
 
 hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream) {
   if (p.n_items <= 0) return hipSuccess;
+  if (p.split < 1 || (p.split > 1 && (mode != MODE_DENSE || !p.partial))) return hipErrorInvalidValue;
   if (p.D == 128)
     return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC, Tile128::OCC>(p, mode, stream);
   if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC, Tile64::OCC>(p, mode, stream);
   return hipErrorInvalidValue;
+}
+
+size_t partial_floats(int D, int n_items) {
+  const int nw = D == 128 ? Tile128::NW : Tile64::NW;
+  return (size_t)n_items * nw * ((D / 32 * 16 + 2) * 64);
+}
+
+hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream) {
+  if (p.split <= 1 || p.n_items <= 0) return hipSuccess;
+  if (!p.partial) return hipErrorInvalidValue;
+  const dim3 grid(p.n_items / p.split);
+  if (p.D == 128) {
+    hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW>), grid, dim3(Tile128::NW * 64), 0, stream, p);
+  } else if (p.D == 64) {
+    hipLaunchKernelGGL((combine_partials_kernel<64, Tile64::NW>), grid, dim3(Tile64::NW * 64), 0, stream, p);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_zero_heads(const AttnLaunch& p, hipStream_t stream) {

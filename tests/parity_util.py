@@ -18,12 +18,14 @@ def f64(t):
     return t.detach().cpu().to(torch.float64).numpy()
 
 
-def run_planned(wl, q, k, v, out=None):
+def run_planned(wl, q, k, v, out=None, dense_split=0):
     """q, k, v: CUDA bf16 [B, H, L, D] (any strides with contiguous D)."""
     desc = svd.desc_of(q)
-    nbytes = svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params)
+    nbytes = svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=dense_split)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
-    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, dense_split=dense_split)
+    if dense_split > 1:
+        assert plan.dense_split() >= 1
     if out is None:
         out = torch.full_like(q, float("nan"))
     svd.svd_attn_forward_planned(plan, q, k, v, out)

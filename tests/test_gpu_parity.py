@@ -185,3 +185,36 @@ def test_peaked_scores_move_the_softmax_reference(D, profile):
     q, k, v = _cuda([q, k, v])
     out = run_planned(wl, q, k, v)
     check_layer(wl, q, k, v, out)
+
+
+@pytest.mark.parametrize("L,D,split", [(1000, 64, 2), (1000, 64, 3), (1000, 128, 5), (777, 128, 8), (130, 64, 8),
+                                       (60, 128, 4)])
+def test_dense_key_range_split(L, D, split):
+    """Dense heads computed in `split` key-range chunks and merged (forced through
+    the plan option; chunk counts above the number of key tiles are capped)."""
+    wl = W.small(L=L, D=D, H=5, seed=51, B=2)
+    q, k, v = _cuda(W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, dense_split=split,
+                               workspace=torch.empty(svd.svd_plan_workspace_bytes(
+                                   desc, wl.strategy_table, wl.pattern_params, dense_split=split),
+                                   dtype=torch.uint8, device=DEV))
+    n_key_tiles = -(-L // svd.svd_default_blocks(D)[1])
+    assert plan.dense_split() == min(split, n_key_tiles)
+    plan.close()
+    out = run_planned(wl, q, k, v, dense_split=split)
+    check_layer(wl, q, k, v, out)
+
+
+def test_dense_split_with_peaked_scores():
+    """Chunks whose reference exponents differ by hundreds must merge exactly."""
+    L, D = 1500, 64
+    wl = W.small(L=L, D=D, H=5, seed=52)
+    q, k, v = W.make_qkv(wl)
+    gain = 0.25 + 2.75 * torch.arange(L, dtype=torch.float32) / L
+    u = torch.ones(D)
+    q = (0.3 * q.float() + 2.0 * u).to(torch.bfloat16)
+    k = (0.3 * k.float() + gain[None, None, :, None] * u).to(torch.bfloat16)
+    q, k, v = _cuda([q, k, v])
+    out = run_planned(wl, q, k, v, dense_split=4)
+    check_layer(wl, q, k, v, out)
