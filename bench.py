@@ -5,7 +5,7 @@ A step is one forward pass of the whole layer: the fused launch of every mode
 group of the per-head strategy table plus the zero fill of skipped heads, on
 Q/K/V already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|wan2.1|stack]
 """
 import argparse
 import json
@@ -75,6 +75,70 @@ def cpu_baseline(wl, q, k, v, out, budget_s, torch, np):
                       f"already widened; scaled by L/rows and H/heads"}, max_err, sum_err / max(n_err, 1)
 
 
+def run_stack(args, torch, np, svd, W):
+    """The 40-layer stack at the Wan2.1-like shape: one plan per layer, built once;
+    a step is one forward pass of all 40 attention layers (the same Q/K/V serve
+    every layer: kernel time does not depend on the values)."""
+    dev = "cuda:0"
+    n_layers = 40
+    layers = [W.stack_layer(i, n_layers) for i in range(n_layers)]
+    wl0 = layers[0]
+    q, k, v = (t.to(dev) for t in W.make_qkv(wl0))
+    out = torch.empty_like(q)
+    desc = svd.desc_of(q)
+    t0 = time.perf_counter()
+    plans, spaces = [], []
+    for wl in layers:
+        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params),
+                         dtype=torch.uint8, device=dev)
+        plans.append(svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws))
+        spaces.append(ws)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+
+    def step():
+        for plan in plans:
+            svd.svd_attn_forward_planned(plan, q, k, v, out)
+    t_warm = time.perf_counter()
+    while time.perf_counter() - t_warm < 1.5:
+        svd.svd_attn_forward_planned(plans[-1], q, k, v, out)
+        torch.cuda.synchronize()
+    steps, warmup = max(1, min(args.steps, 3)), max(1, min(args.warmup, 1))
+    ms_per_step = gpu_time_ms(step, steps, warmup, torch)
+    per_layer = [gpu_time_ms(lambda p=p: svd.svd_attn_forward_planned(p, q, k, v, out), 2, 1, torch) for p in plans]
+    dense_out = torch.empty_like(q)
+    dense_ms = gpu_time_ms(lambda: svd.svd_dense_attn_forward(q, k, v, dense_out), max(1, args.dense_reps), 1, torch)
+    del dense_out
+    work = [p.work() for p in plans]
+    computed = sum(w["computed_flops"] for w in work)
+    dense_flops = wl0.dense_flops * n_layers
+    cpu = None
+    if args.cpu_seconds > 0:
+        mid = layers[n_layers // 2]
+        svd.svd_attn_forward_planned(plans[n_layers // 2], q, k, v, out)
+        torch.cuda.synchronize()
+        cpu, max_err, mean_err = cpu_baseline(mid, q, k, v, out, args.cpu_seconds, torch, np)
+        cpu["value"] *= n_layers
+        cpu["sample"] += f"; layer {n_layers // 2} of the stack, times {n_layers} layers"
+    dense_heads = [int((wl.strategy_table == 0).sum()) for wl in layers]
+    result = {
+        "metric": "sparse-attn layer latency", "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "layer-stack (40 layers, Wan2.1-like shape)", "B": wl0.B, "H": wl0.H, "L": wl0.L,
+                   "D": wl0.D, "dense_heads_first_last": [dense_heads[0], dense_heads[-1]]},
+        "computed_tile_tflops": round(computed / 1e9 / ms_per_step, 1),
+        "computed_tile_frac_of_bf16_peak": round(computed / 1e9 / ms_per_step / BF16_MFMA_PEAK_TFLOPS, 4),
+        "dense_all_heads_ms": round(dense_ms * n_layers, 1),
+        "speedup_vs_dense_kernel": round(dense_ms * n_layers / ms_per_step, 3),
+        "flop_reduction_block_level": round(dense_flops / computed, 3),
+        "per_layer_ms": [round(x, 2) for x in per_layer],
+        "plan_create_ms": round(plan_ms, 1),
+        "roofline": None,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +166,9 @@ def main():
     svd.lib()   # fails loudly if the HIP library is not built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "stack":
+        run_stack(args, torch, np, svd, W)
+        return
     wl = W.BY_NAME[args.workload]()
     t0 = time.perf_counter()
     q, k, v = (t.to(dev) for t in W.make_qkv(wl))

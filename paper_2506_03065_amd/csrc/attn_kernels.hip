@@ -345,17 +345,17 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
       }
     } else {
       // dense: keys past L in the last tile; gather: padding of the column list
-      const int limit = MODE == MODE_DENSE ? L - (t + t_base) * BC : n_cols - t * BC;
+      // (the lane-dependent part goes into the limit so that every element is
+      // compared with a literal and nothing per element is kept across tiles)
+      const int limit = (MODE == MODE_DENSE ? L - (t + t_base) * BC : n_cols - t * BC) - half * 4;
       changed = true;
 #pragma unroll
       for (int kb2 = 0; kb2 < KB2; ++kb2)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int j = kb2 * 32 + half * 4 + (i / 4) * 8 + (i % 4);
-            s[kb2][qb][i] = j < limit ? s[kb2][qb][i] : kNegInf;
-          }
+          for (int i = 0; i < 16; ++i)
+            s[kb2][qb][i] = kb2 * 32 + (i / 4) * 8 + (i % 4) < limit ? s[kb2][qb][i] : kNegInf;
     }
     return changed;
   };
@@ -477,22 +477,24 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 
   // One pipeline stage.  On entry s_cur holds the raw scores of tile t; LDS holds
   // K(t+1) in K buffer (t+1)&1 and V(t) in V buffer t&1, while K(t+2) and V(t+1)
-  // travel global -> registers -> LDS.  MASK: 0 = tile t is wholly kept, 1 =
-  // mask it, 2 = decided per tile (band lists).  NEXT: 1 = a tile t + 1 is known
+  // travel global -> registers -> LDS.  NEXT: 1 = a tile t + 1 is known
   // to exist, 0 = tile t is the last one.  With NEXT the two products and the
   // exponentials sit in one basic block: the matrix pipe computes the scores of
   // tile t + 1 and then O += P V of tile t while the vector pipe turns the
   // scores of tile t into P.
-  auto stage = [&](auto par_tag, auto mask_tag, auto next_tag, const int t, f32x16 (&s_cur)[KB2][QB],
+  auto stage = [&](auto par_tag, auto next_tag, const int t, f32x16 (&s_cur)[KB2][QB],
                    f32x16 (&s_next)[KB2][QB]) {
     constexpr int PAR = decltype(par_tag)::value;     // t & 1
-    constexpr int MASK = decltype(mask_tag)::value;
     constexpr bool has1 = decltype(next_tag)::value != 0;
     const bool has2 = t + 2 < n_tiles;
     if (has2) SVD_LOAD(kreg, K, t + 2);
     if (has1) SVD_LOAD(vreg, V, t + 1);
-    bool masked = MASK == 1;
-    if (MASK == 2) masked = !(entries[t].y & 1);
+    // partly kept tile?  band lists flag it per entry; the dense and gather loops
+    // can only meet one at the very end (keys past L, padding of the column list)
+    bool masked;
+    if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+    else if (MODE == MODE_DENSE) masked = (t + t_base + 1) * BC > L;
+    else masked = (t + 1) * BC > n_cols;
     if (masked && apply_mask(s_cur, t)) tile_max(s_cur);   // the maximum taken before masking may belong to a dropped key
     settle_max(s_cur);
     bf16x8 pf[KB2][2][QB];
@@ -542,20 +544,16 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   };
 
   // Two stages per trip keep buffer indices and the score registers static.
-  // Band lists decide per entry whether to mask; the dense and gather loops can
-  // only meet a partly valid tile at the very end.
-  using MainMask = Int<MODE == MODE_BAND ? 2 : 0>;
-  using TailMask = Int<MODE == MODE_BAND ? 2 : 1>;
   int t = 0;
   for (; t + 2 < n_tiles; t += 2) {
-    stage(Int<0>{}, MainMask{}, Int<1>{}, t, s_a, s_b);
-    stage(Int<1>{}, MainMask{}, Int<1>{}, t + 1, s_b, s_a);
+    stage(Int<0>{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<1>{}, t + 1, s_b, s_a);
   }
   if (t + 1 < n_tiles) {
-    stage(Int<0>{}, MainMask{}, Int<1>{}, t, s_a, s_b);
-    stage(Int<1>{}, TailMask{}, Int<0>{}, t + 1, s_b, s_a);
+    stage(Int<0>{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<0>{}, t + 1, s_b, s_a);
   } else if (t < n_tiles) {
-    stage(Int<0>{}, TailMask{}, Int<0>{}, t, s_a, s_b);
+    stage(Int<0>{}, Int<0>{}, t, s_a, s_b);
   }
 
   // ---- split launch: leave the chunk's state for the merge kernel, register by
