@@ -22,7 +22,9 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 # summarised under profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: the
 # factors a 1 GiB streaming kernel in the same runs gives).  Counters cannot be
 # read from inside this process, so the figure is carried here per workload.
-PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 280909 + 21600) * 1024}}
+# Dense group of the CogVideoX1.5-like layer = the attention kernel over three
+# key-range chunks plus the merge kernel: (2*321023 + 251472) + (2*68978 + 21616) KiB.
+PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 321023 + 251472 + 2 * 68978 + 21616) * 1024}}
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
@@ -255,6 +257,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
+                   "dense_split": plan.dense_split(),
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
         "wall_ms_per_step": round(wall_ms, 4),
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),
