@@ -41,6 +41,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -125,8 +126,13 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   // ---- the list this head walks ----
   int n_tiles = 0;
   int t_base = 0;                               // DENSE: first key tile of this item's chunk
-  const int2* __restrict__ entries = nullptr;  // BAND
-  const int2* __restrict__ runs = nullptr;     // BAND
+  // The band lists are read through the constant address space: the plan's
+  // workspace is never written by a kernel, and loads with a uniform address
+  // from that space are scalar loads, which neither queue behind nor wait for
+  // the tile loads in flight.
+  typedef const i32x2 __attribute__((address_space(4)))* const_int2_ptr;
+  const_int2_ptr entries = nullptr;   // BAND
+  const_int2_ptr runs = nullptr;      // BAND
   const int* __restrict__ cols = nullptr;      // GATHER
   int n_cols = 0;
   if (MODE == MODE_DENSE) {
@@ -138,8 +144,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     if (MODE == MODE_BAND) {
       const int* row_ptr = p.ws + rec[0];
       const int e0 = row_ptr[qblk], e1 = row_ptr[qblk + 1];
-      entries = reinterpret_cast<const int2*>(p.ws + rec[1]) + e0;
-      runs = reinterpret_cast<const int2*>(p.ws + rec[2]);
+      entries = (const_int2_ptr)(uintptr_t)(p.ws + rec[1]) + e0;
+      runs = (const_int2_ptr)(uintptr_t)(p.ws + rec[2]);
       n_tiles = e1 - e0;
     } else {
       cols = p.ws + rec[0];
@@ -207,55 +213,66 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     for (int i = 0; i < 8; ++i) sum_a[i] = v;
   }
 
-  // ---- tile loaders: global -> registers -> LDS, K and V separately ----
-  // Thread `tid` moves chunks g = u * NT + tid: row g / CH = r0 + u * (NT / CH),
-  // 16-byte chunk c0 = tid % CH (the same for every u).  A tile is addressed as a
-  // uniform base (scalar registers) plus a per-thread 32-bit byte offset; rows
-  // past L - 1 (ragged last tile) are bent back onto row L - 1 by clamping that
-  // offset, and masked later.
-  static_assert(NT % CH == 0, "a thread keeps its chunk column");
-  constexpr int RSTEP = NT / CH;   // rows between consecutive chunks of a thread
+  // ---- tile loader: direct global -> LDS loads (global_load_lds_dwordx4: 16 bytes
+  // per lane, a wave instruction fills 1 KB of LDS linearly from a uniform base,
+  // no staging registers).  Wave w fills the slabs w*LPT .. w*LPT+LPT-1 of a tile.
+  // The XOR swizzle is applied on the global side: the lane that fills chunk
+  // slot c' of row r fetches chunk c' ^ swz(r) of that key row, so K and V use
+  // different per-lane offsets.  A tile is addressed as a uniform base (scalar
+  // registers) plus those 32-bit offsets; only a ragged last tile recomputes
+  // them with the row clamped to L - 1 (those rows are masked later). ----
+  constexpr int LPT = TILE_BYTES / (NW * 1024);   // load instructions per wave, tile and matrix
+  static_assert(TILE_BYTES % (NW * 1024) == 0, "tile must split evenly over the waves");
+  typedef __attribute__((address_space(3))) void* lds_ptr;
+  typedef __attribute__((address_space(1))) const void* glb_ptr;
   const unsigned stride_bytes = (unsigned)p.stride_l * 2u;
-  const int ld_r0 = tid / CH, ld_c0 = tid % CH;
-  u32x4 kreg[NCH], vreg[NCH];
-  int st_off_k[NCH], st_off_v[NCH];
+  unsigned g_k[LPT], g_v[LPT];   // DENSE, BAND: byte offset inside the tile; GATHER: chunk offset inside the row
+  unsigned g_r[LPT];             // GATHER: 4 * row of the slab's lane inside the tile
 #pragma unroll
-  for (int u = 0; u < NCH; ++u) {
-    const int r = ld_r0 + u * RSTEP;
-    st_off_k[u] = r * ROW_BYTES + ((ld_c0 ^ swz_k<D>(r)) << 4);
-    st_off_v[u] = r * ROW_BYTES + ((ld_c0 ^ swz_v<D>(r)) << 4);
+  for (int u = 0; u < LPT; ++u) {
+    const int byte = (wave * LPT + u) * 1024 + lane * 16;
+    const int r = byte / ROW_BYTES, slot = (byte % ROW_BYTES) >> 4;
+    const unsigned ck = (unsigned)(slot ^ swz_k<D>(r)) * 16u, cv = (unsigned)(slot ^ swz_v<D>(r)) * 16u;
+    g_r[u] = (unsigned)r * 4u;
+    g_k[u] = MODE == MODE_GATHER ? ck : (unsigned)r * stride_bytes + ck;
+    g_v[u] = MODE == MODE_GATHER ? cv : (unsigned)r * stride_bytes + cv;
   }
-  const unsigned g_off0 = MODE == MODE_GATHER ? (unsigned)ld_r0 * 4u
-                                              : (unsigned)ld_r0 * stride_bytes + (unsigned)ld_c0 * 16u;
-  const unsigned g_last = (unsigned)(L - 1) * stride_bytes + (unsigned)ld_c0 * 16u;   // same chunk of row L - 1
-  auto load_tile = [&](u32x4 (&reg)[NCH], const __bf16* __restrict__ src, const int t) {
-    const char* src_b = reinterpret_cast<const char*>(src);
+  auto load_tile = [&](auto is_k_tag, const int buf, const int t) {
+    constexpr bool IS_K = decltype(is_k_tag)::value != 0;
+    const char* src_b = reinterpret_cast<const char*>(IS_K ? K : V);
+    unsigned char* dst = (IS_K ? sK : sV) + buf * TILE_BYTES + wave * (LPT * 1024);
     if (MODE == MODE_GATHER) {
       // key rows come from the head's column list (-1 = padding: any valid row, masked later)
       const char* list = reinterpret_cast<const char*>(cols + t * BC);
 #pragma unroll
-      for (int u = 0; u < NCH; ++u) {
-        int c = *reinterpret_cast<const int*>(list + (g_off0 + (unsigned)(u * RSTEP * 4)));
+      for (int u = 0; u < LPT; ++u) {
+        int c = *reinterpret_cast<const int*>(list + g_r[u]);
         c = c < 0 ? 0 : c;
-        const unsigned off = __umul24((unsigned)c, stride_bytes) + (unsigned)ld_c0 * 16u;
-        reg[u] = *reinterpret_cast<const u32x4*>(src_b + off);
+        const unsigned off = __umul24((unsigned)c, stride_bytes) + (IS_K ? g_k[u] : g_v[u]);
+        __builtin_amdgcn_global_load_lds((glb_ptr)(src_b + off), (lds_ptr)(dst + u * 1024), 16, 0, 0);
       }
     } else {
-      const unsigned tile_off = (unsigned)((MODE == MODE_BAND ? entries[t].x : t + t_base) * BC) * stride_bytes;
-      const char* base_b = src_b + tile_off;
-      const unsigned lim = g_last - tile_off;
+      const int row0 = (MODE == MODE_BAND ? entries[t].x : t + t_base) * BC;
+      const char* base_b = src_b + (unsigned)row0 * stride_bytes;
+      if (row0 + BC <= L) {
 #pragma unroll
-      for (int u = 0; u < NCH; ++u) {
-        unsigned off = g_off0 + (unsigned)(u * RSTEP) * stride_bytes;
-        off = off < lim ? off : lim;
-        reg[u] = *reinterpret_cast<const u32x4*>(base_b + off);
+        for (int u = 0; u < LPT; ++u)
+          __builtin_amdgcn_global_load_lds((glb_ptr)(base_b + (IS_K ? g_k[u] : g_v[u])), (lds_ptr)(dst + u * 1024), 16,
+                                           0, 0);
+      } else {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+          const int byte = (wave * LPT + u) * 1024 + lane * 16;
+          int r = byte / ROW_BYTES;
+          const int slot = (byte % ROW_BYTES) >> 4;
+          const unsigned c = (unsigned)(slot ^ (IS_K ? swz_k<D>(r) : swz_v<D>(r))) * 16u;
+          r = r < L - 1 - row0 ? r : L - 1 - row0;
+          __builtin_amdgcn_global_load_lds((glb_ptr)(base_b + ((unsigned)r * stride_bytes + c)), (lds_ptr)(dst + u * 1024),
+                                           16, 0, 0);
+        }
       }
     }
   };
-#define SVD_LOAD(REG, PTR, T) load_tile(REG, PTR, (T));
-#define SVD_STORE(REG, SBASE, OFF, BUF)                                                   \
-  _Pragma("unroll") for (int u = 0; u < NCH; ++u)                                         \
-    *reinterpret_cast<u32x4*>(SBASE + (BUF) * TILE_BYTES + OFF[u]) = REG[u];
 
   // per-lane LDS read offsets (everything else is an immediate)
   int k_off[KS];   // K fragment: key l32 of a 32-key block, chunk 2 * ks + half
@@ -299,7 +316,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   auto apply_mask = [&](f32x16 (&s)[KB2][QB], const int t) -> bool {
     bool changed = false;
     if (MODE == MODE_BAND) {
-      const int2 ent = entries[t];
+      const i32x2 ent = entries[t];
       const int kv0 = ent.x * BC;
       const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
       const int qw0 = __builtin_amdgcn_readfirstlane(q0);
@@ -310,7 +327,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
           const int jb0 = kv0 + kb2 * 32;                      // first key of the block
           const int dmin = jb0 - (qw0 + qb * 32) - 31, dmax = dmin + 62;   // diagonals the block touches
           if (rn == 1) {
-            const int2 run = runs[r0];
+            const i32x2 run = runs[r0];
             if (dmin >= run.x && dmax <= run.y && jb0 + 31 < L) continue;   // kept as a whole
             changed = true;
             if (dmax < run.x || dmin > run.y || jb0 >= L) {                    // dropped as a whole
@@ -326,7 +343,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 #pragma unroll
           for (int i = 0; i < 16; ++i) kept[i] = kNegInf;
           for (int r = r0; r < r0 + rn; ++r) {
-            const int2 run = runs[r];
+            const i32x2 run = runs[r];
             // kept iff run.x <= j - iq <= run.y and j < L
             int hi = run.y;
             hi = hi < L - 1 - iq ? hi : L - 1 - iq;
@@ -460,14 +477,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   // ---- prologue: K(0), V(0), K(1) into LDS, scores of tile 0 ----
   f32x16 s_a[KB2][QB], s_b[KB2][QB];
   if (n_tiles > 0) {
-    SVD_LOAD(kreg, K, 0);
-    SVD_LOAD(vreg, V, 0);
-    SVD_STORE(kreg, sK, st_off_k, 0);
-    SVD_STORE(vreg, sV, st_off_v, 0);
-    if (n_tiles > 1) {
-      SVD_LOAD(kreg, K, 1);
-      SVD_STORE(kreg, sK, st_off_k, 1);
-    }
+    load_tile(Int<1>{}, 0, 0);
+    load_tile(Int<0>{}, 0, 0);
+    if (n_tiles > 1) load_tile(Int<1>{}, 1, 1);
   }
   __syncthreads();
   if (n_tiles > 0) {
@@ -487,8 +499,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     constexpr int PAR = decltype(par_tag)::value;     // t & 1
     constexpr bool has1 = decltype(next_tag)::value != 0;
     const bool has2 = t + 2 < n_tiles;
-    if (has2) SVD_LOAD(kreg, K, t + 2);
-    if (has1) SVD_LOAD(vreg, V, t + 1);
+    if (has2) load_tile(Int<1>{}, PAR, t + 2);       // K(t+2) takes the place of K(t), read in the last stage
+    if (has1) load_tile(Int<0>{}, PAR ^ 1, t + 1);   // V(t+1) takes the place of V(t-1)
     // partly kept tile?  band lists flag it per entry; the dense and gather loops
     // can only meet one at the very end (keys past L, padding of the column list)
     bool masked;
@@ -534,12 +546,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         }
       }
     }
-    // Nothing may move across this point: the LDS stores below wait for the
-    // global loads issued at the top of the stage, and must not be hoisted
-    // into the block above (that would expose the whole load latency).
-    __builtin_amdgcn_sched_barrier(0);
-    if (has2) SVD_STORE(kreg, sK, st_off_k, PAR);
-    if (has1) SVD_STORE(vreg, sV, st_off_v, PAR ^ 1);
+    // the loads issued at the top of the stage must have landed before anyone reads them
     __syncthreads();
   };
 
@@ -593,8 +600,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   }
 }
 
-#undef SVD_LOAD
-#undef SVD_STORE
 
 // Merge of a split dense launch: work-group = (query tile, head, batch entry),
 // same thread-to-element mapping as attn_fwd_kernel.  Chunks are folded one by
