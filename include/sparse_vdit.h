@@ -196,6 +196,59 @@ svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
 svd_status svd_dense_attn_forward(const void* q, const void* k, const void* v, void* out,
                                   const svd_tensor_desc* desc, void* hip_stream);
 
+/* ---- Offline search step (Section 4.2 "Offline Sparse Diffusion Search", Eq. 2-3,
+ * Algorithm 1): all five modes run on the same Q, K, V; per head and sparse mode
+ * i = 1..4 the loss is L_i = MSE(O_i - O_0) + lambda * (1 - S_i) (Eq. 2; the
+ * listing of Algorithm 1 prints lambda * S_i, the equation and its text are
+ * followed); a head keeps mode 0 when all four losses exceed epsilon, else it
+ * takes the arg-min mode, lower id on ties (Eq. 3). ---- */
+
+/* Bytes of device scratch svd_head_mse needs for this shape.  Host only. */
+svd_status svd_head_mse_workspace_bytes(const svd_tensor_desc* desc, size_t* bytes);
+
+/* MSE(O_i - O_0) per head: mse[h] = mean over batch, tokens and channels of
+ * (o - o_ref)^2.  o, o_ref: DEVICE bf16 tensors of layout desc; mse: DEVICE
+ * float[H]; device_workspace: DEVICE scratch of svd_head_mse_workspace_bytes.
+ * Two kernels with a fixed summation order (same bits on every run); enqueued
+ * on hip_stream, no synchronisation. */
+svd_status svd_head_mse(const void* o, const void* o_ref, const svd_tensor_desc* desc, float* mse,
+                        void* device_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* S_i of Eq. 2 for every head of a plan: the share of the L x L attention map the
+ * head's mode leaves out (0 dense, 1 skip, element-level count for the patterns).
+ * sparsity: HOST double[H]. */
+svd_status svd_plan_head_sparsity(const svd_plan* plan, double* sparsity);
+
+/* Eq. 2 and Eq. 3 on the host.  mse (float) and sparsity (double) are HOST arrays
+ * of 4 * H values, row i - 1 = mode i; table: HOST int32[H], out; loss: HOST
+ * double[4 * H], out, may be NULL. */
+svd_status svd_search_select(int32_t H, const float* mse, const double* sparsity, double lambda, double epsilon,
+                             int32_t* table, double* loss);
+
+/* x^o of Algorithm 1: out[:, h] = o_modes[table[h]][:, h].  o_modes: HOST array of
+ * five DEVICE tensors of layout src_desc (entries of modes the table does not use
+ * may be NULL); table: HOST int32[H]; out: DEVICE tensor of layout out_desc (same
+ * shape).  H <= 1024. */
+svd_status svd_select_heads(const void* const* o_modes, const svd_tensor_desc* src_desc, const int32_t* table,
+                            void* out, const svd_tensor_desc* out_desc, void* hip_stream);
+
+/* One layer of the search (the loop body of Algorithm 1 between "Attention Part"
+ * and "FFN Part").  params_by_mode: HOST array of five pointers, entries 2, 3, 4 =
+ * the H candidate parameter sets of the diagonal, multi-diagonal and vertical
+ * mode (entries 0, 1 unused).  Runs mode i on all heads for i = 0..4 with the
+ * library's kernels, reduces the four MSEs, applies Eq. 2-3, writes the chosen
+ * outputs to out and returns table (HOST int32[H]) and loss (HOST double[4 * H],
+ * may be NULL).  q, k, v, out must be contiguous [B, H, L, D].  device_workspace:
+ * svd_search_layer_workspace_bytes bytes, 256-byte aligned (five output tensors +
+ * one plan + scratch).  Unlike the forward entry points this call SYNCHRONISES
+ * hip_stream: the losses are needed on the host. */
+svd_status svd_search_layer_workspace_bytes(const svd_tensor_desc* desc,
+                                            const svd_head_params* const* params_by_mode, size_t* bytes);
+svd_status svd_search_layer(const void* q, const void* k, const void* v, const svd_tensor_desc* desc,
+                            const svd_head_params* const* params_by_mode, double lambda, double epsilon,
+                            int32_t* table, double* loss, void* out, void* device_workspace,
+                            size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* svd_status_string(svd_status status);
 

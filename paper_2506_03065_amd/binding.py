@@ -25,7 +25,9 @@ SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
            "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_band_list", "svd_plan_column_list",
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
-           "svd_dense_attn_forward", "svd_status_string"]
+           "svd_dense_attn_forward", "svd_status_string",
+           "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
+           "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer"]
 
 
 class SvdError(RuntimeError):
@@ -78,6 +80,15 @@ def lib():
             "svd_attn_forward_group": [vp, C.c_int32, vp, vp, vp, vp, vp],
             "sparse_vdit_attn_forward": [vp, vp, vp, i32p, hpp, vp, descp, vp, C.c_size_t, vp],
             "svd_dense_attn_forward": [vp, vp, vp, vp, descp, vp],
+            "svd_head_mse_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
+            "svd_head_mse": [vp, vp, descp, vp, vp, C.c_size_t, vp],
+            "svd_plan_head_sparsity": [vp, C.POINTER(C.c_double)],
+            "svd_search_select": [C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_double), C.c_double, C.c_double,
+                                  i32p, C.POINTER(C.c_double)],
+            "svd_select_heads": [C.POINTER(vp), descp, i32p, vp, descp, vp],
+            "svd_search_layer_workspace_bytes": [descp, C.POINTER(hpp), C.POINTER(C.c_size_t)],
+            "svd_search_layer": [vp, vp, vp, descp, C.POINTER(hpp), C.c_double, C.c_double, i32p,
+                                 C.POINTER(C.c_double), vp, vp, C.c_size_t, vp],
         }
         for name, args in sig.items():
             fn = getattr(_lib, name)
@@ -179,6 +190,12 @@ class Plan:
             pass
 
     # ---- inspection ----
+    def head_sparsity(self):
+        out = np.zeros(self.desc.H, dtype=np.float64)
+        _check(lib().svd_plan_head_sparsity(self.handle, out.ctypes.data_as(C.POINTER(C.c_double))),
+               "svd_plan_head_sparsity")
+        return out
+
     def dense_split(self) -> int:
         n = C.c_int32()
         _check(lib().svd_plan_dense_split(self.handle, C.byref(n)), "svd_plan_dense_split")
@@ -281,3 +298,73 @@ def svd_dense_attn_forward(q, k, v, out, stream=None):
     _check(lib().svd_dense_attn_forward(_dev(q), _dev(k), _dev(v), _dev(out), C.byref(desc), _stream_ptr(stream)),
            "svd_dense_attn_forward")
     return out
+
+
+# ---- offline search step (Section 4.2, Eq. 2-3, Algorithm 1) ----
+
+def svd_head_mse_workspace_bytes(desc) -> int:
+    n = C.c_size_t()
+    _check(lib().svd_head_mse_workspace_bytes(C.byref(desc), C.byref(n)), "svd_head_mse_workspace_bytes")
+    return n.value
+
+
+def svd_head_mse(o, o_ref, mse, workspace, stream=None):
+    """o, o_ref: CUDA bf16 [B, H, L, D]; mse: CUDA float32 [H] (written); workspace: CUDA scratch."""
+    desc = desc_of(o)
+    _check(lib().svd_head_mse(_dev(o), _dev(o_ref), C.byref(desc), _dev(mse), _dev(workspace),
+                              workspace.numel() * workspace.element_size(), _stream_ptr(stream)), "svd_head_mse")
+    return mse
+
+
+def svd_search_select(mse, sparsity, lam, eps):
+    """mse, sparsity: [4, H] (row i - 1 = mode i).  Returns (table int32 [H], loss float64 [4, H])."""
+    mse = np.ascontiguousarray(np.asarray(mse, dtype=np.float32))
+    sparsity = np.ascontiguousarray(np.asarray(sparsity, dtype=np.float64))
+    H = mse.shape[1]
+    table = np.zeros(H, dtype=np.int32)
+    loss = np.zeros((4, H), dtype=np.float64)
+    _check(lib().svd_search_select(H, mse.ctypes.data_as(C.POINTER(C.c_float)),
+                                   sparsity.ctypes.data_as(C.POINTER(C.c_double)), float(lam), float(eps),
+                                   _ptr(table), loss.ctypes.data_as(C.POINTER(C.c_double))), "svd_search_select")
+    return table, loss
+
+
+def svd_select_heads(o_modes, table, out, stream=None):
+    """o_modes: five CUDA tensors (None where the table does not use the mode); out[:, h] = o_modes[table[h]][:, h]."""
+    first = next(t for t in o_modes if t is not None)
+    src_desc, out_desc = desc_of(first), desc_of(out)
+    ptrs = (C.c_void_p * 5)(*[C.c_void_p(t.data_ptr()) if t is not None else None for t in o_modes])
+    table = _i32(table)
+    _check(lib().svd_select_heads(ptrs, C.byref(src_desc), _ptr(table), _dev(out), C.byref(out_desc),
+                                  _stream_ptr(stream)), "svd_select_heads")
+    return out
+
+
+def _params_by_mode(params_by_mode, H):
+    """dict mode id (2, 3, 4) -> H parameter dicts  ->  (array of five HeadParams pointers, keep-alive list)."""
+    keep, arr = [], (C.POINTER(HeadParams) * 5)()
+    for mode in (2, 3, 4):
+        m = _Marshalled(np.full(H, mode, dtype=np.int32), params_by_mode[mode])
+        keep.append(m)
+        arr[mode] = C.cast(m.params, C.POINTER(HeadParams))
+    return arr, keep
+
+
+def svd_search_layer_workspace_bytes(desc, params_by_mode) -> int:
+    arr, keep = _params_by_mode(params_by_mode, desc.H)
+    n = C.c_size_t()
+    _check(lib().svd_search_layer_workspace_bytes(C.byref(desc), arr, C.byref(n)), "svd_search_layer_workspace_bytes")
+    return n.value
+
+
+def svd_search_layer(q, k, v, params_by_mode, lam, eps, out, workspace, stream=None):
+    """Returns (table int32 [H], loss float64 [4, H]); out receives the chosen outputs.  Synchronises."""
+    desc = desc_of(q)
+    arr, keep = _params_by_mode(params_by_mode, desc.H)
+    table = np.zeros(desc.H, dtype=np.int32)
+    loss = np.zeros((4, desc.H), dtype=np.float64)
+    _check(lib().svd_search_layer(_dev(q), _dev(k), _dev(v), C.byref(desc), arr, float(lam), float(eps), _ptr(table),
+                                  loss.ctypes.data_as(C.POINTER(C.c_double)), _dev(out), _dev(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "svd_search_layer")
+    return table, loss

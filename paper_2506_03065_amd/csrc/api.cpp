@@ -14,6 +14,7 @@
 
 #include "attn_kernels.h"
 #include "plan.h"
+#include "search_kernels.h"
 #include "sparse_vdit.h"
 
 // A launchable plan owns a few side streams and events: the groups of a layer
@@ -545,6 +546,205 @@ svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
     g_oneshot.workspace_bytes = workspace_bytes;
   }
   return svd_attn_forward_planned(g_oneshot.plan, q, k, v, out, hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// Offline search step (Section 4.2 "Offline Sparse Diffusion Search", Eq. 2-3,
+// Algorithm 1)
+// ---------------------------------------------------------------------------
+
+static svd::TensorView view_of(const svd_tensor_desc& d) {
+  return svd::TensorView{d.B, d.H, d.L, d.D, d.stride_b, d.stride_h, d.stride_l};
+}
+
+static svd_tensor_desc contiguous_desc(const svd_tensor_desc& d) {
+  svd_tensor_desc c = d;
+  c.stride_l = d.D;
+  c.stride_h = static_cast<int64_t>(d.L) * d.D;
+  c.stride_b = c.stride_h * d.H;
+  return c;
+}
+
+svd_status svd_head_mse_workspace_bytes(const svd_tensor_desc* desc, size_t* bytes) {
+  if (!desc || !bytes) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  *bytes = svd::mse_scratch_floats(view_of(*desc)) * sizeof(float);
+  return SVD_OK;
+}
+
+svd_status svd_head_mse(const void* o, const void* o_ref, const svd_tensor_desc* desc, float* mse,
+                        void* device_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!o || !o_ref || !desc || !mse) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  if (!aligned16(o) || !aligned16(o_ref)) return SVD_ERR_ALIGN;
+  const svd::TensorView t = view_of(*desc);
+  if (!device_workspace || workspace_bytes < svd::mse_scratch_floats(t) * sizeof(float) ||
+      (reinterpret_cast<uintptr_t>(device_workspace) & 3u))
+    return SVD_ERR_WORKSPACE;
+  const hipError_t e = svd::launch_head_mse(static_cast<const __bf16*>(o), static_cast<const __bf16*>(o_ref), t, mse,
+                                            static_cast<float*>(device_workspace), static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SVD_OK : SVD_ERR_HIP;
+}
+
+svd_status svd_plan_head_sparsity(const svd_plan* plan, double* sparsity) {
+  if (!plan || !sparsity) return SVD_ERR_NULL;
+  const Plan& p = plan->p;
+  const double all = static_cast<double>(p.desc.L) * static_cast<double>(p.desc.L);
+  for (const svd::Group& g : p.groups) {
+    for (size_t t = 0; t < g.heads.size(); ++t) {
+      double kept = 0.0;
+      if (g.mode == SVD_DENSE) kept = all;
+      else if (g.mode == SVD_DIAG || g.mode == SVD_MULTIDIAG) kept = g.bands[g.list_id[t]].kept_pairs;
+      else if (g.mode == SVD_VSTRIPE) kept = static_cast<double>(g.columns[g.list_id[t]].n_cols) * p.desc.L;
+      sparsity[g.heads[t]] = 1.0 - kept / all;
+    }
+  }
+  return SVD_OK;
+}
+
+svd_status svd_search_select(int32_t H, const float* mse, const double* sparsity, double lambda, double epsilon,
+                             int32_t* table, double* loss) {
+  if (!mse || !sparsity || !table) return SVD_ERR_NULL;
+  if (H < 1) return SVD_ERR_SHAPE;
+  static const int32_t sparse_modes[4] = {SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE};
+  for (int32_t h = 0; h < H; ++h) {
+    int above = 0, best = 0;
+    double best_loss = 0.0;
+    for (int i = 0; i < 4; ++i) {
+      const double l = static_cast<double>(mse[i * H + h]) + lambda * (1.0 - sparsity[i * H + h]);   // Eq. 2
+      if (loss) loss[i * H + h] = l;
+      if (l > epsilon) ++above;
+      if (i == 0 || l < best_loss) {   // strict: ties go to the lower mode id
+        best_loss = l;
+        best = i;
+      }
+    }
+    table[h] = above >= 4 ? SVD_DENSE : sparse_modes[best];   // Eq. 3
+  }
+  return SVD_OK;
+}
+
+svd_status svd_select_heads(const void* const* o_modes, const svd_tensor_desc* src_desc, const int32_t* table,
+                            void* out, const svd_tensor_desc* out_desc, void* hip_stream) {
+  if (!o_modes || !src_desc || !table || !out || !out_desc) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(src_desc)) return st;
+  if (svd_status st = svd::validate_desc(out_desc)) return st;
+  if (src_desc->B != out_desc->B || src_desc->H != out_desc->H || src_desc->L != out_desc->L ||
+      src_desc->D != out_desc->D)
+    return SVD_ERR_SHAPE;
+  if (src_desc->H > svd::kMaxSelectHeads) return SVD_ERR_UNSUPPORTED;
+  if (!aligned16(out)) return SVD_ERR_ALIGN;
+  const __bf16* src[5];
+  bool used[5] = {false, false, false, false, false};
+  for (int h = 0; h < src_desc->H; ++h) {
+    if (table[h] < SVD_DENSE || table[h] > SVD_VSTRIPE) return SVD_ERR_MODE;
+    used[table[h]] = true;
+  }
+  for (int m = 0; m < 5; ++m) {
+    if (used[m] && !o_modes[m]) return SVD_ERR_NULL;
+    if (o_modes[m] && !aligned16(o_modes[m])) return SVD_ERR_ALIGN;
+    src[m] = static_cast<const __bf16*>(o_modes[m]);
+  }
+  const hipError_t e = svd::launch_select_heads(src, view_of(*src_desc), table, static_cast<__bf16*>(out),
+                                                view_of(*out_desc), static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SVD_OK : SVD_ERR_HIP;
+}
+
+// Workspace of svd_search_layer: five contiguous output tensors, the largest
+// plan workspace of the five single-mode tables, the reduction scratch, and
+// 4 * H floats for the per-head MSEs.
+namespace {
+struct SearchLayout {
+  size_t out_bytes = 0, plan_off = 0, plan_bytes = 0, mse_scratch_off = 0, mse_off = 0, total = 0;
+};
+
+svd_status search_layout(const svd_tensor_desc& desc, const svd_head_params* const* params_by_mode, SearchLayout* lay) {
+  lay->out_bytes = align_up(static_cast<size_t>(desc.B) * desc.H * desc.L * desc.D * 2, 256);
+  std::vector<int32_t> table(desc.H);
+  std::vector<svd_head_params> none(desc.H);
+  for (int mode = SVD_SKIP; mode <= SVD_VSTRIPE; ++mode) {
+    std::fill(table.begin(), table.end(), mode);
+    const svd_head_params* pp = (mode >= SVD_DIAG) ? params_by_mode[mode] : none.data();
+    if (!pp) return SVD_ERR_NULL;
+    size_t bytes = 0;
+    const svd_tensor_desc c = contiguous_desc(desc);
+    if (svd_status st = svd_plan_workspace_bytes(&c, table.data(), pp, nullptr, &bytes)) return st;
+    lay->plan_bytes = bytes > lay->plan_bytes ? bytes : lay->plan_bytes;
+  }
+  lay->plan_bytes = align_up(lay->plan_bytes, 256);
+  lay->plan_off = 5 * lay->out_bytes;
+  lay->mse_scratch_off = lay->plan_off + lay->plan_bytes;
+  lay->mse_off = lay->mse_scratch_off + align_up(svd::mse_scratch_floats(view_of(desc)) * sizeof(float), 256);
+  lay->total = lay->mse_off + align_up(static_cast<size_t>(4) * desc.H * sizeof(float), 256);
+  return SVD_OK;
+}
+}  // namespace
+
+svd_status svd_search_layer_workspace_bytes(const svd_tensor_desc* desc,
+                                            const svd_head_params* const* params_by_mode, size_t* bytes) {
+  if (!desc || !params_by_mode || !bytes) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  SearchLayout lay;
+  if (svd_status st = search_layout(*desc, params_by_mode, &lay)) return st;
+  *bytes = lay.total;
+  return SVD_OK;
+}
+
+svd_status svd_search_layer(const void* q, const void* k, const void* v, const svd_tensor_desc* desc,
+                            const svd_head_params* const* params_by_mode, double lambda, double epsilon,
+                            int32_t* table, double* loss, void* out, void* device_workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  if (!desc || !params_by_mode || !table) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  if (svd_status st = check_tensors(q, k, v, out)) return st;
+  if (desc->H > svd::kMaxSelectHeads) return SVD_ERR_UNSUPPORTED;
+  SearchLayout lay;
+  if (svd_status st = search_layout(*desc, params_by_mode, &lay)) return st;
+  if (!device_workspace || workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(device_workspace) & 255u))
+    return SVD_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(device_workspace);
+  const int H = desc->H;
+  const svd_tensor_desc cdesc = contiguous_desc(*desc);
+  void* o_modes[5];
+  for (int m = 0; m < 5; ++m) o_modes[m] = ws + m * lay.out_bytes;
+
+  // The single-mode plans read q, k, v with the caller's strides and write the
+  // contiguous buffers: the kernels take one descriptor, so a strided input is
+  // only accepted when it is already contiguous.
+  if (std::memcmp(&cdesc, desc, sizeof(cdesc)) != 0) return SVD_ERR_UNSUPPORTED;
+
+  std::vector<int32_t> mode_table(H);
+  std::vector<svd_head_params> none(H);
+  std::vector<double> sparsity(static_cast<size_t>(4) * H);
+  float* mse_dev = reinterpret_cast<float*>(ws + lay.mse_off);
+  for (int mode = SVD_DENSE; mode <= SVD_VSTRIPE; ++mode) {
+    std::fill(mode_table.begin(), mode_table.end(), mode);
+    const svd_head_params* pp = (mode >= SVD_DIAG) ? params_by_mode[mode] : none.data();
+    if (mode == SVD_DENSE) {
+      if (svd_status st = svd_dense_attn_forward(q, k, v, o_modes[0], desc, hip_stream)) return st;
+      continue;
+    }
+    svd_plan* plan = nullptr;
+    if (svd_status st = svd_plan_create(&plan, desc, mode_table.data(), pp, nullptr, ws + lay.plan_off,
+                                        lay.plan_bytes, hip_stream))
+      return st;
+    svd_status st = svd_attn_forward_planned(plan, q, k, v, o_modes[mode], hip_stream);
+    if (st == SVD_OK) st = svd_plan_head_sparsity(plan, sparsity.data() + static_cast<size_t>(mode - 1) * H);
+    if (st == SVD_OK)
+      st = svd_head_mse(o_modes[mode], o_modes[0], desc, mse_dev + static_cast<size_t>(mode - 1) * H,
+                        ws + lay.mse_scratch_off, lay.mse_off - lay.mse_scratch_off, hip_stream);
+    // the next plan reuses the list area: everything of this one must have run
+    if (st == SVD_OK && hipStreamSynchronize(stream) != hipSuccess) st = SVD_ERR_HIP;
+    svd_plan_destroy(plan);
+    if (st != SVD_OK) return st;
+  }
+  std::vector<float> mse(static_cast<size_t>(4) * H);
+  if (hipMemcpyAsync(mse.data(), mse_dev, mse.size() * sizeof(float), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+      hipStreamSynchronize(stream) != hipSuccess)
+    return SVD_ERR_HIP;
+  if (svd_status st = svd_search_select(H, mse.data(), sparsity.data(), lambda, epsilon, table, loss)) return st;
+  return svd_select_heads(o_modes, &cdesc, table, out, desc, hip_stream);
 }
 
 }  // extern "C"
