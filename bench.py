@@ -5,7 +5,7 @@ A step is one forward pass of the whole layer: the fused launch of every mode
 group of the per-head strategy table plus the zero fill of skipped heads, on
 Q/K/V already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|wan2.1|stack]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|wan2.1|stack|search]
 """
 import argparse
 import json
@@ -141,6 +141,51 @@ def run_stack(args, torch, np, svd, W):
     print(json.dumps(result))
 
 
+def run_search(args, torch, np, svd, W):
+    """One layer of the offline search at the CogVideoX1.5-like shape: all five
+    modes on the same Q/K/V, four per-head MSE reductions, selection, assembly."""
+    dev = "cuda:0"
+    wl = W.BY_NAME["cogvideox1.5"]()
+    q, k, v = (t.to(dev) for t in W.make_qkv(wl))
+    out = torch.empty_like(q)
+    desc = svd.desc_of(q)
+    by_mode = {m: [None] * wl.H for m in (2, 3, 4)}
+    first = {m: next(p for h, p in enumerate(wl.pattern_params) if wl.strategy_table[h] == m) for m in (2, 3)}
+    vert = [p for h, p in enumerate(wl.pattern_params) if wl.strategy_table[h] == 4]
+    for h in range(wl.H):
+        by_mode[2][h], by_mode[3][h], by_mode[4][h] = first[2], first[3], vert[h % len(vert)]
+    ws = torch.empty(svd.svd_search_layer_workspace_bytes(desc, by_mode), dtype=torch.uint8, device=dev)
+    lam, eps = 0.5, 1.0
+    table, loss = svd.svd_search_layer(q, k, v, by_mode, lam, eps, out, ws)      # warm-up
+    steps = max(1, min(args.steps, 3))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        table, loss = svd.svd_search_layer(q, k, v, by_mode, lam, eps, out, ws)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps       # the call synchronises: wall clock is the time
+    # the reduction kernel on its own: reads two tensors once
+    mse = torch.empty(wl.H, dtype=torch.float32, device=dev)
+    mws = torch.empty(max(svd.svd_head_mse_workspace_bytes(desc), 4), dtype=torch.uint8, device=dev)
+    other = torch.empty_like(q).copy_(q)
+    mse_ms = gpu_time_ms(lambda: svd.svd_head_mse(out, other, mse, mws), 20, 3, torch)
+    nbytes = 2.0 * q.numel() * 2
+    sel_ms = gpu_time_ms(lambda: svd.svd_select_heads([q, k, v, other, out], table, out), 20, 3, torch)
+    result = {
+        "metric": "search-step latency (five modes + four reductions + selection, one layer)",
+        "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1, "steps": steps, "warmup": 1,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "search step, " + wl.name, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
+                   "lambda": lam, "epsilon": eps},
+        "table_counts": {MODE_NAMES[m]: int((table == m).sum()) for m in range(5)},
+        "head_mse_ms": round(mse_ms, 4), "select_heads_ms": round(sel_ms, 4),
+        "roofline": {"bound": "hbm", "kernel": "head_mse_partial_kernel", "achieved": round(nbytes / 1e6 / mse_ms, 1),
+                     "peak": 8000.0, "unit": "GB/s", "frac": round(nbytes / 1e6 / mse_ms / 8000.0, 4), "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,6 +215,9 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "stack":
         run_stack(args, torch, np, svd, W)
+        return
+    if args.workload == "search":
+        run_search(args, torch, np, svd, W)
         return
     wl = W.BY_NAME[args.workload]()
     t0 = time.perf_counter()

@@ -11,7 +11,10 @@ namespace {
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMseThreads = 256;
-constexpr int kMseChunkBytes = 1 << 20;   // of one tensor, per work-group
+#ifndef SVD_MSE_CHUNK
+#define SVD_MSE_CHUNK (1 << 18)
+#endif
+constexpr int kMseChunkBytes = SVD_MSE_CHUNK;   // of one tensor, per work-group
 
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
@@ -30,16 +33,31 @@ __global__ void __launch_bounds__(kMseThreads) head_mse_partial_kernel(const __b
   const int64_t g0 = (int64_t)blockIdx.x * per;
   const int64_t g1 = g0 + per < total ? g0 + per : total;
   float acc = 0.f;
-  for (int64_t g = g0 + threadIdx.x; g < g1; g += kMseThreads) {
+  auto piece = [&](const int64_t g, u32x4* x, u32x4* y) {
     const int64_t off = base + (g / cpr) * t.stride_l + (g % cpr) * 8;
-    const u32x4 x = *reinterpret_cast<const u32x4*>(a + off);
-    const u32x4 y = *reinterpret_cast<const u32x4*>(ref + off);
+    *x = *reinterpret_cast<const u32x4*>(a + off);
+    *y = *reinterpret_cast<const u32x4*>(ref + off);
+  };
+  auto add = [&](const u32x4& x, const u32x4& y) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float d0 = bf16_lo(x[i]) - bf16_lo(y[i]), d1 = bf16_hi(x[i]) - bf16_hi(y[i]);
       acc = __builtin_fmaf(d0, d0, acc);
       acc = __builtin_fmaf(d1, d1, acc);
     }
+  };
+  int64_t g = g0 + threadIdx.x;
+  for (; g + 3 * kMseThreads < g1; g += 4 * kMseThreads) {   // eight loads in flight per thread
+    u32x4 x[4], y[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) piece(g + u * kMseThreads, &x[u], &y[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) add(x[u], y[u]);
+  }
+  for (; g < g1; g += kMseThreads) {
+    u32x4 x, y;
+    piece(g, &x, &y);
+    add(x, y);
   }
   // wave reduction, then the four waves through LDS, always in the same order
 #pragma unroll
