@@ -51,3 +51,59 @@ def test_plan_head_sparsity_small_mixed_layer():
     plan.close()
     want = [S.head_sparsity(int(wl.strategy_table[h]), wl.pattern_params[h], wl.L) for h in range(wl.H)]
     assert np.allclose(got, want, rtol=0, atol=1e-15)
+
+
+def test_search_entry_points_validate_before_any_launch():
+    """Bad arguments are turned into status codes on the host (fake 16-byte aligned
+    'device' addresses are never dereferenced)."""
+    import ctypes as C
+    lib = svd.lib()
+    d = svd.tensor_desc(1, 4, 100, 64)
+    p16, p8 = C.c_void_p(0x1000), C.c_void_p(0x1008)
+    n = C.c_size_t()
+    assert lib.svd_head_mse_workspace_bytes(C.byref(d), C.byref(n)) == 0 and n.value >= 16
+    assert lib.svd_head_mse_workspace_bytes(None, C.byref(n)) == 1
+    bad = svd.tensor_desc(1, 4, 100, 96)
+    assert lib.svd_head_mse_workspace_bytes(C.byref(bad), C.byref(n)) == 2
+    # svd_head_mse: null pointers, alignment, workspace too small
+    assert lib.svd_head_mse(None, p16, C.byref(d), p16, p16, 1 << 20, None) == 1
+    assert lib.svd_head_mse(p8, p16, C.byref(d), p16, p16, 1 << 20, None) == 4
+    assert lib.svd_head_mse(p16, p16, C.byref(d), p16, p16, 4, None) == 8
+    assert lib.svd_head_mse(p16, p16, C.byref(d), p16, None, 0, None) == 8
+    # svd_select_heads: bad mode id, missing source of a used mode, shape mismatch, too many heads
+    ptrs = (C.c_void_p * 5)(p16, p16, p16, None, p16)
+    table = np.array([0, 1, 2, 4], dtype=np.int32)
+    tp = table.ctypes.data_as(C.POINTER(C.c_int32))
+    bad_table = np.array([0, 1, 2, 7], dtype=np.int32)
+    assert lib.svd_select_heads(ptrs, C.byref(d), bad_table.ctypes.data_as(C.POINTER(C.c_int32)), p16, C.byref(d), None) == 5
+    need3 = np.array([0, 1, 3, 4], dtype=np.int32)
+    assert lib.svd_select_heads(ptrs, C.byref(d), need3.ctypes.data_as(C.POINTER(C.c_int32)), p16, C.byref(d), None) == 1
+    other = svd.tensor_desc(1, 4, 101, 64)
+    assert lib.svd_select_heads(ptrs, C.byref(d), tp, p16, C.byref(other), None) == 2
+    assert lib.svd_select_heads(ptrs, C.byref(d), tp, p8, C.byref(d), None) == 4
+    many = svd.tensor_desc(1, 1025, 16, 64)
+    big_table = np.zeros(1025, dtype=np.int32)
+    assert lib.svd_select_heads(ptrs, C.byref(many), big_table.ctypes.data_as(C.POINTER(C.c_int32)), p16,
+                                C.byref(many), None) == 9
+    # svd_search_layer: workspace size comes from the host; too small or misaligned workspaces and
+    # non-contiguous tensors are refused
+    params = {2: [{"half_width": 5}] * 4, 3: [{"half_width": 2, "offsets": (-30, 0, 30)}] * 4,
+              4: [{"cols": (1, 2, 3)}] * 4}
+    need = svd.svd_search_layer_workspace_bytes(d, params)
+    assert need >= 5 * 4 * 100 * 64 * 2
+    arr, keep = svd._params_by_mode(params, 4)
+    out_table = np.zeros(4, dtype=np.int32)
+    call = lambda desc, ws, nbytes: lib.svd_search_layer(p16, p16, p16, C.byref(desc), arr, 0.5, 1.0,
+                                                         out_table.ctypes.data_as(C.POINTER(C.c_int32)), None, p16,
+                                                         ws, nbytes, None)
+    assert call(d, C.c_void_p(0x10000), need - 1) == 8
+    assert call(d, C.c_void_p(0x10010), need) == 8          # not 256-byte aligned
+    assert call(d, None, need) == 8
+    strided = svd.tensor_desc(1, 4, 100, 64, stride_b=4 * 100 * 64, stride_h=64, stride_l=4 * 64)
+    assert call(strided, C.c_void_p(0x10000), 1 << 30) == 9
+    # a parameter set that leaves a row without keys is reported as such
+    empty = dict(params)
+    empty[3] = [{"half_width": 1, "offsets": (40,)}] * 4
+    with pytest.raises(svd.SvdError) as e:
+        svd.svd_search_layer_workspace_bytes(d, empty)
+    assert e.value.status == 7
