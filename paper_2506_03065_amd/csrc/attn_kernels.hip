@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps everything derived from it in scalar registers
   const int l32 = lane & 31;
   const int half = lane >> 5;
 
@@ -237,9 +237,16 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     g_k[u] = MODE == MODE_GATHER ? ck : (unsigned)r * stride_bytes + ck;
     g_v[u] = MODE == MODE_GATHER ? cv : (unsigned)r * stride_bytes + cv;
   }
-  auto load_tile = [&](auto is_k_tag, const int buf, const int t) {
+  // buffer resources of this head's K and V (raw buffers: base, byte range, no swizzle)
+  const unsigned head_bytes = (unsigned)(L - 1) * stride_bytes + (unsigned)ROW_BYTES;
+  const __amdgpu_buffer_rsrc_t rsrc_k = __builtin_amdgcn_make_buffer_rsrc((void*)K, 0, (int)head_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_v = __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)head_bytes, 0x00020000);
+  // INNER: the tile is known to lie inside [0, L) (anything but the last tile of a list)
+  auto load_tile = [&](auto is_k_tag, auto inner_tag, const int buf, const int t) {
     constexpr bool IS_K = decltype(is_k_tag)::value != 0;
+    constexpr bool INNER = decltype(inner_tag)::value != 0;
     const char* src_b = reinterpret_cast<const char*>(IS_K ? K : V);
+    const __amdgpu_buffer_rsrc_t rsrc = IS_K ? rsrc_k : rsrc_v;
     unsigned char* dst = (IS_K ? sK : sV) + buf * TILE_BYTES + wave * (LPT * 1024);
     if (MODE == MODE_GATHER) {
       // key rows come from the head's column list (-1 = padding: any valid row, masked later)
@@ -249,16 +256,16 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         int c = *reinterpret_cast<const int*>(list + g_r[u]);
         c = c < 0 ? 0 : c;
         const unsigned off = __umul24((unsigned)c, stride_bytes) + (IS_K ? g_k[u] : g_v[u]);
-        __builtin_amdgcn_global_load_lds((glb_ptr)(src_b + off), (lds_ptr)(dst + u * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dst + u * 1024), 16, (int)off, 0, 0, 0);
       }
     } else {
       const int row0 = (MODE == MODE_BAND ? entries[t].x : t + t_base) * BC;
       const char* base_b = src_b + (unsigned)row0 * stride_bytes;
-      if (row0 + BC <= L) {
+      if (INNER || row0 + BC <= L) {
 #pragma unroll
         for (int u = 0; u < LPT; ++u)
-          __builtin_amdgcn_global_load_lds((glb_ptr)(base_b + (IS_K ? g_k[u] : g_v[u])), (lds_ptr)(dst + u * 1024), 16,
-                                           0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dst + u * 1024), 16, (int)(IS_K ? g_k[u] : g_v[u]),
+                                                   (int)((unsigned)row0 * stride_bytes), 0, 0);
       } else {
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
@@ -267,8 +274,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
           const int slot = (byte % ROW_BYTES) >> 4;
           const unsigned c = (unsigned)(slot ^ (IS_K ? swz_k<D>(r) : swz_v<D>(r))) * 16u;
           r = r < L - 1 - row0 ? r : L - 1 - row0;
-          __builtin_amdgcn_global_load_lds((glb_ptr)(base_b + ((unsigned)r * stride_bytes + c)), (lds_ptr)(dst + u * 1024),
-                                           16, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dst + u * 1024), 16,
+                                                   (int)((unsigned)r * stride_bytes + c),
+                                                   (int)((unsigned)row0 * stride_bytes), 0, 0);
         }
       }
     }
@@ -477,9 +485,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   // ---- prologue: K(0), V(0), K(1) into LDS, scores of tile 0 ----
   f32x16 s_a[KB2][QB], s_b[KB2][QB];
   if (n_tiles > 0) {
-    load_tile(Int<1>{}, 0, 0);
-    load_tile(Int<0>{}, 0, 0);
-    if (n_tiles > 1) load_tile(Int<1>{}, 1, 1);
+    load_tile(Int<1>{}, Int<0>{}, 0, 0);
+    load_tile(Int<0>{}, Int<0>{}, 0, 0);
+    if (n_tiles > 1) load_tile(Int<1>{}, Int<0>{}, 1, 1);
   }
   __syncthreads();
   if (n_tiles > 0) {
@@ -494,17 +502,22 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   // exponentials sit in one basic block: the matrix pipe computes the scores of
   // tile t + 1 and then O += P V of tile t while the vector pipe turns the
   // scores of tile t into P.
-  auto stage = [&](auto par_tag, auto next_tag, const int t, f32x16 (&s_cur)[KB2][QB],
+  // INNER: t + 2 is not the last tile of the list.  Lists are ascending, so only
+  // their last tile can reach past L (or hold padding of a column list): an INNER
+  // stage loads without the ragged-tile test and, outside band lists, never masks.
+  auto stage = [&](auto par_tag, auto next_tag, auto inner_tag, const int t, f32x16 (&s_cur)[KB2][QB],
                    f32x16 (&s_next)[KB2][QB]) {
     constexpr int PAR = decltype(par_tag)::value;     // t & 1
     constexpr bool has1 = decltype(next_tag)::value != 0;
-    const bool has2 = t + 2 < n_tiles;
-    if (has2) load_tile(Int<1>{}, PAR, t + 2);       // K(t+2) takes the place of K(t), read in the last stage
-    if (has1) load_tile(Int<0>{}, PAR ^ 1, t + 1);   // V(t+1) takes the place of V(t-1)
+    constexpr bool INNER = decltype(inner_tag)::value != 0;
+    const bool has2 = INNER || t + 2 < n_tiles;
+    if (has2) load_tile(Int<1>{}, inner_tag, PAR, t + 2);       // K(t+2) takes the place of K(t), read in the last stage
+    if (has1) load_tile(Int<0>{}, inner_tag, PAR ^ 1, t + 1);   // V(t+1) takes the place of V(t-1)
     // partly kept tile?  band lists flag it per entry; the dense and gather loops
     // can only meet one at the very end (keys past L, padding of the column list)
     bool masked;
     if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+    else if (INNER) masked = false;
     else if (MODE == MODE_DENSE) masked = (t + t_base + 1) * BC > L;
     else masked = (t + 1) * BC > n_cols;
     if (masked && apply_mask(s_cur, t)) tile_max(s_cur);   // the maximum taken before masking may belong to a dropped key
@@ -546,21 +559,34 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         }
       }
     }
+    // The maximum of the next tile is used only in the next stage: without this
+    // anchor at the end of the block the compiler sinks the whole chain out of
+    // it, away from the MFMAs that hide it.
+    if (has1) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) asm volatile("" : "+v"(mx_raw[qb]));
+    }
     // the loads issued at the top of the stage must have landed before anyone reads them
     __syncthreads();
   };
 
   // Two stages per trip keep buffer indices and the score registers static.
+  // The bulk of a list runs through INNER stages (t + 3 is at most the last tile
+  // but one for both stages of the trip); the generic stages finish it.
   int t = 0;
+  for (; t + 5 <= n_tiles; t += 2) {
+    stage(Int<0>{}, Int<1>{}, Int<1>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<1>{}, Int<1>{}, t + 1, s_b, s_a);
+  }
   for (; t + 2 < n_tiles; t += 2) {
-    stage(Int<0>{}, Int<1>{}, t, s_a, s_b);
-    stage(Int<1>{}, Int<1>{}, t + 1, s_b, s_a);
+    stage(Int<0>{}, Int<1>{}, Int<0>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<1>{}, Int<0>{}, t + 1, s_b, s_a);
   }
   if (t + 1 < n_tiles) {
-    stage(Int<0>{}, Int<1>{}, t, s_a, s_b);
-    stage(Int<1>{}, Int<0>{}, t + 1, s_b, s_a);
+    stage(Int<0>{}, Int<1>{}, Int<0>{}, t, s_a, s_b);
+    stage(Int<1>{}, Int<0>{}, Int<0>{}, t + 1, s_b, s_a);
   } else if (t < n_tiles) {
-    stage(Int<0>{}, Int<0>{}, t, s_a, s_b);
+    stage(Int<0>{}, Int<0>{}, Int<0>{}, t, s_a, s_b);
   }
 
   // ---- split launch: leave the chunk's state for the merge kernel, register by
