@@ -23,8 +23,8 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 # factors a 1 GiB streaming kernel in the same runs gives).  Counters cannot be
 # read from inside this process, so the figure is carried here per workload.
 # Dense group of the CogVideoX1.5-like layer = the attention kernel over three
-# key-range chunks plus the merge kernel: (2*331653 + 255528) + (2*68979 + 21641) KiB.
-PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 331653 + 255528 + 2 * 68979 + 21641) * 1024}}
+# key-range chunks plus the merge kernel: (2*325302 + 243360) + (2*68979 + 21631) KiB.
+PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 325302 + 243360 + 2 * 68979 + 21631) * 1024}}
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
