@@ -17,12 +17,13 @@
 #include "search_kernels.h"
 #include "sparse_vdit.h"
 
-// A launchable plan owns a few side streams and events: the groups of a layer
-// are independent (they write different heads), so the forward pass forks them
-// onto side streams and joins them again on the caller's stream.  The GPU then
-// runs the group kernels concurrently and the work-groups of the lighter groups
-// fill the compute units that the last, partial round of a heavy group leaves
-// idle.  Streams keep the default priority.
+// A launchable plan owns a few side streams and events.  The groups of a layer
+// are independent (they write different heads); when the last, partial round of
+// work-groups of the heaviest group would leave most compute units idle, the
+// forward pass forks the groups onto the side streams and joins them again on
+// the caller's stream, so that the lighter groups fill those units.  Otherwise
+// the groups run one after the other on the caller's stream.  Streams keep the
+// default priority.
 constexpr int kSideStreams = 3;
 struct svd_plan {
   svd::Plan p;

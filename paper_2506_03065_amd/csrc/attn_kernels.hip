@@ -13,16 +13,20 @@
 // Per work-group: one tile of BR query rows of one head.  Online-softmax
 // recurrence over the listed key tiles; scores are computed TRANSPOSED,
 // S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a lane owns one query
-// column: the row maximum and row sum are per-lane scalars (one cross-half
-// exchange), and the exponentiated scores already sit in the operand layout of
-// the second product O^T += V^T P^T.  V^T fragments come from the row-major V
-// tile in LDS through the transposing LDS read (ds_read_b64_tr_b16).
-// Accumulation, scores and softmax are fp32; P is rounded to bf16 for the
-// second product.
+// column: the row maximum is a per-lane scalar (one cross-half exchange), and
+// the exponentiated scores already sit in the operand layout of the second
+// product O^T += V^T P^T.  V^T fragments come from the row-major V tile in LDS
+// through the transposing LDS read (ds_read_b64_tr_b16).  Accumulation, scores
+// and softmax are fp32; P is rounded to bf16 for the second product, and its
+// row sums are taken on the matrix pipe.
 //
-// The loop is software-pipelined inside each wave: while the VALU turns the
-// scores of tile t into P, the matrix pipe already computes the scores of tile
-// t + 1; K therefore runs one tile ahead of V through the LDS buffers.
+// K and V tiles travel global -> LDS directly (buffer loads with the LDS bit),
+// one tile ahead of their use.  The loop is software-pipelined inside each
+// wave: while the VALU turns the scores of tile t into P, the matrix pipe
+// already computes the scores of tile t + 1; K therefore runs one tile ahead of
+// V through the LDS buffers.  The vector work per score is one exp2, half a
+// conversion and half a max3: Q carries log2(e) / sqrt(D), and the score
+// accumulators are seeded with minus the reference exponent.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>

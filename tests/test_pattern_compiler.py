@@ -186,3 +186,22 @@ def test_host_only_plan_refuses_to_launch():
     st = svd.lib().svd_attn_forward_planned(plan.handle, ctypes.c_void_p(8), ctypes.c_void_p(16),
                                             ctypes.c_void_p(16), ctypes.c_void_p(16), None)
     assert st == 4
+
+
+def test_workspace_holds_lists_and_the_scratch_of_a_forced_dense_split():
+    """With dense_split forced the workspace is the list image, padded to 256
+    bytes, plus per chunk item and wave (D/2 + 2) rows of 64 floats."""
+    wl = W.small(L=1000, D=64, H=5, seed=3, B=2)
+    desc = svd.tensor_desc(wl.B, wl.H, wl.L, wl.D)
+    base = svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=1)
+    n_dense = int((wl.strategy_table == 0).sum())
+    bq, bk = svd.svd_default_blocks(wl.D)
+    for split in (2, 3, 8):
+        got = svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=split)
+        chunks = min(split, -(-wl.L // bk))
+        items = -(-wl.L // bq) * n_dense * wl.B * chunks
+        waves = bq // 32
+        want = -(-base // 256) * 256 + items * waves * (wl.D // 2 + 2) * 64 * 4
+        assert got == (want if n_dense else base)
+    with pytest.raises(svd.SvdError):
+        svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=-1)
