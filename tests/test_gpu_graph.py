@@ -1,0 +1,47 @@
+"""The forward pass recorded into a HIP graph: only kernel launches and
+event-based fork/join are enqueued, so a captured layer must replay to the
+same bits as the eager call, also with eager work between the replays."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_03065_amd import binding as svd
+from paper_2506_03065_amd import workloads as W
+from parity_util import check_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("L,D,split", [(1500, 64, 0), (900, 128, 2)])
+def test_captured_forward_replays_to_the_eager_bits(L, D, split):
+    wl = W.small(L=L, D=D, H=6, seed=71, B=2)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=split),
+                     dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, dense_split=split)
+    eager = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_planned(plan, q, k, v, eager)
+    torch.cuda.synchronize()
+    check_layer(wl, q, k, v, eager)
+
+    out = torch.full_like(q, float("nan"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        svd.svd_attn_forward_planned(plan, q, k, v, out)       # warm-up on the capture stream
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        svd.svd_attn_forward_planned(plan, q, k, v, out)       # the binding picks up the capturing stream
+    scratch = torch.empty(1 << 20, device=DEV)
+    for rep in range(4):
+        out.fill_(float("nan"))
+        scratch.normal_()                                      # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
+    del graph
+    plan.close()
