@@ -249,6 +249,31 @@ svd_status svd_search_layer(const void* q, const void* k, const void* v, const s
                             int32_t* table, double* loss, void* out, void* device_workspace,
                             size_t workspace_bytes, void* hip_stream);
 
+/* ---- FP8 variant (Appendix B, Table 4: "Sparse-vDiT + FP8") ----
+ * The paper combines the sparse kernels with FP8 quantisation but gives no
+ * recipe.  This library's reading: OCP E4M3 operands with fixed power-of-two
+ * scales, Q8 = e4m3(q * 4 log2(e) / sqrt(D)) (product in fp32), K8 = e4m3(k / 4),
+ * V8 = e4m3(v), P8 = e4m3(2^(Q8.K8 - m)) with the integer reference
+ * m = ceil(row max) - 8; values beyond +-448 saturate; scores, row sums and the
+ * output accumulate in fp32, the output is rounded to bf16.  Masks, modes and
+ * the plan are those of the bf16 path.
+ *
+ * svd_attn_forward_fp8: the layer of svd_attn_forward_planned in this
+ * arithmetic.  q, k, v, out: DEVICE bf16 tensors of the plan's descriptor.
+ * fp8_workspace: DEVICE scratch of svd_fp8_workspace_bytes(desc) bytes, 256-byte
+ * aligned, owned by the caller; the call fills it with the quantised keys and
+ * values of the layer (first half K8 [B][H][Lp][D] bytes, Lp = L rounded up to a
+ * multiple of 128; second half V8 [B][H][Lp/64][D][64], byte 32*h + 16*b + 4*g + r
+ * of a 64-byte record = key 32*b + 8*g + 4*h + r of the group of 64; keys past
+ * the head's key count are zero; a vertical-stripe head's arrays hold its listed
+ * columns in list order) and reads it back; nothing is kept between calls.  All
+ * launches go to hip_stream in order; the call does not synchronise and
+ * allocates nothing.  Errors as for svd_attn_forward_planned, plus
+ * SVD_ERR_WORKSPACE for a missing, small or misaligned fp8_workspace. */
+svd_status svd_fp8_workspace_bytes(const svd_tensor_desc* desc, size_t* bytes);
+svd_status svd_attn_forward_fp8(const svd_plan* plan, const void* q, const void* k, const void* v, void* out,
+                                void* fp8_workspace, size_t fp8_workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* svd_status_string(svd_status status);
 

@@ -67,6 +67,23 @@ def round_e4m3(x):
     return np.copysign(q, x)
 
 
+def rounding_margin(x):
+    """Relative distance of every element to the nearest point where round_e4m3
+    changes its result (the midpoint between two neighbouring E4M3 values);
+    infinite for zero.  A blocked fp32 implementation whose value differs from
+    the exact one by less than this margin takes the same rounding decision."""
+    a = np.minimum(np.abs(np.asarray(x, dtype=np.float64)), E4M3_MAX)
+    e = np.maximum(np.floor(np.log2(np.where(a > 0, a, 1.0))), -6.0)
+    units = a / np.exp2(e - 3.0)          # in [8, 16) for normal numbers, [0, 8) for subnormal ones
+    lo = np.floor(units)
+    up = lo + 0.5                          # midpoint towards the next value
+    # midpoint towards the previous value: the spacing halves below the bottom of a normal binade
+    down = np.where((lo == 8.0) & (e > -6.0), 7.75, lo - 0.5)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        m = np.minimum(np.abs(up - units), units - down) / units
+    return np.where(a > 0, m, np.inf)
+
+
 def quantise_q(q):
     """Q8 of the header: the score scale and log2(e) are folded in before rounding."""
     d = q.shape[-1]
@@ -82,31 +99,42 @@ def quantise_v(v):
     return round_e4m3(np.asarray(v, dtype=np.float64))
 
 
-def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0):
+def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0, with_margin=False):
     """The quantised row arithmetic of the header for operands already in E4M3.
 
     q8_rows [R, D], k8 [L, D], v8 [L, D] float64 holding E4M3 values, mask [R, L].
     shift: integer added to the reference (0 in the definition; the tests use it
     to show that the result does not depend on it).
+    with_margin: also return, per row, the smallest rounding_margin of the
+    probabilities that carry more than 1e-3 of the row's weight: how far the
+    row's result is from depending on the last bits of a score.
     """
     if not mask.any(axis=1).all():
         raise ValueError("a query row keeps no key")
     s2 = q8_rows @ k8.T
     s2[~mask] = -np.inf
     m = np.ceil(s2.max(axis=1, keepdims=True)) - P_HEADROOM + int(shift)
-    p8 = round_e4m3(np.exp2(s2 - m))
-    return (p8 @ v8) / p8.sum(axis=1, keepdims=True)
+    p = np.exp2(s2 - m)
+    p8 = round_e4m3(p)
+    den = p8.sum(axis=1, keepdims=True)
+    out = (p8 @ v8) / den
+    if not with_margin:
+        return out
+    margin = np.where(p8 > 1e-3 * den, rounding_margin(p), np.inf).min(axis=1)
+    return out, margin
 
 
-def attention_head_fp8(q, k, v, mode, params, rows=None, chunk=128):
-    """One head in the FP8 variant, all rows or the given rows.  q, k, v: [L, D]."""
+def attention_head_fp8(q, k, v, mode, params, rows=None, chunk=128, with_margin=False):
+    """One head in the FP8 variant, all rows or the given rows.  q, k, v: [L, D].
+    with_margin: also return the per-row margin of attention_rows_fp8."""
     L, d = q.shape
     rows = np.arange(L, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
     out = np.zeros((rows.size, d), dtype=np.float64)
-    if mode == SA.MODE_SKIP:
-        return out
-    q8, k8, v8 = quantise_q(q), quantise_k(k), quantise_v(v)
-    for s in range(0, rows.size, chunk):
-        r = rows[s:s + chunk]
-        out[s:s + chunk] = attention_rows_fp8(q8[r], k8, v8, SA.allowed_mask(mode, params, L, r))
-    return out
+    margin = np.full(rows.size, np.inf)
+    if mode != SA.MODE_SKIP:
+        q8, k8, v8 = quantise_q(q), quantise_k(k), quantise_v(v)
+        for s in range(0, rows.size, chunk):
+            r = rows[s:s + chunk]
+            out[s:s + chunk], margin[s:s + chunk] = attention_rows_fp8(
+                q8[r], k8, v8, SA.allowed_mask(mode, params, L, r), with_margin=True)
+    return (out, margin) if with_margin else out

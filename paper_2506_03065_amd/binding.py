@@ -27,7 +27,8 @@ EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", 
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
-           "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer"]
+           "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
+           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8"]
 
 
 class SvdError(RuntimeError):
@@ -89,6 +90,8 @@ def lib():
             "svd_search_layer_workspace_bytes": [descp, C.POINTER(hpp), C.POINTER(C.c_size_t)],
             "svd_search_layer": [vp, vp, vp, descp, C.POINTER(hpp), C.c_double, C.c_double, i32p,
                                  C.POINTER(C.c_double), vp, vp, C.c_size_t, vp],
+            "svd_fp8_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
+            "svd_attn_forward_fp8": [vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
         }
         for name, args in sig.items():
             fn = getattr(_lib, name)
@@ -274,6 +277,20 @@ def _dev(t):
 def svd_attn_forward_planned(plan: Plan, q, k, v, out, stream=None):
     _check(lib().svd_attn_forward_planned(plan.handle, _dev(q), _dev(k), _dev(v), _dev(out), _stream_ptr(stream)),
            "svd_attn_forward_planned")
+    return out
+
+
+def svd_fp8_workspace_bytes(desc) -> int:
+    n = C.c_size_t(0)
+    _check(lib().svd_fp8_workspace_bytes(C.byref(desc), C.byref(n)), "svd_fp8_workspace_bytes")
+    return int(n.value)
+
+
+def svd_attn_forward_fp8(plan: Plan, q, k, v, out, fp8_workspace, stream=None):
+    """fp8_workspace: uint8 CUDA tensor of svd_fp8_workspace_bytes(desc) bytes."""
+    _check(lib().svd_attn_forward_fp8(plan.handle, _dev(q), _dev(k), _dev(v), _dev(out), _dev(fp8_workspace),
+                                      fp8_workspace.numel() * fp8_workspace.element_size(), _stream_ptr(stream)),
+           "svd_attn_forward_fp8")
     return out
 
 

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "attn_kernels.h"
+#include "fp8_kernels.h"
 #include "plan.h"
 #include "search_kernels.h"
 #include "sparse_vdit.h"
@@ -746,6 +747,63 @@ svd_status svd_search_layer(const void* q, const void* k, const void* v, const s
     return SVD_ERR_HIP;
   if (svd_status st = svd_search_select(H, mse.data(), sparsity.data(), lambda, epsilon, table, loss)) return st;
   return svd_select_heads(o_modes, &cdesc, table, out, desc, hip_stream);
+}
+
+// ---- FP8 variant (Appendix B) ----
+
+svd_status svd_fp8_workspace_bytes(const svd_tensor_desc* desc, size_t* bytes) {
+  if (!desc || !bytes) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  *bytes = svd::fp8_scratch_bytes(desc->B, desc->H, desc->L, desc->D);
+  return SVD_OK;
+}
+
+svd_status svd_attn_forward_fp8(const svd_plan* plan, const void* q, const void* k, const void* v, void* out,
+                                void* fp8_workspace, size_t fp8_workspace_bytes, void* hip_stream) {
+  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  const Plan& p = plan->p;
+  const svd_tensor_desc& d = p.desc;
+  const size_t need = svd::fp8_scratch_bytes(d.B, d.H, d.L, d.D);
+  if (!fp8_workspace || fp8_workspace_bytes < need || (reinterpret_cast<uintptr_t>(fp8_workspace) & 255u))
+    return SVD_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int* ws = static_cast<const int*>(p.device_workspace);
+  static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
+  for (int mode : order) {
+    for (const svd::Group& g : p.groups) {
+      if (g.mode != mode) continue;
+      svd::Fp8Launch f{};
+      svd::AttnLaunch& a = f.a;
+      a = base_launch(d, q, k, v, out);
+      a.n_q_blocks = p.n_q_blocks;
+      a.n_heads = static_cast<int>(g.heads.size());
+      a.n_items = a.n_q_blocks * a.n_heads * a.B;
+      a.heads = ws + g.ws_heads;
+      a.list_id = ws + g.ws_list_id;
+      a.ws = ws;
+      a.list_table = static_cast<int>(g.ws_list_table);
+      if (g.mode == SVD_SKIP) {
+        if (svd::launch_zero_heads(a, stream) != hipSuccess) return SVD_ERR_HIP;
+        continue;
+      }
+      f.Lp = svd::fp8_padded_len(d.L);
+      f.k8 = static_cast<uint8_t*>(fp8_workspace);
+      f.v8t = f.k8 + need / 2;
+      const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
+                        : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+      // the pre-pass of a group runs right before its attention launch, so the
+      // quantised arrays of the group are read back while they are fresh in L2
+      if (svd::launch_quantise_kv(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
+      if (g.mode == SVD_DENSE && plan->dense_split > 1) {
+        a.split = plan->dense_split;
+        a.n_items *= a.split;
+        a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + plan->partial_offset);
+      }
+      if (svd::launch_attention_fp8(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
+      if (a.split > 1 && svd::launch_combine(a, stream) != hipSuccess) return SVD_ERR_HIP;
+    }
+  }
+  return SVD_OK;
 }
 
 }  // extern "C"

@@ -1,0 +1,223 @@
+"""GPU parity of the FP8 variant: the HIP path, called through the C ABI, against
+the quantise-dequantise oracle; the quantised arrays byte by byte."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp8_attention as F8
+from oracle import sparse_attention as O
+from paper_2506_03065_amd import binding as svd
+from paper_2506_03065_amd import workloads as W
+from parity_util import MEAN_ABS, REL_L2, assert_close, f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _cuda(ts):
+    return [t.to(DEV) for t in ts]
+
+
+def run_fp8(wl, q, k, v, dense_split=0, out=None):
+    desc = svd.desc_of(q)
+    nbytes = svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=dense_split)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, dense_split=dense_split)
+    ws8 = torch.full((svd.svd_fp8_workspace_bytes(desc),), 0x7f, dtype=torch.uint8, device=q.device)   # NaN bytes
+    if out is None:
+        out = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
+    torch.cuda.synchronize()
+    plan.close()
+    return out, ws8
+
+
+# A probability closer than this (relatively) to a midpoint between two E4M3 values
+# may round either way: the fp32 score of the matrix unit and the float64 score of
+# the oracle differ by a few 1e-6 (order of the sums, hardware exp2).
+MARGIN = 2e-5
+
+
+def check_layer_fp8(wl, q, k, v, out, rows=None, heads=None):
+    """Against the FP8 oracle.  Rows in which every probability of weight is
+    further than MARGIN from a rounding decision must meet the bar of the bf16
+    path element by element.  In the other rows a P may sit one E4M3 step
+    (relative 2^-3) away, which moves the row by at most weight / 8 * |v - o|:
+    they are held to 0.25 * max|V|, and all rows together to the mean and
+    relative-L2 bars."""
+    qc, kc, vc, oc = q.cpu(), k.cpu(), v.cpu(), out.cpu()
+    for b in range(wl.B):
+        for h in (range(wl.H) if heads is None else heads):
+            mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+            what = f"fp8 {wl.name} b{b} h{h} mode{mode}"
+            want, margin = F8.attention_head_fp8(f64(qc[b, h]), f64(kc[b, h]), f64(vc[b, h]), mode, p, rows=rows,
+                                                 with_margin=True)
+            got = f64(oc[b, h]) if rows is None else f64(oc[b, h][torch.as_tensor(rows)])
+            sure = margin > MARGIN
+            assert sure.mean() >= 0.8, f"{what}: only {sure.mean():.2f} of the rows are decided"
+            assert_close(got[sure], want[sure], what)
+            assert np.isfinite(got).all(), f"{what}: non-finite output"
+            diff = np.abs(got - want)
+            assert diff.max() <= 0.25 * np.abs(f64(vc[b, h])).max() + 1e-3, f"{what}: max abs {diff.max():.3e}"
+            assert diff.mean() <= MEAN_ABS, f"{what}: mean abs {diff.mean():.3e}"
+            if (want ** 2).sum() > 0:
+                rel = float(np.sqrt((diff ** 2).sum() / (want ** 2).sum()))
+                assert rel <= REL_L2, f"{what}: relative L2 {rel:.3e}"
+
+
+def decode(bytes_u8):
+    return bytes_u8.view(torch.float8_e4m3fn).to(torch.float64).cpu().numpy()
+
+
+@pytest.mark.parametrize("L,D", [(333, 64), (200, 128), (450, 128)])
+def test_quantised_arrays_byte_for_byte(L, D):
+    wl = W.small(L=L, D=D, H=5, seed=13, B=2)
+    q, k, v = _cuda(W.make_qkv(wl))
+    _, ws8 = run_fp8(wl, q, k, v)
+    Lp = (L + 127) // 128 * 128
+    k8 = decode(ws8[: ws8.numel() // 2]).reshape(wl.B, wl.H, Lp, D)
+    v8 = decode(ws8[ws8.numel() // 2:]).reshape(wl.B, wl.H, Lp // 64, D, 64)
+    # key of byte position 32*h + 16*blk + 4*g + r inside a group of 64
+    pos = np.arange(64)
+    h_, blk, g, r = pos // 32, (pos // 16) % 2, (pos // 4) % 4, pos % 4
+    key_of_pos = 32 * blk + 8 * g + 4 * h_ + r
+    assert sorted(key_of_pos) == list(range(64))
+    kc, vc = k.cpu(), v.cpu()
+    for b in range(wl.B):
+        for h in range(wl.H):
+            mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+            if mode == W.SKIP:
+                continue
+            src = np.unique(np.asarray(p["cols"])) if mode == W.VSTRIPE else np.arange(L)
+            n = len(src)
+            want_k = np.zeros((Lp, D))
+            want_v = np.zeros((Lp, D))
+            want_k[:n] = F8.quantise_k(f64(kc[b, h]))[src]
+            want_v[:n] = F8.quantise_v(f64(vc[b, h]))[src]
+            bk = svd.svd_default_blocks(D)[1]
+            n_pad = Lp if mode != W.VSTRIPE else (n + bk - 1) // bk * bk
+            np.testing.assert_array_equal(k8[b, h, :n_pad], want_k[:n_pad], err_msg=f"K8 b{b} h{h}")
+            got_v = np.zeros((Lp, D))
+            for G in range(n_pad // 64):
+                got_v[G * 64 + key_of_pos] = v8[b, h, G].T     # [64 positions, D] -> rows by key
+            np.testing.assert_array_equal(got_v[:n_pad], want_v[:n_pad], err_msg=f"V8 b{b} h{h}")
+
+
+def test_tiny_all_rows():
+    wl = W.tiny()
+    q, k, v = _cuda(W.make_qkv(wl))
+    out, _ = run_fp8(wl, q, k, v)
+    check_layer_fp8(wl, q, k, v, out)
+
+
+@pytest.mark.parametrize("L,D,H,seed,B", [(333, 64, 5, 7, 1), (200, 128, 5, 11, 1), (1000, 64, 5, 3, 1),
+                                           (1000, 128, 5, 4, 1), (77, 128, 4, 5, 1), (31, 64, 4, 6, 1),
+                                           (520, 128, 10, 8, 2), (700, 64, 5, 9, 2)])
+def test_small_ragged_all_rows(L, D, H, seed, B):
+    wl = W.small(L=L, D=D, H=H, seed=seed, B=B)
+    q, k, v = _cuda(W.make_qkv(wl))
+    out, _ = run_fp8(wl, q, k, v)
+    check_layer_fp8(wl, q, k, v, out)
+    for h in range(wl.H):
+        if wl.strategy_table[h] == W.SKIP:
+            assert not out[:, h].view(torch.int16).any(), "skipped head must be exact zeros"
+
+
+def test_close_to_the_unquantised_attention():
+    wl = W.small(L=600, D=128, H=5, seed=23)
+    q, k, v = _cuda(W.make_qkv(wl))
+    out, _ = run_fp8(wl, q, k, v)
+    qc, kc, vc, oc = q.cpu(), k.cpu(), v.cpu(), out.cpu()
+    for h in range(wl.H):
+        mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+        if mode == W.SKIP:
+            continue
+        want = O.attention_head(f64(qc[0, h]), f64(kc[0, h]), f64(vc[0, h]), mode, p)
+        got = f64(oc[0, h])
+        rel = np.sqrt(((got - want) ** 2).sum() / (want ** 2).sum())
+        assert rel < 0.08, (h, mode, rel)
+
+
+def test_closed_forms_constant_v_and_zero_q():
+    wl = W.small(L=900, D=128, H=5, seed=61)
+    q, k, v = _cuda(W.make_qkv(wl))
+    vc = torch.full_like(v, 0.625)      # representable in E4M3
+    out, _ = run_fp8(wl, q, k, vc)
+    for h in range(wl.H):
+        want = 0.0 if wl.strategy_table[h] == W.SKIP else 0.625
+        assert torch.allclose(out[0, h].float(), torch.full_like(out[0, h].float(), want), atol=4e-3)
+    # zero queries: every kept key has the same P, the output is the mean of the quantised V
+    out, _ = run_fp8(wl, torch.zeros_like(q), k, v)
+    v8 = F8.quantise_v(f64(v[0].cpu()))
+    for h in range(wl.H):
+        mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+        if mode == W.DENSE:
+            want = np.tile(v8[h].mean(axis=0), (wl.L, 1))
+        elif mode == W.VSTRIPE:
+            want = np.tile(v8[h][list(p["cols"])].mean(axis=0), (wl.L, 1))
+        else:
+            continue
+        assert_close(f64(out[0, h].cpu()), want, f"zero-q mean, head {h}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("profile", ["rising", "falling", "late_outlier", "very_negative"])
+def test_peaked_scores_move_the_reference(D, profile):
+    """Score profiles that move the integer reference many times, never after the
+    first tile, once by a large jump near the end, or that sit far below zero."""
+    L, H = 1500, 5
+    wl = W.small(L=L, D=D, H=H, seed=41)
+    q, k, v = W.make_qkv(wl)
+    j = torch.arange(L, dtype=torch.float32)
+    if profile == "rising":
+        gain = 0.25 + 2.75 * j / L
+    elif profile == "falling":
+        gain = 3.0 - 2.75 * j / L
+    elif profile == "late_outlier":
+        gain = torch.ones(L)
+        gain[L - 37] = 5.0
+    else:
+        gain = torch.full((L,), 8.0)
+    u = torch.nn.functional.normalize(torch.ones(D), dim=0) * (D ** 0.5)
+    sign = -1.0 if profile == "very_negative" else 1.0
+    q = (0.3 * q.float() + 2.0 * u).to(torch.bfloat16)
+    k = (0.3 * k.float() + sign * gain[None, None, :, None] * u).to(torch.bfloat16)
+    q, k, v = _cuda([q, k, v])
+    out, _ = run_fp8(wl, q, k, v)
+    check_layer_fp8(wl, q, k, v, out)
+
+
+@pytest.mark.parametrize("L,D,split", [(1000, 64, 3), (1000, 128, 5), (130, 64, 8)])
+def test_dense_key_range_split(L, D, split):
+    wl = W.small(L=L, D=D, H=5, seed=51, B=2)
+    q, k, v = _cuda(W.make_qkv(wl))
+    out, _ = run_fp8(wl, q, k, v, dense_split=split)
+    check_layer_fp8(wl, q, k, v, out)
+
+
+def test_strided_token_major_layout():
+    wl = W.small(L=450, D=64, H=5, seed=41)
+    q, k, v = _cuda(W.make_qkv(wl))
+    qs, ks, vs = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    out = torch.full_like(qs, float("nan"))
+    run_fp8(wl, qs, ks, vs, out=out)
+    check_layer_fp8(wl, q, k, v, out)
+
+
+def test_workspace_validation():
+    wl = W.small(L=300, D=64, H=5, seed=71)
+    q, k, v = _cuda(W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params), dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws)
+    out = torch.full_like(q, 3.0)
+    need = svd.svd_fp8_workspace_bytes(desc)
+    assert need == 2 * wl.B * wl.H * 384 * 64
+    ws8 = torch.empty(need + 256, dtype=torch.uint8, device=DEV)
+    for bad in (ws8[: need - 1], ws8[16: 16 + need]):      # too small, misaligned
+        with pytest.raises(svd.SvdError) as e:
+            svd.svd_attn_forward_fp8(plan, q, k, v, out, bad)
+        assert e.value.status == 8
+    torch.cuda.synchronize()
+    assert (out == 3.0).all()
+    plan.close()

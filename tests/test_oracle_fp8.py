@@ -64,6 +64,20 @@ def test_rounding_is_idempotent_and_odd():
     np.testing.assert_array_equal(F8.round_e4m3(-x), -r)
 
 
+def test_rounding_margin_is_the_distance_to_a_change_of_the_result():
+    rng = np.random.default_rng(8)
+    x = np.abs(rng.standard_normal(4000)) * np.exp2(rng.integers(-8, 8, 4000))
+    x = x[(x > 2.0 ** -9) & (x < 440)]
+    m = F8.rounding_margin(x)
+    r = F8.round_e4m3(x)
+    # inside the margin nothing changes, just beyond it (on one side) the result does
+    np.testing.assert_array_equal(F8.round_e4m3(x * (1 + 0.999 * m)), r)
+    np.testing.assert_array_equal(F8.round_e4m3(x * (1 - 0.999 * m)), r)
+    moved = (F8.round_e4m3(x * (1 + 1.001 * m)) != r) | (F8.round_e4m3(x * (1 - 1.001 * m)) != r)
+    assert moved.all()
+    assert F8.rounding_margin(np.array([0.0]))[0] == np.inf
+
+
 def test_operand_scales():
     rng = np.random.default_rng(3)
     d = 64
