@@ -54,7 +54,9 @@ constexpr float kE4M3Max = 448.0f;
 // Four floats to four E4M3 bytes, first argument in the lowest byte (round to
 // nearest even; the caller keeps the values inside +-448).
 __device__ __forceinline__ int pack_e4m3(float a, float b, float c, float d) {
-  int w = 0;
+  // the first conversion overwrites the low half of its destination and the second
+  // the high half: starting from the bits of `a` (dead afterwards) saves a move
+  int w = __builtin_bit_cast(int, a);
   w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, w, false);
   w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
   return w;
@@ -169,6 +171,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   constexpr int KS = D / 64;         // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;         // 32-row blocks of O^T
   constexpr int TILE_BYTES = BC * D;
+  constexpr bool DEEP = D == 128 && MODE == MODE_DENSE;   // pipeline shape, see the stages below
   constexpr int LPT = TILE_BYTES / (NW * 1024);   // load instructions per wave, tile and matrix
   static_assert(TILE_BYTES % (NW * 1024) == 0 && LPT >= 1, "tile must split evenly over the waves");
   static_assert(BC % 64 == 0, "key tiles are whole groups of 64");
@@ -407,11 +410,14 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   // ---- reference update.  When a tile exceeds the reference by more than 8 the
   // reference moves to ceil(row max) - 8, an integer: the scores already
   // computed and the accumulator seed shift by it, l and O scale by an exact
-  // power of two.  The branch is wave-uniform and rarely taken. ----
-  auto settle_max = [&](f32x16 (&s)[KB2]) {
+  // power of two.  The branch is wave-uniform and rarely taken.  `flush` runs
+  // first inside the branch: it adds what is still waiting to be accumulated
+  // under the old reference. ----
+  auto settle_max = [&](f32x16 (&s)[KB2], auto&& flush) {
     const float mx = half_max(mx_raw);
     const bool grow = mx > thr;   // false when the lane's tile is fully masked
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      flush();
       const float step = __builtin_ceilf(mx) - kHeadroom;
       const float delta = grow ? step : 0.f;
       const float alpha = (grow && thr != kNegInf) ? __builtin_amdgcn_exp2f(-step) : 1.0f;
@@ -464,89 +470,209 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
     }
   };
 
-  // ---- prologue: K(0), V(0), K(1) into LDS, scores of tile 0 ----
+  // Two pipeline shapes.  FLAT (two tiles deep, the shape of the bf16 kernel): a
+  // stage turns the scores of tile t into P and accumulates P V of the same tile.
+  // The FP8 product takes the probabilities of 64 keys at once, so its first
+  // instruction waits for the whole tile's exponentials and the matrix pipe of
+  // the wave idles meanwhile (the other wave of the SIMD fills in).  DEEP (three
+  // tiles deep): P of tile t is consumed one stage later, nothing in a stage
+  // waits for anything else in it; it costs one more stage per list and eight
+  // more registers per 64 keys of tile, and pays only for long dense lists at
+  // D = 128.
   f32x16 s_a[KB2], s_b[KB2];
-  if (n_tiles > 0) {
-    load_tile(Int<1>{}, 0, 0);
-    load_tile(Int<0>{}, 0, 0);
-    if (n_tiles > 1) load_tile(Int<1>{}, 1, 1);
-  }
-  __syncthreads();
-  if (n_tiles > 0) {
-    scores(Int<0>{}, s_a);
-    tile_max(s_a);
-  }
+  if (!DEEP) {
+    if (n_tiles > 0) {
+      load_tile(Int<1>{}, 0, 0);
+      load_tile(Int<0>{}, 0, 0);
+      if (n_tiles > 1) load_tile(Int<1>{}, 1, 1);
+    }
+    __syncthreads();
+    if (n_tiles > 0) {
+      scores(Int<0>{}, s_a);
+      tile_max(s_a);
+    }
 
-  // One pipeline stage (see the bf16 kernel): on entry s_cur holds the raw scores
-  // of tile t; LDS holds K(t+1) and V(t); K(t+2) and V(t+1) are requested here.
-  // INNER: t + 2 is not the last tile of the list, so outside band lists nothing
-  // of tile t can be masked.
-  auto stage = [&](auto par_tag, auto next_tag, auto inner_tag, const int t, f32x16 (&s_cur)[KB2],
-                   f32x16 (&s_next)[KB2]) {
-    constexpr int PAR = decltype(par_tag)::value;
-    constexpr bool has1 = decltype(next_tag)::value != 0;
-    constexpr bool INNER = decltype(inner_tag)::value != 0;
-    const bool has2 = INNER || t + 2 < n_tiles;
-    if (has2) load_tile(Int<1>{}, PAR, t + 2);
-    if (has1) load_tile(Int<0>{}, PAR ^ 1, t + 1);
-    bool masked;
-    if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
-    else if (INNER) masked = false;
-    else masked = (t + t_base + 1) * BC > n_keys;
-    if (masked && apply_mask(s_cur, t)) tile_max(s_cur);
-    settle_max(s_cur);
-    i32x8 pf[G64];
-    if (has1) scores(Int<PAR ^ 1>{}, s_next);
-    exponentiate(s_cur, pf);
-    if (has1) tile_max(s_next);
-    accumulate(Int<PAR>{}, pf);
+    // One pipeline stage (see the bf16 kernel): on entry s_cur holds the raw scores
+    // of tile t; LDS holds K(t+1) and V(t); K(t+2) and V(t+1) are requested here.
+    // INNER: t + 2 is not the last tile of the list, so outside band lists nothing
+    // of tile t can be masked.
+    auto flat_stage = [&](auto par_tag, auto next_tag, auto inner_tag, const int t, f32x16 (&s_cur)[KB2],
+                     f32x16 (&s_next)[KB2]) {
+      constexpr int PAR = decltype(par_tag)::value;
+      constexpr bool has1 = decltype(next_tag)::value != 0;
+      constexpr bool INNER = decltype(inner_tag)::value != 0;
+      const bool has2 = INNER || t + 2 < n_tiles;
+      if (has2) load_tile(Int<1>{}, PAR, t + 2);
+      if (has1) load_tile(Int<0>{}, PAR ^ 1, t + 1);
+      bool masked;
+      if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+      else if (INNER) masked = false;
+      else masked = (t + t_base + 1) * BC > n_keys;
+      if (masked && apply_mask(s_cur, t)) tile_max(s_cur);
+      settle_max(s_cur, []() {});
+      i32x8 pf[G64];
+      if (has1) scores(Int<PAR ^ 1>{}, s_next);
+      exponentiate(s_cur, pf);
+      if (has1) tile_max(s_next);
+      accumulate(Int<PAR>{}, pf);
 #ifndef SVD_FP8_NO_SCHED
-    if (has1) {
-      // Issue order: one MFMA, the LDS reads that feed the MFMAs two steps later,
-      // then a share of the vector work (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
-      constexpr int N_QK = KS * KB2, N_PV = G64 * DB, N_SUM = G64;
-      constexpr int N_KRD = N_QK * 2, N_VRD = N_PV * 2;
-      // per score element: one exp2, half a conversion, half a max3
-      constexpr int VALU_PER = (KB2 * 16 * 2 + N_QK + N_PV + N_SUM - 1) / (N_QK + N_PV + N_SUM);
-      constexpr int AHEAD = 4;   // reads issued ahead of the MFMA that needs them (two MFMAs' worth)
-      __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+      if (has1) {
+        // Issue order: one MFMA, the LDS reads that feed the MFMAs two steps later,
+        // then a share of the vector work (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
+        constexpr int N_QK = KS * KB2, N_PV = G64 * DB, N_SUM = G64;
+        constexpr int N_KRD = N_QK * 2, N_VRD = N_PV * 2;
+        // per score element: one exp2, half a conversion, half a max3
+        constexpr int VALU_PER = (KB2 * 16 * 2 + N_QK + N_PV + N_SUM - 1) / (N_QK + N_PV + N_SUM);
+        constexpr int AHEAD = 4;   // reads issued ahead of the MFMA that needs them (two MFMAs' worth)
+        __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
 #pragma unroll
-      for (int i = 0; i < N_QK; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (2 * i + AHEAD < N_KRD + N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
-      }
-#pragma unroll
-      for (int g = 0; g < G64; ++g) {
-#pragma unroll
-        for (int j = 0; j < DB; ++j) {
+        for (int i = 0; i < N_QK; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (2 * (N_QK + g * DB + j) + AHEAD < N_KRD + N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          if (2 * i + AHEAD < N_KRD + N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
           __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+#pragma unroll
+        for (int g = 0; g < G64; ++g) {
+#pragma unroll
+          for (int j = 0; j < DB; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (2 * (N_QK + g * DB + j) + AHEAD < N_KRD + N_VRD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+        }
       }
-    }
 #endif
-    if (has1) asm volatile("" : "+v"(mx_raw));   // keeps the maximum chain of the next tile inside this block
-    __syncthreads();
-  };
+      if (has1) asm volatile("" : "+v"(mx_raw));   // keeps the maximum chain of the next tile inside this block
+      __syncthreads();
+    };
 
-  int t = 0;
-  for (; t + 5 <= n_tiles; t += 2) {
-    stage(Int<0>{}, Int<1>{}, Int<1>{}, t, s_a, s_b);
-    stage(Int<1>{}, Int<1>{}, Int<1>{}, t + 1, s_b, s_a);
-  }
-  for (; t + 2 < n_tiles; t += 2) {
-    stage(Int<0>{}, Int<1>{}, Int<0>{}, t, s_a, s_b);
-    stage(Int<1>{}, Int<1>{}, Int<0>{}, t + 1, s_b, s_a);
-  }
-  if (t + 1 < n_tiles) {
-    stage(Int<0>{}, Int<1>{}, Int<0>{}, t, s_a, s_b);
-    stage(Int<1>{}, Int<0>{}, Int<0>{}, t + 1, s_b, s_a);
-  } else if (t < n_tiles) {
-    stage(Int<0>{}, Int<0>{}, Int<0>{}, t, s_a, s_b);
+    int t = 0;
+    for (; t + 5 <= n_tiles; t += 2) {
+      flat_stage(Int<0>{}, Int<1>{}, Int<1>{}, t, s_a, s_b);
+      flat_stage(Int<1>{}, Int<1>{}, Int<1>{}, t + 1, s_b, s_a);
+    }
+    for (; t + 2 < n_tiles; t += 2) {
+      flat_stage(Int<0>{}, Int<1>{}, Int<0>{}, t, s_a, s_b);
+      flat_stage(Int<1>{}, Int<1>{}, Int<0>{}, t + 1, s_b, s_a);
+    }
+    if (t + 1 < n_tiles) {
+      flat_stage(Int<0>{}, Int<1>{}, Int<0>{}, t, s_a, s_b);
+      flat_stage(Int<1>{}, Int<0>{}, Int<0>{}, t + 1, s_b, s_a);
+    } else if (t < n_tiles) {
+      flat_stage(Int<0>{}, Int<0>{}, Int<0>{}, t, s_a, s_b);
+    }
+  } else {
+    i32x8 pf_a[G64], pf_b[G64];
+    if (n_tiles > 0) {
+      load_tile(Int<1>{}, 0, 0);
+      if (n_tiles > 1) load_tile(Int<1>{}, 1, 1);
+    }
+    __syncthreads();
+    if (n_tiles > 0) {
+      scores(Int<0>{}, s_a);
+      tile_max(s_a);
+    }
+
+    // One pipeline stage, three tiles deep.  On entry s_cur holds the raw scores of
+    // tile t and pf_prev the probabilities of tile t - 1; LDS holds K(t+1) and
+    // V(t-1); K(t+2) and V(t) are requested here.  The block then contains the
+    // scores of tile t + 1 and O += P V of tile t - 1 on the matrix pipe, and the
+    // exponentials of tile t plus the maximum of tile t + 1 on the vector pipe:
+    // nothing in it waits for anything else in it.  (The FP8 product takes the
+    // probabilities of 64 keys at once, so P of a tile cannot be consumed in the
+    // stage that produces it without stalling the matrix pipe.)
+    // FIRST: t = 0, nothing to accumulate yet.  NEXT: a tile t + 1 exists.
+    // INNER: t + 2 is not the last tile of the list, so outside band lists nothing
+    // of tile t can be masked.
+    auto deep_stage = [&](auto par_tag, auto first_tag, auto next_tag, auto inner_tag, const int t, f32x16 (&s_cur)[KB2],
+                     f32x16 (&s_next)[KB2], i32x8 (&pf_prev)[G64], i32x8 (&pf_cur)[G64]) {
+      constexpr int PAR = decltype(par_tag)::value;     // t & 1
+      constexpr bool FIRST = decltype(first_tag)::value != 0;
+      constexpr bool has1 = decltype(next_tag)::value != 0;
+      constexpr bool INNER = decltype(inner_tag)::value != 0;
+      const bool has2 = INNER || t + 2 < n_tiles;
+      if (has2) load_tile(Int<1>{}, PAR, t + 2);   // K(t+2) takes the place of K(t), read in the last stage
+      load_tile(Int<0>{}, PAR, t);                 // V(t) takes the place of V(t-2)
+      bool masked;
+      if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+      else if (INNER) masked = false;
+      else masked = (t + t_base + 1) * BC > n_keys;
+      if (masked && apply_mask(s_cur, t)) tile_max(s_cur);
+      settle_max(s_cur, [&]() {
+        if (!FIRST) {
+          accumulate(Int<PAR ^ 1>{}, pf_prev);
+#pragma unroll
+          for (int g64 = 0; g64 < G64; ++g64)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pf_prev[g64][i] = 0;   // the block below adds it once more: zeros now
+        }
+      });
+      if (has1) scores(Int<PAR ^ 1>{}, s_next);
+      if (!FIRST) accumulate(Int<PAR ^ 1>{}, pf_prev);
+      exponentiate(s_cur, pf_cur);
+      if (has1) tile_max(s_next);
+#ifndef SVD_FP8_NO_SCHED
+      if (has1 && !FIRST) {
+        // Issue order: one MFMA, the LDS reads that feed the MFMAs two steps later,
+        // then a share of the vector work (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
+        constexpr int N_QK = KS * KB2, N_PV = G64 * DB, N_SUM = G64;
+        constexpr int N_RD = (N_QK + N_PV) * 2;
+        // per score element: one exp2, half a conversion, half a max3
+        constexpr int VALU_PER = (KB2 * 16 * 2 + N_QK + N_PV + N_SUM - 1) / (N_QK + N_PV + N_SUM);
+        constexpr int AHEAD = 4;   // reads issued ahead of the MFMA that needs them (two MFMAs' worth)
+        __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+        for (int i = 0; i < N_QK; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (2 * i + AHEAD < N_RD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+        }
+#pragma unroll
+        for (int g = 0; g < G64; ++g) {
+#pragma unroll
+          for (int j = 0; j < DB; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (2 * (N_QK + g * DB + j) + AHEAD < N_RD) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
+        }
+      }
+#endif
+      if (has1) asm volatile("" : "+v"(mx_raw));   // keeps the maximum chain of the next tile inside this block
+      // the loads issued at the top of the stage must have landed before anyone reads them
+      __syncthreads();
+    };
+
+    // Tile 0 alone, then two stages per trip (odd tile first) so that buffer indices
+    // and register sets stay static; after the last stage the probabilities of the
+    // last tile are still to be accumulated.
+    if (n_tiles > 1) {
+      deep_stage(Int<0>{}, Int<1>{}, Int<1>{}, Int<0>{}, 0, s_a, s_b, pf_b, pf_a);
+      int t = 1;
+      for (; t + 5 <= n_tiles; t += 2) {
+        deep_stage(Int<1>{}, Int<0>{}, Int<1>{}, Int<1>{}, t, s_b, s_a, pf_a, pf_b);
+        deep_stage(Int<0>{}, Int<0>{}, Int<1>{}, Int<1>{}, t + 1, s_a, s_b, pf_b, pf_a);
+      }
+      for (; t + 2 < n_tiles; t += 2) {
+        deep_stage(Int<1>{}, Int<0>{}, Int<1>{}, Int<0>{}, t, s_b, s_a, pf_a, pf_b);
+        deep_stage(Int<0>{}, Int<0>{}, Int<1>{}, Int<0>{}, t + 1, s_a, s_b, pf_b, pf_a);
+      }
+      if (t + 1 < n_tiles) {
+        deep_stage(Int<1>{}, Int<0>{}, Int<1>{}, Int<0>{}, t, s_b, s_a, pf_a, pf_b);
+        deep_stage(Int<0>{}, Int<0>{}, Int<0>{}, Int<0>{}, t + 1, s_a, s_b, pf_b, pf_a);
+        accumulate(Int<0>{}, pf_a);
+      } else {
+        deep_stage(Int<1>{}, Int<0>{}, Int<0>{}, Int<0>{}, t, s_b, s_a, pf_a, pf_b);
+        accumulate(Int<1>{}, pf_b);
+      }
+    } else if (n_tiles == 1) {
+      deep_stage(Int<0>{}, Int<1>{}, Int<0>{}, Int<0>{}, 0, s_a, s_b, pf_b, pf_a);
+      accumulate(Int<0>{}, pf_a);
+    }
   }
 
   // ---- split launch: leave the chunk's state for the merge kernel (layout of the bf16 kernel) ----
