@@ -6,6 +6,10 @@ group of the per-head strategy table plus the zero fill of skipped heads, on
 Q/K/V already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|wan2.1|stack|search]
+                    [--precision bf16|fp8]
+
+--precision fp8 times the FP8 (E4M3) variant of the same layer: a step then also
+contains the quantisation pre-pass of K and V (the inputs stay bf16).
 """
 import argparse
 import json
@@ -18,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+FP8_MFMA_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 matrix peak
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc passes
 # summarised under profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: the
 # factors a 1 GiB streaming kernel in the same runs gives).  Counters cannot be
@@ -42,10 +47,11 @@ def gpu_time_ms(fn, reps, warmup, torch):
     return start.elapsed_time(stop) / reps
 
 
-def cpu_baseline(wl, q, k, v, out, budget_s, torch, np):
+def cpu_baseline(wl, q, k, v, out, budget_s, torch, np, fp8=False):
     """The oracle on a bounded row sample of every head, on the host cores; the
     same rows are used to check the GPU output."""
     from oracle import sparse_attention as O
+    from oracle import fp8_attention as F8
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -62,7 +68,10 @@ def cpu_baseline(wl, q, k, v, out, budget_s, torch, np):
         full_q = np.zeros((wl.L, wl.D))
         full_q[rows] = qh
         t0 = time.perf_counter()
-        want = O.attention_head(full_q, kh, vh, mode, p, rows=rows)
+        if fp8:
+            want = F8.attention_head_fp8(full_q, kh, vh, mode, p, rows=rows)
+        else:
+            want = O.attention_head(full_q, kh, vh, mode, p, rows=rows)
         spent += time.perf_counter() - t0
         heads_done += 1
         got = f64(out[0, h][torch.as_tensor(rows)])
@@ -123,7 +132,7 @@ def run_stack(args, torch, np, svd, W):
         cpu["sample"] += f"; layer {n_layers // 2} of the stack, times {n_layers} layers"
     dense_heads = [int((wl.strategy_table == 0).sum()) for wl in layers]
     result = {
-        "metric": "sparse-attn layer latency", "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1,
+        "metric": "sparse-attn layer latency" + (" (FP8 variant, pre-pass included)" if fp8 else ""), "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "layer-stack (40 layers, Wan2.1-like shape)", "B": wl0.B, "H": wl0.H, "L": wl0.L,
@@ -192,6 +201,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cogvideox1.5")
+    ap.add_argument("--precision", default="bf16", choices=["bf16", "fp8"],
+                    help="bf16 (the headline metric) or the FP8 E4M3 variant of the same layer")
     ap.add_argument("--dense-reps", type=int, default=2, help="timed passes of the all-heads dense baseline (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=25.0, help="budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -213,6 +224,10 @@ def main():
     svd.lib()   # fails loudly if the HIP library is not built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    fp8 = args.precision == "fp8"
+    if fp8 and args.workload in ("stack", "search"):
+        print("--precision fp8 is measured on the single-layer workloads", file=sys.stderr)
+        sys.exit(2)
     if args.workload == "stack":
         run_stack(args, torch, np, svd, W)
         return
@@ -234,7 +249,11 @@ def main():
     work = plan.work()
 
     # ---- the timed region: K full-layer steps ----
-    step = lambda: svd.svd_attn_forward_planned(plan, q, k, v, out)
+    step16 = lambda: svd.svd_attn_forward_planned(plan, q, k, v, out)
+    step = step16
+    if fp8:
+        ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        step = lambda: svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
     t_warm = time.perf_counter()          # bring the clocks up before the W warm-up steps
     while time.perf_counter() - t_warm < 1.5:
         step()
@@ -256,16 +275,20 @@ def main():
     groups = []
     for gi, g in enumerate(plan.groups()):
         gw = plan.work(gi)
-        ms = gpu_time_ms(lambda: svd.svd_attn_forward_group(plan, gi, q, k, v, out), max(3, args.steps // 2), 1, torch)
+        run_group = ((lambda: svd.svd_attn_forward_fp8_group(plan, gi, q, k, v, out, ws8)) if fp8 else
+                     (lambda: svd.svd_attn_forward_group(plan, gi, q, k, v, out)))
+        ms = gpu_time_ms(run_group, max(3, args.steps // 2), 1, torch)
         groups.append({"mode": MODE_NAMES[g["mode"]], "heads": len(g["heads"]), "ms": round(ms, 4),
                        "computed_tflop": round(gw["computed_flops"] / 1e12, 4),
                        "tflops": round(gw["computed_flops"] / 1e9 / ms, 1) if ms > 0 else None,
                        "tiles": gw["computed_tiles"]})
     compute_groups = [g for g in groups if g["mode"] != "skip"]
     dom = max(compute_groups, key=lambda g: g["ms"])
-    roofline = {"bound": "mfma", "kernel": f"attn_fwd_kernel[{dom['mode']} group]", "achieved": dom["tflops"],
-                "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(dom["tflops"] / BF16_MFMA_PEAK_TFLOPS, 4),
-                "traffic": PMC_TRAFFIC_BYTES.get(wl.name, {}).get(dom["mode"])}
+    peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
+    roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[{dom['mode']} group]",
+                "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(dom["tflops"] / peak, 4),
+                "traffic": None if fp8 else PMC_TRAFFIC_BYTES.get(wl.name, {}).get(dom["mode"])}
+    bf16_ms = gpu_time_ms(step16, max(3, args.steps // 2), 1, torch) if fp8 else None
 
     # ---- in-house dense kernel on all heads: the speed-up baseline ----
     dense_ms = None
@@ -286,12 +309,12 @@ def main():
 
     cpu, max_err, mean_err = (None, None, None)
     if args.cpu_seconds > 0:
-        cpu, max_err, mean_err = cpu_baseline(wl, q, k, v, out, args.cpu_seconds, torch, np)
+        cpu, max_err, mean_err = cpu_baseline(wl, q, k, v, out, args.cpu_seconds, torch, np, fp8=fp8)
 
     dense_flops = wl.dense_flops
     computed_tflops = work["computed_flops"] / 1e9 / ms_per_step
     result = {
-        "metric": "sparse-attn layer latency",
+        "metric": "sparse-attn layer latency" + (" (FP8 variant, pre-pass included)" if fp8 else ""),
         "value": round(ms_per_step, 4),
         "unit": "ms",
         "n_gpus": 1,
@@ -301,9 +324,9 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "fp8-e4m3 (fp32 accumulation)" if fp8 else "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
+        "config": {"workload": wl.name, "precision": args.precision, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
@@ -311,6 +334,9 @@ def main():
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),
         "computed_tile_tflops": round(computed_tflops, 1),
         "computed_tile_frac_of_bf16_peak": round(computed_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+        "computed_tile_frac_of_fp8_peak": round(computed_tflops / FP8_MFMA_PEAK_TFLOPS, 4) if fp8 else None,
+        "bf16_same_plan_ms": round(bf16_ms, 4) if bf16_ms else None,
+        "speedup_vs_bf16_sparse": round(bf16_ms / ms_per_step, 3) if bf16_ms else None,
         "computed_tflop_per_layer": round(work["computed_flops"] / 1e12, 3),
         "dense_tflop_per_layer": round(dense_flops / 1e12, 3),
         "flop_reduction_block_level": round(dense_flops / work["computed_flops"], 3),

@@ -273,6 +273,12 @@ svd_status svd_search_layer(const void* q, const void* k, const void* v, const s
 svd_status svd_fp8_workspace_bytes(const svd_tensor_desc* desc, size_t* bytes);
 svd_status svd_attn_forward_fp8(const svd_plan* plan, const void* q, const void* k, const void* v, void* out,
                                 void* fp8_workspace, size_t fp8_workspace_bytes, void* hip_stream);
+/* One group of the plan in the FP8 arithmetic (pre-pass of the group's heads,
+ * attention, merge of a split dense launch), as svd_attn_forward_group is to
+ * svd_attn_forward_planned.  SVD_ERR_SHAPE for a group index out of range. */
+svd_status svd_attn_forward_fp8_group(const svd_plan* plan, int32_t group, const void* q, const void* k,
+                                      const void* v, void* out, void* fp8_workspace, size_t fp8_workspace_bytes,
+                                      void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* svd_status_string(svd_status status);

@@ -28,7 +28,7 @@ EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", 
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
            "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
-           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8"]
+           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8", "svd_attn_forward_fp8_group"]
 
 
 class SvdError(RuntimeError):
@@ -92,6 +92,7 @@ def lib():
                                  C.POINTER(C.c_double), vp, vp, C.c_size_t, vp],
             "svd_fp8_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
             "svd_attn_forward_fp8": [vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
+            "svd_attn_forward_fp8_group": [vp, C.c_int32, vp, vp, vp, vp, vp, C.c_size_t, vp],
         }
         for name, args in sig.items():
             fn = getattr(_lib, name)
@@ -291,6 +292,13 @@ def svd_attn_forward_fp8(plan: Plan, q, k, v, out, fp8_workspace, stream=None):
     _check(lib().svd_attn_forward_fp8(plan.handle, _dev(q), _dev(k), _dev(v), _dev(out), _dev(fp8_workspace),
                                       fp8_workspace.numel() * fp8_workspace.element_size(), _stream_ptr(stream)),
            "svd_attn_forward_fp8")
+    return out
+
+
+def svd_attn_forward_fp8_group(plan: Plan, group: int, q, k, v, out, fp8_workspace, stream=None):
+    _check(lib().svd_attn_forward_fp8_group(plan.handle, int(group), _dev(q), _dev(k), _dev(v), _dev(out),
+                                            _dev(fp8_workspace), fp8_workspace.numel() * fp8_workspace.element_size(),
+                                            _stream_ptr(stream)), "svd_attn_forward_fp8_group")
     return out
 
 

@@ -758,52 +758,69 @@ svd_status svd_fp8_workspace_bytes(const svd_tensor_desc* desc, size_t* bytes) {
   return SVD_OK;
 }
 
+static svd_status check_fp8_workspace(const svd_tensor_desc& d, const void* ws8, size_t bytes) {
+  const size_t need = svd::fp8_scratch_bytes(d.B, d.H, d.L, d.D);
+  if (!ws8 || bytes < need || (reinterpret_cast<uintptr_t>(ws8) & 255u)) return SVD_ERR_WORKSPACE;
+  return SVD_OK;
+}
+
+// Pre-pass plus attention of one group on `stream`.
+static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, const void* q, const void* k,
+                                   const void* v, void* out, void* ws8, hipStream_t stream) {
+  const Plan& p = sp.p;
+  const svd_tensor_desc& d = p.desc;
+  const int* ws = static_cast<const int*>(p.device_workspace);
+  svd::Fp8Launch f{};
+  svd::AttnLaunch& a = f.a;
+  a = base_launch(d, q, k, v, out);
+  a.n_q_blocks = p.n_q_blocks;
+  a.n_heads = static_cast<int>(g.heads.size());
+  a.n_items = a.n_q_blocks * a.n_heads * a.B;
+  a.heads = ws + g.ws_heads;
+  a.list_id = ws + g.ws_list_id;
+  a.ws = ws;
+  a.list_table = static_cast<int>(g.ws_list_table);
+  if (g.mode == SVD_SKIP) return svd::launch_zero_heads(a, stream) == hipSuccess ? SVD_OK : SVD_ERR_HIP;
+  f.Lp = svd::fp8_padded_len(d.L);
+  f.k8 = static_cast<uint8_t*>(ws8);
+  f.v8t = f.k8 + svd::fp8_scratch_bytes(d.B, d.H, d.L, d.D) / 2;
+  const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
+                    : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+  // the pre-pass of a group runs right before its attention launch, so the
+  // quantised arrays of the group are read back while they are fresh in L2
+  if (svd::launch_quantise_kv(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
+  if (g.mode == SVD_DENSE && sp.dense_split > 1) {
+    a.split = sp.dense_split;
+    a.n_items *= a.split;
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.partial_offset);
+  }
+  if (svd::launch_attention_fp8(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
+  if (a.split > 1 && svd::launch_combine(a, stream) != hipSuccess) return SVD_ERR_HIP;
+  return SVD_OK;
+}
+
 svd_status svd_attn_forward_fp8(const svd_plan* plan, const void* q, const void* k, const void* v, void* out,
                                 void* fp8_workspace, size_t fp8_workspace_bytes, void* hip_stream) {
   if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
-  const Plan& p = plan->p;
-  const svd_tensor_desc& d = p.desc;
-  const size_t need = svd::fp8_scratch_bytes(d.B, d.H, d.L, d.D);
-  if (!fp8_workspace || fp8_workspace_bytes < need || (reinterpret_cast<uintptr_t>(fp8_workspace) & 255u))
-    return SVD_ERR_WORKSPACE;
+  if (svd_status st = check_fp8_workspace(plan->p.desc, fp8_workspace, fp8_workspace_bytes)) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int* ws = static_cast<const int*>(p.device_workspace);
+  // heaviest first, all on the caller's stream
   static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
-  for (int mode : order) {
-    for (const svd::Group& g : p.groups) {
-      if (g.mode != mode) continue;
-      svd::Fp8Launch f{};
-      svd::AttnLaunch& a = f.a;
-      a = base_launch(d, q, k, v, out);
-      a.n_q_blocks = p.n_q_blocks;
-      a.n_heads = static_cast<int>(g.heads.size());
-      a.n_items = a.n_q_blocks * a.n_heads * a.B;
-      a.heads = ws + g.ws_heads;
-      a.list_id = ws + g.ws_list_id;
-      a.ws = ws;
-      a.list_table = static_cast<int>(g.ws_list_table);
-      if (g.mode == SVD_SKIP) {
-        if (svd::launch_zero_heads(a, stream) != hipSuccess) return SVD_ERR_HIP;
-        continue;
-      }
-      f.Lp = svd::fp8_padded_len(d.L);
-      f.k8 = static_cast<uint8_t*>(fp8_workspace);
-      f.v8t = f.k8 + need / 2;
-      const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
-                        : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
-      // the pre-pass of a group runs right before its attention launch, so the
-      // quantised arrays of the group are read back while they are fresh in L2
-      if (svd::launch_quantise_kv(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
-      if (g.mode == SVD_DENSE && plan->dense_split > 1) {
-        a.split = plan->dense_split;
-        a.n_items *= a.split;
-        a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + plan->partial_offset);
-      }
-      if (svd::launch_attention_fp8(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
-      if (a.split > 1 && svd::launch_combine(a, stream) != hipSuccess) return SVD_ERR_HIP;
-    }
-  }
+  for (int mode : order)
+    for (const svd::Group& g : plan->p.groups)
+      if (g.mode == mode)
+        if (svd_status st = launch_group_fp8(*plan, g, q, k, v, out, fp8_workspace, stream)) return st;
   return SVD_OK;
+}
+
+svd_status svd_attn_forward_fp8_group(const svd_plan* plan, int32_t group, const void* q, const void* k,
+                                      const void* v, void* out, void* fp8_workspace, size_t fp8_workspace_bytes,
+                                      void* hip_stream) {
+  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  if (svd_status st = check_fp8_workspace(plan->p.desc, fp8_workspace, fp8_workspace_bytes)) return st;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  return launch_group_fp8(*plan, plan->p.groups[group], q, k, v, out, fp8_workspace,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

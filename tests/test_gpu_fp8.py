@@ -221,3 +221,46 @@ def test_workspace_validation():
     torch.cuda.synchronize()
     assert (out == 3.0).all()
     plan.close()
+
+
+def test_group_entry_point_matches_the_layer_call():
+    wl = W.small(L=700, D=128, H=10, seed=81, B=2)
+    q, k, v = _cuda(W.make_qkv(wl))
+    want, _ = run_fp8(wl, q, k, v)
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params), dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws)
+    ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    out = torch.full_like(q, float("nan"))
+    for gi in range(len(plan.groups())):
+        svd.svd_attn_forward_fp8_group(plan, gi, q, k, v, out, ws8)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), want.view(torch.int16))
+    with pytest.raises(svd.SvdError) as e:
+        svd.svd_attn_forward_fp8_group(plan, len(plan.groups()), q, k, v, out, ws8)
+    assert e.value.status == 2
+    plan.close()
+
+
+@pytest.mark.parametrize("name", ["cogvideox1.5", "hunyuanvideo", "wan2.1"])
+def test_benchmark_shape_sampled_rows_and_closed_form(name):
+    """The FP8 path at the benchmark shapes, in the launch configuration bench.py
+    times with --precision fp8: sampled rows of every head against the FP8 oracle,
+    every row of one head per mode against the zero-query closed form."""
+    from test_gpu_full_size import _windowed_means
+    wl = W.BY_NAME[name]()
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    out, _ = run_fp8(wl, q, k, v)
+    assert torch.isfinite(out.float()).all()
+    rows = W.sample_rows(wl, n_random=24)
+    bq, _ = svd.svd_default_blocks(wl.D)
+    rows = np.unique(np.concatenate([rows, np.arange(max(0, wl.L - 2 * bq - 3), wl.L, 61)]))
+    check_layer_fp8(wl, q, k, v, out, rows=rows)
+    for h in range(wl.H):
+        if wl.strategy_table[h] == W.SKIP:
+            assert not out[0, h].view(torch.int16).any()
+    out0, _ = run_fp8(wl, torch.zeros_like(q), k, v)
+    for mode in (W.DENSE, W.DIAG, W.MULTIDIAG, W.VSTRIPE):
+        h = int(np.nonzero(wl.strategy_table == mode)[0][0])
+        want = _windowed_means(F8.quantise_v(f64(v[0, h].cpu())), mode, wl.pattern_params[h], wl.L)
+        assert_close(f64(out0[0, h].cpu()), want, f"fp8 {name} zero-q head {h} mode {mode}")
