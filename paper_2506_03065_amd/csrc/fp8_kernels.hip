@@ -171,7 +171,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   constexpr int KS = D / 64;         // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;         // 32-row blocks of O^T
   constexpr int TILE_BYTES = BC * D;
-  constexpr bool DEEP = D == 128 && MODE == MODE_DENSE;   // pipeline shape, see the stages below
+#ifndef SVD_FP8_DEEP
+#define SVD_FP8_DEEP (D == 128 && MODE == MODE_DENSE)
+#endif
+  constexpr bool DEEP = SVD_FP8_DEEP;   // pipeline shape, see the stages below
   constexpr int LPT = TILE_BYTES / (NW * 1024);   // load instructions per wave, tile and matrix
   static_assert(TILE_BYTES % (NW * 1024) == 0 && LPT >= 1, "tile must split evenly over the waves");
   static_assert(BC % 64 == 0, "key tiles are whole groups of 64");
