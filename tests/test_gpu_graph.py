@@ -45,3 +45,40 @@ def test_captured_forward_replays_to_the_eager_bits(L, D, split):
         assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
     del graph
     plan.close()
+
+
+def test_captured_fp8_forward_replays_to_the_eager_bits():
+    """The FP8 layer (pre-pass, attention, merge of a split dense launch) enqueues
+    kernel launches only."""
+    wl = W.small(L=900, D=128, H=6, seed=73, B=2)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=2),
+                     dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, dense_split=2)
+    ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    eager = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_fp8(plan, q, k, v, eager, ws8)
+    torch.cuda.synchronize()
+    assert torch.isfinite(eager.float()).all()
+
+    out = torch.full_like(q, float("nan"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
+    scratch = torch.empty(1 << 20, device=DEV)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws8.fill_(0x7f)                                        # the replay must refill the quantised arrays
+        scratch.normal_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
+    del graph
+    plan.close()

@@ -107,3 +107,28 @@ def test_search_entry_points_validate_before_any_launch():
     with pytest.raises(svd.SvdError) as e:
         svd.svd_search_layer_workspace_bytes(d, empty)
     assert e.value.status == 7
+
+
+def test_fp8_entry_points_validate_before_any_launch():
+    """Sizes come from the host; bad arguments become status codes without a launch."""
+    import ctypes as C
+    lib = svd.lib()
+    d = svd.tensor_desc(2, 4, 300, 64)
+    n = C.c_size_t()
+    assert lib.svd_fp8_workspace_bytes(C.byref(d), C.byref(n)) == 0
+    assert n.value == 2 * 2 * 4 * 384 * 64          # K8 and V8, L rounded up to a multiple of 128
+    assert lib.svd_fp8_workspace_bytes(None, C.byref(n)) == 1
+    assert lib.svd_fp8_workspace_bytes(C.byref(d), None) == 1
+    bad = svd.tensor_desc(1, 4, 100, 96)
+    assert lib.svd_fp8_workspace_bytes(C.byref(bad), C.byref(n)) == 2
+    p16 = C.c_void_p(0x1000)
+    # without a plan nothing is dereferenced
+    assert lib.svd_attn_forward_fp8(None, p16, p16, p16, p16, C.c_void_p(0x10000), 1 << 30, None) == 1
+    assert lib.svd_attn_forward_fp8_group(None, 0, p16, p16, p16, p16, C.c_void_p(0x10000), 1 << 30, None) == 1
+    # a plan without device workspace can be inspected but not launched
+    table = np.array([0, 2, 3, 4], dtype=np.int32)
+    params = [{}, {"half_width": 5}, {"half_width": 2, "offsets": (-30, 0, 30)}, {"cols": (1, 2, 3)}]
+    plan = svd.svd_plan_create(d, table, params)
+    assert lib.svd_attn_forward_fp8(plan.handle, p16, p16, p16, p16, C.c_void_p(0x10000), 1 << 30, None) == 8
+    assert lib.svd_attn_forward_fp8(plan.handle, None, p16, p16, p16, C.c_void_p(0x10000), 1 << 30, None) == 1
+    plan.close()
