@@ -17,6 +17,11 @@ What it follows in the paper
 * Section 4.2: the sparsity of a kernel is counted in blocks of the attention
   map, which is why block lists are derived here as well.
 
+* Section 4.1.1: with text tokens in the sequence the attention map has four
+  regions, T-T, T-V, V-T and V-V, and the patterns are described for V-V.  A
+  head whose parameters carry text_tokens = T > 0 (text first) keeps the three
+  border regions whole: key j < T for every query, every key for query i < T.
+
 Readings where the paper is silent (all listed in the design notes):
 the band is inclusive (|delta| <= w), several bands form a union, the softmax is
 renormalised over the kept keys, a row without any kept key is an error, modes
@@ -55,6 +60,11 @@ def _offsets_of(mode, params):
     return offs
 
 
+def text_tokens_of(params):
+    """Length T of the text prefix whose borders the head keeps whole (0: none)."""
+    return int(params.get("text_tokens", 0)) if params else 0
+
+
 def allowed_mask(mode, params, L, rows):
     """Explicit boolean mask [len(rows), L]: True where key j is kept for query i.
 
@@ -63,10 +73,25 @@ def allowed_mask(mode, params, L, rows):
       diagonal       |i - j| <= w
       multi-diagonal exists o in offsets with |j - i - o| <= w
       vertical       j in the head's column set
+    and, for the sparse modes with text_tokens = T > 0 (Section 4.1.1), also every
+    j < T and every j when i < T.
     """
     rows = np.asarray(rows, dtype=np.int64)
     if mode == MODE_DENSE:
         return np.ones((rows.size, L), dtype=bool)
+    T = text_tokens_of(params)
+    if T:
+        if not 0 < T < L:
+            raise ValueError("text prefix must be shorter than the sequence")
+        mask = _pattern_mask(mode, params, L, rows)
+        mask[:, :T] = True
+        mask[rows < T, :] = True
+        return mask
+    return _pattern_mask(mode, params, L, rows)
+
+
+def _pattern_mask(mode, params, L, rows):
+    """The V-V pattern of Section 4.1.2 on the global token index, without borders."""
     if mode in BAND_MODES:
         w = int(params["half_width"])
         if w < 0:
@@ -180,23 +205,33 @@ def query_block_entries(mode, params, L, block_q, block_k, qb, runs=None):
     run_count) as int32 arrays; see block_lists for their meaning."""
     if mode not in BAND_MODES:
         raise ValueError("block lists exist for the band modes only")
+    T = text_tokens_of(params)
+    if T and (T % block_q or T % block_k):
+        raise ValueError("the text prefix must be a multiple of both block sizes")
     runs = delta_runs(mode, params, L) if runs is None else runs
     run_of_delta = _run_lookup(runs, L)
     n_kb = -(-L // block_k)
     rows = np.arange(qb * block_q, min(L, (qb + 1) * block_q), dtype=np.int64)
+    as32 = lambda a: np.asarray(a, dtype=np.int32)
+    if T and rows[0] < T:
+        # text queries see every key: their rows are computed densely, not from a list
+        return (as32([]), as32([]), as32([]), as32([]))
     mask = allowed_mask(mode, params, L, rows)
+    band = _pattern_mask(mode, params, L, rows)
     delta = np.arange(L, dtype=np.int64)[None, :] - rows[:, None]
     rid = run_of_delta[delta + (L - 1)]
     pad = n_kb * block_k - L
-    tiles = np.pad(mask, ((0, 0), (0, pad)), constant_values=False).reshape(rows.size, n_kb, block_k)
-    rtiles = np.pad(rid, ((0, 0), (0, pad)), constant_values=-1).reshape(rows.size, n_kb, block_k)
+    tile = lambda a, fill: np.pad(a, ((0, 0), (0, pad)), constant_values=fill).reshape(rows.size, n_kb, block_k)
+    tiles, btiles, rtiles = tile(mask, False), tile(band, False), tile(rid, -1)
     any_ = tiles.any(axis=(0, 2))
     all_ = tiles.all(axis=(0, 2))
-    rmin = np.where(tiles, rtiles, np.iinfo(np.int32).max).min(axis=(0, 2))
-    rmax = np.where(tiles, rtiles, -1).max(axis=(0, 2))
+    rmin = np.where(btiles, rtiles, np.iinfo(np.int32).max).min(axis=(0, 2))
+    rmax = np.where(btiles, rtiles, -1).max(axis=(0, 2))
+    has_band = btiles.any(axis=(0, 2))
+    rmin = np.where(has_band, rmin, 0)
+    count = np.where(has_band, rmax - rmin + 1, 0)
     kbs = np.nonzero(any_)[0]
-    as32 = lambda a: np.asarray(a, dtype=np.int32)
-    return (as32(kbs), as32(all_[kbs]), as32(rmin[kbs]), as32(rmax[kbs] - rmin[kbs] + 1))
+    return (as32(kbs), as32(all_[kbs]), as32(rmin[kbs]), as32(count[kbs]))
 
 
 def block_lists(mode, params, L, block_q, block_k):
@@ -208,8 +243,11 @@ def block_lists(mode, params, L, block_q, block_k):
                     row and the tile lies wholly inside [0, L), else 0
       run_first,    the kept-diagonal runs (see delta_runs) that have a kept
       run_count     element in the tile are consecutive; their first id and
-                    their number
+                    their number (0, 0 for a tile kept for its text keys only)
     row_ptr is the CSR pointer over query blocks.  All int32.
+    With a text prefix T (a multiple of both block sizes) the query blocks of the
+    text rows have no entries (those rows are dense) and every other query block
+    lists the T / block_k text tiles, kept whole.
     """
     runs = delta_runs(mode, params, L)
     n_qb = -(-L // block_q)
@@ -227,12 +265,13 @@ def block_lists(mode, params, L, block_q, block_k):
 
 
 def column_list(params, L, block_k):
-    """Sorted unique key columns of a vertical-stripe head, padded with -1 to a
-    multiple of block_k (int32)."""
+    """Sorted unique key columns of a vertical-stripe head (with the text columns
+    0..T-1 when the head has a text prefix), padded with -1 to a multiple of
+    block_k (int32)."""
     cols = np.asarray(params["cols"], dtype=np.int64)
     if cols.size < 1 or cols.min() < 0 or cols.max() >= L or np.unique(cols).size != cols.size:
         raise ValueError("bad column set")
-    cols = np.sort(cols)
+    cols = np.union1d(cols, np.arange(text_tokens_of(params), dtype=np.int64))   # sorted, text columns included
     padded = -(-cols.size // block_k) * block_k
     out = np.full(padded, -1, dtype=np.int32)
     out[:cols.size] = cols
@@ -250,9 +289,9 @@ def mask_popcount(mode, params, L, chunk=256):
 
 def _params_key(mode, params):
     if mode in BAND_MODES:
-        return (int(params["half_width"]), tuple(sorted(set(_offsets_of(mode, params)))))
+        return (int(params["half_width"]), tuple(sorted(set(_offsets_of(mode, params)))), text_tokens_of(params))
     if mode == MODE_VSTRIPE:
-        return tuple(sorted(int(c) for c in params["cols"]))
+        return (tuple(sorted(int(c) for c in params["cols"])), text_tokens_of(params))
     return ()
 
 
