@@ -92,8 +92,20 @@ typedef struct {
  * of work-groups partly empty; splitting the key range makes the rounds shorter
  * at the price of a merge pass over partial results kept in the workspace.
  * 0 = chosen from the shape and the device's compute-unit count, 1 = off,
- * 2..8 = forced (capped at the number of key tiles). */
-typedef struct { int32_t block_q, block_k, dense_split; } svd_plan_options;
+ * 2..8 = forced (capped at the number of key tiles).
+ * text_tokens: Section 4.1.1 describes the attention map of a sequence of text
+ * and video tokens as four regions, T-T, T-V, V-T and V-V, and the sparse
+ * patterns for V-V.  With text_tokens = T > 0 the first T tokens are text and
+ * every head in a sparse mode (diagonal, multi-diagonal, vertical-stripe) keeps
+ * the three border regions whole: key j < T for every query, every key for
+ * query i < T; bands are still taken on the global token index.  T must be
+ * smaller than L and a multiple of block_q and of block_k (256 for the kernels'
+ * shapes), else SVD_ERR_UNSUPPORTED.  The band lists of the text query blocks
+ * are then empty (their rows come from a dense launch over the group's heads),
+ * the other query blocks list the text tiles first, and the column lists gain
+ * columns 0..T-1.  0 = no text prefix.  sparse_vdit_attn_forward takes no
+ * options and therefore no text prefix. */
+typedef struct { int32_t block_q, block_k, dense_split, text_tokens; } svd_plan_options;
 
 typedef struct svd_plan svd_plan;
 

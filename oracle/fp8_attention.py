@@ -99,6 +99,9 @@ def quantise_v(v):
     return round_e4m3(np.asarray(v, dtype=np.float64))
 
 
+WEIGHT_FLOOR = 5e-3   # share of the row sum below which a probability is too light to matter for the margin
+
+
 def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0, with_margin=False):
     """The quantised row arithmetic of the header for operands already in E4M3.
 
@@ -106,8 +109,10 @@ def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0, with_margin=False):
     shift: integer added to the reference (0 in the definition; the tests use it
     to show that the result does not depend on it).
     with_margin: also return, per row, the smallest rounding_margin of the
-    probabilities that carry more than 1e-3 of the row's weight: how far the
-    row's result is from depending on the last bits of a score.
+    probabilities that carry more than WEIGHT_FLOOR of the row's weight: how far
+    the row's result is from depending on the last bits of a score.  (A lighter
+    probability that rounds the other way moves the row by less than
+    WEIGHT_FLOOR / 8 * |v - o|.)
     """
     if not mask.any(axis=1).all():
         raise ValueError("a query row keeps no key")
@@ -120,7 +125,7 @@ def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0, with_margin=False):
     out = (p8 @ v8) / den
     if not with_margin:
         return out
-    margin = np.where(p8 > 1e-3 * den, rounding_margin(p), np.inf).min(axis=1)
+    margin = np.where(p8 > WEIGHT_FLOOR * den, rounding_margin(p), np.inf).min(axis=1)
     return out, margin
 
 

@@ -48,7 +48,8 @@ class HeadParams(C.Structure):
 
 
 class PlanOptions(C.Structure):
-    _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32), ("dense_split", C.c_int32)]
+    _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32), ("dense_split", C.c_int32),
+                ("text_tokens", C.c_int32)]
 
 
 _lib = None
@@ -157,15 +158,27 @@ class _Marshalled:
             self.params[h].cols = _ptr(cols) if cols.size else None
 
 
+def _text_tokens(strategy_table, pattern_params, text_tokens):
+    """The plan option text_tokens: given explicitly, or read from the parameter
+    dicts of the heads in a sparse mode (key "text_tokens"; they must agree)."""
+    if text_tokens is not None:
+        return int(text_tokens)
+    found = {int((p or {}).get("text_tokens", 0)) for m, p in zip(strategy_table, pattern_params) if int(m) >= 2}
+    if len(found) > 1:
+        raise ValueError("the sparse heads of a layer must share one text prefix")
+    return found.pop() if found else 0
+
+
 def svd_default_blocks(D: int):
     bq, bk = C.c_int32(), C.c_int32()
     _check(lib().svd_default_blocks(D, C.byref(bq), C.byref(bk)), "svd_default_blocks")
     return bq.value, bk.value
 
 
-def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0, dense_split=0) -> int:
+def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0, dense_split=0,
+                             text_tokens=None) -> int:
     m = _Marshalled(strategy_table, pattern_params)
-    opt = PlanOptions(block_q, block_k, dense_split)
+    opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens))
     n = C.c_size_t()
     _check(lib().svd_plan_workspace_bytes(C.byref(desc), _ptr(m.table), m.params, C.byref(opt), C.byref(n)),
            "svd_plan_workspace_bytes")
@@ -249,11 +262,13 @@ class Plan:
 
 
 def svd_plan_create(desc, strategy_table, pattern_params, block_q=0, block_k=0, workspace=None, stream=None,
-                    dense_split=0) -> Plan:
+                    dense_split=0, text_tokens=None) -> Plan:
     """workspace: a torch uint8/int32 CUDA tensor of at least svd_plan_workspace_bytes
-    bytes, or None for a host-only plan (inspection, no launches)."""
+    bytes, or None for a host-only plan (inspection, no launches).  text_tokens:
+    the plan option; None reads it from the "text_tokens" key of the sparse
+    heads' parameter dicts."""
     m = _Marshalled(strategy_table, pattern_params)
-    opt = PlanOptions(block_q, block_k, dense_split)
+    opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens))
     handle = C.c_void_p()
     ws_ptr = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0

@@ -34,6 +34,10 @@ struct svd_plan {
   bool concurrent = false;
   int dense_split = 1;          // key-range chunks per dense item
   size_t partial_offset = 0;    // byte offset of the split scratch in the workspace
+  // text prefix (Section 4.1.1): per group, key-range chunks of the dense launch
+  // that computes the text rows of its heads, and the byte offset of its scratch
+  std::vector<int> text_split;
+  std::vector<size_t> text_partial_offset;
   ~svd_plan() {
     for (int i = 0; i < kSideStreams; ++i) {
       if (side[i]) (void)hipStreamDestroy(side[i]);
@@ -57,6 +61,7 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
   *bk = (opt && opt->block_k) ? opt->block_k : kk;
   if (*bq < 1 || *bk < 1) return SVD_ERR_UNSUPPORTED;
   if (opt && opt->dense_split < 0) return SVD_ERR_UNSUPPORTED;
+  if (opt && opt->text_tokens < 0) return SVD_ERR_PARAMS;
   *native = (*bq == kq && *bk == kk);
   return SVD_OK;
 }
@@ -107,15 +112,48 @@ int count_dense_heads(const Plan& p) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workspace = [compiled lists | padding to 256 bytes | scratch of the dense split].
-size_t workspace_need(const Plan& p, int dense_split, size_t* partial_offset) {
-  const size_t lists = p.ws_image.size() * sizeof(int32_t);
+bool has_text_rows(const Plan& p, const svd::Group& g) {
+  return p.text_tokens > 0 && (g.mode == SVD_DIAG || g.mode == SVD_MULTIDIAG || g.mode == SVD_VSTRIPE);
+}
+
+// Key-range chunks of the dense launch over the text rows of one sparse group:
+// few query tiles (T / block_q per head) against every key, so the key range is
+// cut until about two work-groups per compute unit exist, chunks of 8 tiles at least.
+int choose_text_split(const Plan& p, const svd::Group& g, int n_cu) {
+  if (n_cu < 1) return 1;
+  const long long base = static_cast<long long>(p.text_tokens / p.block_q) * g.heads.size() * p.desc.B;
+  long long s = (2LL * n_cu + base - 1) / base;
+  const long long cap = p.n_k_blocks / 8 > 64 ? 64 : p.n_k_blocks / 8;
+  if (s > cap) s = cap;
+  return s < 1 ? 1 : static_cast<int>(s);
+}
+
+// Workspace = [compiled lists | padding to 256 bytes | scratch of the dense split |
+// scratch of the text-row launches, one area per sparse group].
+size_t workspace_need(const Plan& p, int dense_split, int n_cu, size_t* partial_offset, std::vector<int>* text_split,
+                      std::vector<size_t>* text_offset) {
+  size_t end = p.ws_image.size() * sizeof(int32_t);
   if (partial_offset) *partial_offset = 0;
-  if (dense_split <= 1) return lists;
-  const size_t off = align_up(lists, 256);
-  if (partial_offset) *partial_offset = off;
-  const int items = p.n_q_blocks * count_dense_heads(p) * p.desc.B * dense_split;
-  return off + svd::partial_floats(p.desc.D, items) * sizeof(float);
+  if (dense_split > 1) {
+    const size_t off = align_up(end, 256);
+    if (partial_offset) *partial_offset = off;
+    const int items = p.n_q_blocks * count_dense_heads(p) * p.desc.B * dense_split;
+    end = off + svd::partial_floats(p.desc.D, items) * sizeof(float);
+  }
+  if (text_split) text_split->assign(p.groups.size(), 1);
+  if (text_offset) text_offset->assign(p.groups.size(), 0);
+  for (size_t gi = 0; gi < p.groups.size(); ++gi) {
+    const svd::Group& g = p.groups[gi];
+    if (!has_text_rows(p, g)) continue;
+    const int split = choose_text_split(p, g, n_cu);
+    if (text_split) (*text_split)[gi] = split;
+    if (split <= 1) continue;
+    const size_t off = align_up(end, 256);
+    if (text_offset) (*text_offset)[gi] = off;
+    const int items = (p.text_tokens / p.block_q) * static_cast<int>(g.heads.size()) * p.desc.B * split;
+    end = off + svd::partial_floats(p.desc.D, items) * sizeof(float);
+  }
+  return end;
 }
 
 svd::AttnLaunch base_launch(const svd_tensor_desc& d, const void* q, const void* k, const void* v,
@@ -213,10 +251,12 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   bool native;
   if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
   Plan tmp;
-  if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, &tmp)) return st;
-  const int split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), device_compute_units(), options)
-                           : 1;
-  *bytes = workspace_need(tmp, split, nullptr);
+  if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk,
+                                        options ? options->text_tokens : 0, &tmp))
+    return st;
+  const int n_cu = device_compute_units();
+  const int split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), n_cu, options) : 1;
+  *bytes = workspace_need(tmp, split, native ? n_cu : 0, nullptr, nullptr, nullptr);
   return SVD_OK;
 }
 
@@ -234,7 +274,7 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
   if (!sp) return SVD_ERR_HIP;
   svd_status st = SVD_OK;
   try {
-    st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, &sp->p);
+    st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, options ? options->text_tokens : 0, &sp->p);
   } catch (...) {
     st = SVD_ERR_UNSUPPORTED;
   }
@@ -243,9 +283,10 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
     return st;
   }
   if (device_workspace) {
-    sp->dense_split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), device_compute_units(), options)
-                             : 1;
-    const size_t need = workspace_need(sp->p, sp->dense_split, &sp->partial_offset);
+    const int n_cu_ws = device_compute_units();
+    sp->dense_split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), n_cu_ws, options) : 1;
+    const size_t need = workspace_need(sp->p, sp->dense_split, native ? n_cu_ws : 0, &sp->partial_offset,
+                                       &sp->text_split, &sp->text_partial_offset);
     if (workspace_bytes < need || !aligned16(device_workspace)) {
       delete sp;
       return SVD_ERR_WORKSPACE;
@@ -370,18 +411,23 @@ static void group_work(const Plan& p, const svd::Group& g, int64_t* tiles, doubl
         const svd::BandList& bl = g.bands[g.list_id[t]];
         *tiles += static_cast<int64_t>(bl.kv_block_idx.size());
         *area += bl.tile_area;
-        *pairs += bl.kept_pairs;
+        *pairs += bl.kept_pairs;   // text borders included
         break;
       }
       case SVD_VSTRIPE: {
         const svd::ColumnList& cl = g.columns[g.list_id[t]];
         *tiles += static_cast<int64_t>(p.n_q_blocks) * static_cast<int64_t>(cl.cols.size() / p.block_k);
         *area += L * cl.n_cols;
-        *pairs += L * cl.n_cols;
+        *pairs += L * cl.n_cols + static_cast<double>(p.text_tokens) * (L - cl.n_cols);
         break;
       }
       default:
         break;
+    }
+    // the text rows of a sparse head are computed densely on top of its list
+    if (has_text_rows(p, g)) {
+      *tiles += static_cast<int64_t>(p.text_tokens / p.block_q) * p.n_k_blocks;
+      *area += static_cast<double>(p.text_tokens) * L;
     }
   }
 }
@@ -413,6 +459,22 @@ svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* com
   return SVD_OK;
 }
 
+// The dense launch over the text rows of a sparse group, derived from the group's own launch.
+static svd::AttnLaunch text_rows_launch(const svd_plan& sp, const svd::Group& g, const svd::AttnLaunch& a) {
+  const Plan& p = sp.p;
+  const size_t gi = static_cast<size_t>(&g - p.groups.data());
+  svd::AttnLaunch d = a;
+  d.n_q_blocks = p.text_tokens / p.block_q;
+  d.n_items = d.n_q_blocks * d.n_heads * d.B;
+  d.split = gi < sp.text_split.size() ? sp.text_split[gi] : 1;
+  d.partial = nullptr;
+  if (d.split > 1) {
+    d.n_items *= d.split;
+    d.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.text_partial_offset[gi]);
+  }
+  return d;
+}
+
 static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const void* q, const void* k,
                                const void* v, void* out, hipStream_t stream) {
   const Plan& p = sp.p;
@@ -438,6 +500,14 @@ static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const vo
     }
     err = svd::launch_attention(a, kmode, stream);
     if (err == hipSuccess && a.split > 1) err = svd::launch_combine(a, stream);
+    if (err == hipSuccess && has_text_rows(p, g)) {
+      // Section 4.1.1: text queries see every key.  Their rows (the first
+      // T / block_q query tiles of every head of the group) are computed by the
+      // dense kernel, after the group's own launch on the same stream.
+      svd::AttnLaunch d = text_rows_launch(sp, g, a);
+      err = svd::launch_attention(d, svd::MODE_DENSE, stream);
+      if (err == hipSuccess && d.split > 1) err = svd::launch_combine(d, stream);
+    }
   }
   return err == hipSuccess ? SVD_OK : SVD_ERR_HIP;
 }
@@ -597,7 +667,10 @@ svd_status svd_plan_head_sparsity(const svd_plan* plan, double* sparsity) {
       double kept = 0.0;
       if (g.mode == SVD_DENSE) kept = all;
       else if (g.mode == SVD_DIAG || g.mode == SVD_MULTIDIAG) kept = g.bands[g.list_id[t]].kept_pairs;
-      else if (g.mode == SVD_VSTRIPE) kept = static_cast<double>(g.columns[g.list_id[t]].n_cols) * p.desc.L;
+      else if (g.mode == SVD_VSTRIPE) {
+        const double n_cols = g.columns[g.list_id[t]].n_cols;
+        kept = n_cols * p.desc.L + static_cast<double>(p.text_tokens) * (p.desc.L - n_cols);
+      }
       sparsity[g.heads[t]] = 1.0 - kept / all;
     }
   }
@@ -796,6 +869,17 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
   }
   if (svd::launch_attention_fp8(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
   if (a.split > 1 && svd::launch_combine(a, stream) != hipSuccess) return SVD_ERR_HIP;
+  if (has_text_rows(p, g)) {
+    // text rows: dense over every key; a stripe head's arrays hold its columns
+    // only, so they are quantised once more, uncompacted
+    a.split = 1;
+    a.n_items = a.n_q_blocks * a.n_heads * a.B;
+    if (g.mode == SVD_VSTRIPE && svd::launch_quantise_kv(f, svd::MODE_DENSE, stream) != hipSuccess) return SVD_ERR_HIP;
+    svd::Fp8Launch t = f;
+    t.a = text_rows_launch(sp, g, a);
+    if (svd::launch_attention_fp8(t, svd::MODE_DENSE, stream) != hipSuccess) return SVD_ERR_HIP;
+    if (t.a.split > 1 && svd::launch_combine(t.a, stream) != hipSuccess) return SVD_ERR_HIP;
+  }
   return SVD_OK;
 }
 

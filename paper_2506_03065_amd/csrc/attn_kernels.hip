@@ -151,6 +151,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
       entries = (const_int2_ptr)(uintptr_t)(p.ws + rec[1]) + e0;
       runs = (const_int2_ptr)(uintptr_t)(p.ws + rec[2]);
       n_tiles = e1 - e0;
+      if (n_tiles == 0) return;   // rows that another launch computes (text rows of a layer with a text prefix)
     } else {
       cols = p.ws + rec[0];
       n_tiles = rec[1] / BC;

@@ -225,6 +225,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       entries = (const_int2_ptr)(uintptr_t)(p.ws + rec[1]) + e0;
       runs = (const_int2_ptr)(uintptr_t)(p.ws + rec[2]);
       n_tiles = e1 - e0;
+      if (n_tiles == 0) return;   // rows that another launch computes (text rows of a layer with a text prefix)
     } else {
       n_tiles = rec[1] / BC;
       n_keys = rec[2];

@@ -70,21 +70,27 @@ struct Entry {
   int32_t kb, flag, first, count;
 };
 
-void build_band_list(BandList* bl, int64_t L, int64_t bq, int64_t bk) {
+// T > 0 (a multiple of bq and bk): text prefix of Section 4.1.1.  Query blocks of
+// text rows get no entries; the others list the text tiles first, kept whole.
+void build_band_list(BandList* bl, int64_t L, int64_t bq, int64_t bk, int64_t T) {
   const int64_t n_qb = ceil_div(L, bq);
   const size_t n_runs = bl->runs.size() / 2;
   bl->row_ptr.assign(1, 0);
-  bl->kept_pairs = 0.0;
+  // element-level pairs: text rows and text columns whole, plus the band inside
+  // the video x video square, which has the structure of a sequence of L - T
+  const int64_t Lv = L - T;
+  bl->kept_pairs = static_cast<double>(T) * L + static_cast<double>(Lv) * T;
   for (size_t r = 0; r < n_runs; ++r) {
-    const int64_t a = bl->runs[2 * r], b = bl->runs[2 * r + 1];
+    const int64_t a = std::max<int64_t>(bl->runs[2 * r], -(Lv - 1)), b = std::min<int64_t>(bl->runs[2 * r + 1], Lv - 1);
+    if (a > b) continue;
     // diagonal delta holds L - |delta| cells: (b - a + 1) * L - sum |delta|
     double pairs = 0.0;
     if (a >= 0) {
-      pairs = static_cast<double>(b - a + 1) * L - (static_cast<double>(a + b) * (b - a + 1)) / 2.0;
+      pairs = static_cast<double>(b - a + 1) * Lv - (static_cast<double>(a + b) * (b - a + 1)) / 2.0;
     } else if (b <= 0) {
-      pairs = static_cast<double>(b - a + 1) * L - (static_cast<double>(-a - b) * (b - a + 1)) / 2.0;
+      pairs = static_cast<double>(b - a + 1) * Lv - (static_cast<double>(-a - b) * (b - a + 1)) / 2.0;
     } else {
-      pairs = static_cast<double>(b - a + 1) * L - static_cast<double>(b) * (b + 1) / 2.0 -
+      pairs = static_cast<double>(b - a + 1) * Lv - static_cast<double>(b) * (b + 1) / 2.0 -
               static_cast<double>(-a) * (-a + 1) / 2.0;
     }
     bl->kept_pairs += pairs;
@@ -94,6 +100,12 @@ void build_band_list(BandList* bl, int64_t L, int64_t bq, int64_t bk) {
   for (int64_t qb = 0; qb < n_qb; ++qb) {
     const int64_t i0 = qb * bq, i1 = std::min(L, i0 + bq) - 1;
     row.clear();
+    if (i0 < T) {   // text rows: dense, not listed
+      bl->row_ptr.push_back(static_cast<int32_t>(bl->kv_block_idx.size()));
+      continue;
+    }
+    for (int64_t kb = 0; kb < T / bk; ++kb) row.push_back({static_cast<int32_t>(kb), 1, 0, 0});
+    const size_t n_text = row.size();
     for (size_t r = 0; r < n_runs; ++r) {
       const int64_t a = bl->runs[2 * r], b = bl->runs[2 * r + 1];
       const int64_t j_lo = std::max<int64_t>(0, i0 + a), j_hi = std::min<int64_t>(L - 1, i1 + b);
@@ -107,6 +119,7 @@ void build_band_list(BandList* bl, int64_t L, int64_t bq, int64_t bk) {
         const int64_t jt0 = kb * bk, jt1 = kb * bk + bk - 1;
         const bool full = jt1 <= L - 1 && a <= jt0 - i1 && jt1 - i0 <= b;
         if (pos < row.size() && row[pos].kb == kb) {
+          if (pos < n_text && row[pos].count == 0) row[pos].first = static_cast<int32_t>(r);   // a text tile the band reaches
           row[pos].count += 1;
           row[pos].flag |= full ? 1 : 0;
           ++pos;
@@ -153,11 +166,15 @@ svd_status validate_desc(const svd_tensor_desc* desc) {
 
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
-                        Plan* plan) {
+                        int32_t text_tokens, Plan* plan) {
   if (!strategy_table || !pattern_params || !plan) return SVD_ERR_NULL;
   if (svd_status st = validate_desc(&desc)) return st;
   if (block_q < 1 || block_k < 1) return SVD_ERR_UNSUPPORTED;
   const int64_t L = desc.L;
+  const int64_t T = text_tokens;
+  if (T < 0 || T >= L) return SVD_ERR_PARAMS;
+  if (T % block_q || T % block_k) return SVD_ERR_UNSUPPORTED;
+  plan->text_tokens = text_tokens;
   plan->desc = desc;
   plan->block_q = block_q;
   plan->block_k = block_k;
@@ -197,8 +214,8 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
           bl.offsets = offs;
           bl.runs = merged_runs(offs, p.half_width, L);
           if (bl.runs.size() / 2 > static_cast<size_t>(kMaxRuns)) return SVD_ERR_UNSUPPORTED;
-          if (!every_row_keeps_a_key(bl.runs, L)) return SVD_ERR_EMPTY_PATTERN;
-          build_band_list(&bl, L, block_q, block_k);
+          if (T == 0 && !every_row_keeps_a_key(bl.runs, L)) return SVD_ERR_EMPTY_PATTERN;   // text keys are kept by every row
+          build_band_list(&bl, L, block_q, block_k, T);
           id = static_cast<int32_t>(g.bands.size());
           band_ids.emplace(std::move(key), id);
           g.bands.push_back(std::move(bl));
@@ -212,12 +229,19 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
         std::sort(cols.begin(), cols.end());
         if (cols.front() < 0 || cols.back() >= L) return SVD_ERR_PARAMS;
         if (std::adjacent_find(cols.begin(), cols.end()) != cols.end()) return SVD_ERR_PARAMS;
+        if (T > 0) {   // the text columns belong to every stripe head
+          std::vector<int32_t> with_text;
+          for (int32_t c = 0; c < T; ++c) with_text.push_back(c);
+          for (int32_t c : cols)
+            if (c >= T) with_text.push_back(c);
+          cols.swap(with_text);
+        }
         auto it = col_ids.find(cols);
         if (it == col_ids.end()) {
           ColumnList cl;
-          cl.n_cols = p.n_cols;
+          cl.n_cols = static_cast<int32_t>(cols.size());
           cl.cols = cols;
-          cl.cols.resize(static_cast<size_t>(ceil_div(p.n_cols, block_k) * block_k), -1);
+          cl.cols.resize(static_cast<size_t>(ceil_div(cl.n_cols, block_k) * block_k), -1);
           id = static_cast<int32_t>(g.columns.size());
           col_ids.emplace(std::move(cols), id);
           g.columns.push_back(std::move(cl));

@@ -24,13 +24,13 @@ struct BandList {
   std::vector<int32_t> flags;         // per entry: 1 = tile needs no mask
   std::vector<int32_t> run_first;     // per entry
   std::vector<int32_t> run_count;     // per entry
-  double kept_pairs = 0.0;            // element-level count for one head
+  double kept_pairs = 0.0;            // element-level count for one head (text borders included)
   double tile_area = 0.0;             // sum over entries of in-range rows * in-range keys
 };
 
 // One distinct column set (mode 4).
 struct ColumnList {
-  int32_t n_cols = 0;
+  int32_t n_cols = 0;                 // text columns included
   std::vector<int32_t> cols;          // sorted, padded with -1 to a multiple of block_k
 };
 
@@ -56,6 +56,9 @@ struct Plan {
   svd_tensor_desc desc{};
   int32_t block_q = 0, block_k = 0;
   int32_t n_q_blocks = 0, n_k_blocks = 0;
+  // Section 4.1.1: length of the text prefix whose borders (T-T, T-V, V-T) the
+  // sparse heads keep whole; 0 = none.  A multiple of block_q and of block_k.
+  int32_t text_tokens = 0;
   std::vector<Group> groups;          // ascending mode id
   std::vector<int32_t> ws_image;      // host image of the device workspace
   void* device_workspace = nullptr;   // nullptr: host-only plan
@@ -64,9 +67,13 @@ struct Plan {
 
 // Validates the table and parameters and fills plan->groups (lists included)
 // and plan->ws_image.  Pure host code, no HIP.
+// text_tokens > 0: the band lists of the text query blocks stay empty (their rows
+// are computed densely by the caller of the kernels), every other query block
+// lists the text key tiles, kept whole, ahead of its band tiles, and the column
+// lists gain the text columns.
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
-                        Plan* plan);
+                        int32_t text_tokens, Plan* plan);
 
 svd_status validate_desc(const svd_tensor_desc* desc);
 

@@ -143,7 +143,29 @@ def stack_layer(layer: int, n_layers: int = 40) -> Workload:
     return wl
 
 
-BY_NAME = {"tiny": tiny, "cogvideox1.5": cogvideox15, "hunyuanvideo": hunyuanvideo, "wan2.1": wan21}
+def with_text_borders(wl: Workload, text_tokens=None) -> Workload:
+    """The same layer with the borders of the text prefix kept whole by every
+    sparse head (Section 4.1.1: T-T, T-V and V-T around the V-V pattern): the
+    parameter dicts of the sparse heads gain the key "text_tokens".  Default
+    prefix: the workload's own text tokens."""
+    import copy
+    T = wl.text_tokens if text_tokens is None else int(text_tokens)
+    out = copy.copy(wl)
+    out.name = f"{wl.name}+text{T}"
+    out.text_tokens = T
+    out.notes = dict(wl.notes)
+    out.pattern_params = [dict(p, text_tokens=T) if int(m) >= DIAG else dict(p)
+                          for m, p in zip(wl.strategy_table, wl.pattern_params)]
+    return out
+
+
+def hunyuanvideo_text() -> Workload:
+    """The HunyuanVideo-shaped layer with the borders of its 256 text tokens kept whole."""
+    return with_text_borders(hunyuanvideo())
+
+
+BY_NAME = {"tiny": tiny, "cogvideox1.5": cogvideox15, "hunyuanvideo": hunyuanvideo, "wan2.1": wan21,
+           "hunyuanvideo+text": hunyuanvideo_text}
 
 
 def small(L=333, H=5, D=64, seed=7, B=1) -> Workload:

@@ -50,7 +50,7 @@ def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
             if g["mode"] == svd.SVD_VSTRIPE:
                 got = plan.column_list(gi, lst)
                 want = O.column_list(p, wl.L, bk)
-                assert got["n_cols"] == len(p["cols"])
+                assert got["n_cols"] == len(set(p["cols"]) | set(range(O.text_tokens_of(p))))
                 assert got["cols"].dtype == np.int32 and np.array_equal(got["cols"], want)
                 continue
             got = plan.band_list(gi, lst)
@@ -205,3 +205,61 @@ def test_workspace_holds_lists_and_the_scratch_of_a_forced_dense_split():
         assert got == (want if n_dense else base)
     with pytest.raises(svd.SvdError):
         svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=-1)
+
+
+# ---- text prefix (Section 4.1.1): borders kept whole by the sparse heads ----
+
+@pytest.mark.parametrize("L,D,seed,bq,bk,T", [(600, 64, 7, 64, 32, 64), (1000, 128, 3, 256, 64, 256),
+                                               (1000, 64, 4, 256, 128, 256), (333, 64, 5, 16, 8, 32),
+                                               (700, 128, 6, 256, 64, 512)])
+def test_text_prefix_lists_bit_exact(L, D, seed, bq, bk, T):
+    wl = W.with_text_borders(W.small(L=L, D=D, H=10, seed=seed), T)
+    _assert_plan_matches_oracle(wl, bq, bk)
+
+
+@pytest.mark.parametrize("mode,p,L,bq,bk", [
+    (O.MODE_DIAG, {"half_width": 0, "text_tokens": 16}, 130, 16, 8),                       # band never reaches the text
+    (O.MODE_DIAG, {"half_width": 1000, "text_tokens": 16}, 130, 16, 16),                   # band covers everything
+    (O.MODE_MULTIDIAG, {"half_width": 2, "offsets": (-40, 0, 40), "text_tokens": 32}, 150, 32, 8),
+    (O.MODE_MULTIDIAG, {"half_width": 1, "offsets": (50,), "text_tokens": 8}, 60, 8, 8),   # rows that keep text keys only
+])
+def test_text_prefix_band_edge_cases_bit_exact(mode, p, L, bq, bk):
+    _assert_plan_matches_oracle(_one_head(mode, p, L), bq, bk)
+
+
+def test_text_prefix_counts_and_validation():
+    L, T = 1000, 256
+    wl = W.with_text_borders(W.small(L=L, D=64, H=5, seed=9), T)
+    plan = _compile(wl, 256, 128)
+    # element-level sparsity against the explicit mask
+    sp = plan.head_sparsity()
+    for h in range(wl.H):
+        mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+        want = 0.0 if mode == W.DENSE else 1.0 if mode == W.SKIP else 1.0 - O.mask_popcount(mode, p, L) / L ** 2
+        assert abs(sp[h] - want) < 1e-12, (h, mode)
+    # computed tiles: the lists plus one dense query tile of text rows per sparse head
+    n_kb = -(-L // 128)
+    want_tiles = n_kb * -(-L // 256)                                  # the dense head
+    for h in range(wl.H):
+        mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
+        if mode in O.BAND_MODES:
+            want_tiles += O.block_lists(mode, p, L, 256, 128)["kv_block_idx"].size + (T // 256) * n_kb
+        elif mode == W.VSTRIPE:
+            want_tiles += -(-L // 256) * (O.column_list(p, L, 128).size // 128) + (T // 256) * n_kb
+    assert plan.work()["computed_tiles"] == want_tiles
+    plan.close()
+    desc = svd.tensor_desc(1, wl.H, L, 64)
+    for T_bad, status in ((100, 9), (128, 9), (1024, 6), (-256, 6)):   # not a multiple of both blocks; not shorter than L
+        with pytest.raises(svd.SvdError) as e:
+            svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, 256, 128, text_tokens=T_bad)
+        assert e.value.status == status, T_bad
+    mixed = [dict(p) for p in wl.pattern_params]
+    mixed[1]["text_tokens"] = 512
+    with pytest.raises(ValueError):
+        svd.svd_plan_create(desc, wl.strategy_table, mixed, 256, 128)
+    # a pattern that leaves rows without band keys is accepted once they keep the text keys
+    lonely = W.with_text_borders(_one_head(O.MODE_MULTIDIAG, {"half_width": 1, "offsets": (50,)}, 600), 256)
+    _compile(lonely, 256, 128).close()
+    with pytest.raises(svd.SvdError) as e:
+        _compile(_one_head(O.MODE_MULTIDIAG, {"half_width": 1, "offsets": (50,)}, 600), 256, 128)
+    assert e.value.status == 7
