@@ -118,11 +118,12 @@ bool has_text_rows(const Plan& p, const svd::Group& g) {
 
 // Key-range chunks of the dense launch over the text rows of one sparse group:
 // few query tiles (T / block_q per head) against every key, so the key range is
-// cut until about two work-groups per compute unit exist, chunks of 8 tiles at least.
+// cut until about one work-group per compute unit exists, chunks of 8 tiles at least
+// (the merge pass walks the chunks one after the other).
 int choose_text_split(const Plan& p, const svd::Group& g, int n_cu) {
   if (n_cu < 1) return 1;
   const long long base = static_cast<long long>(p.text_tokens / p.block_q) * g.heads.size() * p.desc.B;
-  long long s = (2LL * n_cu + base - 1) / base;
+  long long s = n_cu / base;   // rounded down: one more item than compute units would cost a whole second round
   const long long cap = p.n_k_blocks / 8 > 64 ? 64 : p.n_k_blocks / 8;
   if (s > cap) s = cap;
   return s < 1 ? 1 : static_cast<int>(s);

@@ -632,24 +632,31 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 }
 
 
-// Merge of a split dense launch: work-group = (query tile, head, batch entry),
-// same thread-to-element mapping as attn_fwd_kernel.  Chunks are folded one by
-// one with the online-softmax rule: O = O * 2^(m - m') + O_c * 2^(m_c - m').
-template <int D, int NW>
+// Merge of a split dense launch: work-group = (query tile, head, batch entry,
+// slice of RPS accumulator rows), same thread-to-element mapping as
+// attn_fwd_kernel.  Chunks are folded one by one with the online-softmax rule:
+// O = O * 2^(m - m') + O_c * 2^(m_c - m').  RPS = all rows for the few chunks of
+// a dense group; launches with many chunks and few query tiles (the text rows
+// of a layer with a text prefix) use slices of four rows, so that the chain over
+// the chunks is short per thread and spread over many work-groups.
+template <int D, int NW, int RPS>
 __global__ void __launch_bounds__(NW * 64) combine_partials_kernel(const AttnLaunch p) {
   constexpr int DB = D / 32;
   constexpr int BR = NW * 32;
+  static_assert(RPS % 4 == 0 && (DB * 16) % RPS == 0, "a slice is a whole number of 4-row groups");
   const int qblk = blockIdx.x % p.n_q_blocks;
   const int hb = blockIdx.x / p.n_q_blocks;
   const int hg = hb % p.n_heads;
   const int b = hb / p.n_heads;
   const int head = p.heads ? p.heads[hg] : hg;
+  const int r0 = blockIdx.y * RPS;     // first accumulator row of this slice
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  float o[DB * 16];
+  float o[RPS];
 #pragma unroll
-  for (int r = 0; r < DB * 16; ++r) o[r] = 0.f;
+  for (int r = 0; r < RPS; ++r) o[r] = 0.f;
   float m = kNegInf, l = 0.f;
+#pragma unroll 2
   for (int c = 0; c < p.split; ++c) {
     const size_t item = ((size_t)hb * p.split + c) * p.n_q_blocks + qblk;
     const float* src = p.partial + (item * NW + wave) * ((DB * 16 + 2) * 64) + lane;
@@ -658,7 +665,7 @@ __global__ void __launch_bounds__(NW * 64) combine_partials_kernel(const AttnLau
     const float wa = __builtin_amdgcn_exp2f(m - m_new), wc = __builtin_amdgcn_exp2f(mc - m_new);
     l = l * wa + lc * wc;
 #pragma unroll
-    for (int r = 0; r < DB * 16; ++r) o[r] = o[r] * wa + src[r * 64] * wc;
+    for (int r = 0; r < RPS; ++r) o[r] = o[r] * wa + src[(r0 + r) * 64] * wc;
     m = m_new;
   }
   const float inv = 1.0f / l;
@@ -666,16 +673,14 @@ __global__ void __launch_bounds__(NW * 64) combine_partials_kernel(const AttnLau
   if (row < p.L) {
     __bf16* dst = p.out + (int64_t)b * p.stride_b + (int64_t)head * p.stride_h + (int64_t)row * p.stride_l;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x2 a01 = {o[db * 16 + g * 4 + 0] * inv, o[db * 16 + g * 4 + 1] * inv};
-        const f32x2 a23 = {o[db * 16 + g * 4 + 2] * inv, o[db * 16 + g * 4 + 3] * inv};
-        const bf16x2 b01 = __builtin_convertvector(a01, bf16x2);
-        const bf16x2 b23 = __builtin_convertvector(a23, bf16x2);
-        const bf16x4 out4 = {b01[0], b01[1], b23[0], b23[1]};
-        *reinterpret_cast<bf16x4*>(dst + db * 32 + g * 8 + half * 4) = out4;
-      }
+    for (int rr = 0; rr < RPS; rr += 4) {
+      const int db = (r0 + rr) / 16, g = ((r0 + rr) % 16) / 4;
+      const f32x2 a01 = {o[rr + 0] * inv, o[rr + 1] * inv};
+      const f32x2 a23 = {o[rr + 2] * inv, o[rr + 3] * inv};
+      const bf16x2 b01 = __builtin_convertvector(a01, bf16x2);
+      const bf16x2 b23 = __builtin_convertvector(a23, bf16x2);
+      const bf16x4 out4 = {b01[0], b01[1], b23[0], b23[1]};
+      *reinterpret_cast<bf16x4*>(dst + db * 32 + g * 8 + half * 4) = out4;
     }
   }
 }
@@ -745,11 +750,18 @@ size_t partial_floats(int D, int n_items) {
 hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream) {
   if (p.split <= 1 || p.n_items <= 0) return hipSuccess;
   if (!p.partial) return hipErrorInvalidValue;
-  const dim3 grid(p.n_items / p.split);
+  const int tiles = p.n_items / p.split;
+  const bool sliced = p.split > 8;   // many chunks: slices of four accumulator rows
   if (p.D == 128) {
-    hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW>), grid, dim3(Tile128::NW * 64), 0, stream, p);
+    if (sliced)
+      hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW, 4>), dim3(tiles, 16), dim3(Tile128::NW * 64), 0, stream, p);
+    else
+      hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW, 64>), dim3(tiles, 1), dim3(Tile128::NW * 64), 0, stream, p);
   } else if (p.D == 64) {
-    hipLaunchKernelGGL((combine_partials_kernel<64, Tile64::NW>), grid, dim3(Tile64::NW * 64), 0, stream, p);
+    if (sliced)
+      hipLaunchKernelGGL((combine_partials_kernel<64, Tile64::NW, 4>), dim3(tiles, 8), dim3(Tile64::NW * 64), 0, stream, p);
+    else
+      hipLaunchKernelGGL((combine_partials_kernel<64, Tile64::NW, 32>), dim3(tiles, 1), dim3(Tile64::NW * 64), 0, stream, p);
   } else {
     return hipErrorInvalidValue;
   }
