@@ -5,7 +5,7 @@ A step is one forward pass of the whole layer: the fused launch of every mode
 group of the per-head strategy table plus the zero fill of skipped heads, on
 Q/K/V already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|wan2.1|stack|search]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|hunyuanvideo+text|wan2.1|stack|search]
                     [--precision bf16|fp8]
 
 --precision fp8 times the FP8 (E4M3) variant of the same layer: a step then also
@@ -334,7 +334,7 @@ def main():
         "vs_baseline": None,
         "dtype": "fp8-e4m3 (fp32 accumulation)" if fp8 else "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "precision": args.precision, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
+        "config": {"workload": wl.name, "precision": args.precision, "text_tokens_with_dense_borders": int(wl.pattern_params[int((wl.strategy_table >= 2).argmax())].get("text_tokens", 0)) if (wl.strategy_table >= 2).any() else 0, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
