@@ -30,6 +30,9 @@ FP8_MFMA_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 matrix peak
 # Dense group of the CogVideoX1.5-like layer = the attention kernel over three
 # key-range chunks plus the merge kernel: (2*325302 + 243360) + (2*68979 + 21631) KiB.
 PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 325302 + 243360 + 2 * 68979 + 21631) * 1024}}
+# FP8 variant, dense group of the HunyuanVideo-like layer = pre-pass + attention kernel:
+# (2*28892 + 28864) + (2*273879 + 91146) KiB.
+PMC_TRAFFIC_BYTES_FP8 = {"hunyuanvideo": {"dense": (2 * 28892 + 28864 + 2 * 273879 + 91146) * 1024}}
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
@@ -295,7 +298,7 @@ def main():
     peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
     roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[{dom['mode']} group]",
                 "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(dom["tflops"] / peak, 4),
-                "traffic": None if fp8 else PMC_TRAFFIC_BYTES.get(wl.name, {}).get(dom["mode"])}
+                "traffic": (PMC_TRAFFIC_BYTES_FP8 if fp8 else PMC_TRAFFIC_BYTES).get(wl.name, {}).get(dom["mode"])}
     bf16_ms = gpu_time_ms(step16, max(3, args.steps // 2), 1, torch) if fp8 else None
 
     # ---- in-house dense kernel on all heads: the speed-up baseline ----
