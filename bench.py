@@ -5,7 +5,7 @@ A step is one forward pass of the whole layer: the fused launch of every mode
 group of the per-head strategy table plus the zero fill of skipped heads, on
 Q/K/V already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|hunyuanvideo+text|wan2.1|stack|search]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|hunyuanvideo+text|wan2.1|stack|search|rearranged]
                     [--precision bf16|fp8]
 
 --precision fp8 times the FP8 (E4M3) variant of the same layer: a step then also
@@ -206,6 +206,70 @@ def run_search(args, torch, np, svd, W):
     print(json.dumps(result))
 
 
+def run_rearranged(args, torch, np, svd, W):
+    """Section 4.1.2: attention between nearby positions of all frames, computed (a)
+    as the multi-diagonal mode with every frame offset on the frame-major order and
+    (b) as the diagonal mode on rearranged (position-major) tokens: three
+    rearrangements in, one out.  Wan2.1-like shape, 8 heads."""
+    dev = "cuda:0"
+    H, D, N, F, w = 8, 128, 3600, 21, 40
+    L = N * F
+    gen = torch.Generator().manual_seed(20250603)
+    q, k, v = (torch.randn(1, H, L, D, generator=gen).to(torch.bfloat16).to(dev) for _ in range(3))
+    out = torch.empty_like(q)
+    desc = svd.desc_of(q)
+
+    def planned(table, params):
+        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, table, params), dtype=torch.uint8, device=dev)
+        return svd.svd_plan_create(desc, table, params, workspace=ws), ws
+    multi, ws_a = planned(np.full(H, W.MULTIDIAG, dtype=np.int32),
+                          [{"half_width": w, "offsets": tuple(kk * N for kk in range(-(F - 1), F))}] * H)
+    Wd = w * F + F - 1
+    diag, ws_b = planned(np.full(H, W.DIAG, dtype=np.int32), [{"half_width": Wd}] * H)
+    qp, kp, vp, op = (torch.empty_like(q) for _ in range(4))
+
+    def step():
+        for src, dst in ((q, qp), (k, kp), (v, vp)):
+            svd.svd_rearrange_tokens(src, dst, 0, N, F)
+        svd.svd_attn_forward_planned(diag, qp, kp, vp, op)
+        svd.svd_rearrange_tokens(op, out, 0, N, F, inverse=True)
+    t_warm = time.perf_counter()
+    while time.perf_counter() - t_warm < 1.5:
+        step()
+        torch.cuda.synchronize()
+    ms = gpu_time_ms(step, args.steps, args.warmup, torch)
+    ms_move = gpu_time_ms(lambda: svd.svd_rearrange_tokens(q, qp, 0, N, F), args.steps, 1, torch)
+    ms_back = gpu_time_ms(lambda: svd.svd_rearrange_tokens(op, out, 0, N, F, inverse=True), args.steps, 1, torch)
+    ms_diag = gpu_time_ms(lambda: svd.svd_attn_forward_planned(diag, qp, kp, vp, op), args.steps, 1, torch)
+    ms_multi = gpu_time_ms(lambda: svd.svd_attn_forward_planned(multi, q, k, v, out), max(2, args.steps // 2), 1, torch)
+    tensor_bytes = q.numel() * 2
+    wd, wm = diag.work(), multi.work()
+    result = {
+        "metric": "position-window attention latency (tokens rearranged to position-major order)",
+        "value": round(ms, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "rearranged window, Wan2.1-like shape", "B": 1, "H": H, "L": L, "D": D,
+                   "frame_tokens": N, "frames": F, "position_half_width": w, "band_half_width": Wd},
+        "rearrange_one_tensor_ms": round(ms_move, 4), "rearrange_back_ms": round(ms_back, 4),
+        "diagonal_on_rearranged_ms": round(ms_diag, 4),
+        "diagonal_tflops": round(wd["computed_flops"] / 1e9 / ms_diag, 1),
+        "computed_tiles": wd["computed_tiles"],
+        "multi_diagonal_all_offsets_ms": round(ms_multi, 4),
+        "multi_diagonal_all_offsets_tiles": wm["computed_tiles"],
+        "speedup_vs_multi_diagonal_lists": round(ms_multi / ms, 3),
+        "roofline": {"bound": "hbm", "kernel": "rearrange_tokens_kernel", "achieved": round(2 * tensor_bytes / 1e6 / ms_move, 1),
+                     "peak": 8000.0, "unit": "GB/s", "frac": round(2 * tensor_bytes / 1e6 / ms_move / 8000.0, 4),
+                     "traffic": None},
+        "cpu_baseline": None,
+        "note": "the two paths keep different pairs at frame edges: diagonals on the frame-major index wrap from "
+                "the end of a frame into the next one, the window in position-major order does not",
+    }
+    print(json.dumps(result))
+    multi.close()
+    diag.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -236,14 +300,17 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     fp8 = args.precision == "fp8"
-    if fp8 and args.workload == "search":
-        print("--precision fp8: the search step is built in bf16 only", file=sys.stderr)
+    if fp8 and args.workload in ("search", "rearranged"):
+        print("--precision fp8: this workload is built in bf16 only", file=sys.stderr)
         sys.exit(2)
     if args.workload == "stack":
         run_stack(args, torch, np, svd, W)
         return
     if args.workload == "search":
         run_search(args, torch, np, svd, W)
+        return
+    if args.workload == "rearranged":
+        run_rearranged(args, torch, np, svd, W)
         return
     wl = W.BY_NAME[args.workload]()
     t0 = time.perf_counter()

@@ -261,6 +261,24 @@ svd_status svd_search_layer(const void* q, const void* k, const void* v, const s
                             int32_t* table, double* loss, void* out, void* device_workspace,
                             size_t workspace_bytes, void* hip_stream);
 
+/* ---- Token rearrangement (Section 4.1.2, multi-diagonal pattern) ----
+ * Video tokens are ordered frame by frame (Section 4.1.1); the evenly spaced
+ * diagonals of the multi-diagonal pattern are attention between nearby spatial
+ * positions of different frames, and the paper notes that rearranging the tokens
+ * turns them into one diagonal band that window attention computes.  This call
+ * is that rearrangement: with F = frames frames of N = frame_tokens tokens
+ * starting at token first_video_token, the token of frame f and position p moves
+ * from row first + f*N + p to row first + p*F + f (inverse != 0: back); rows
+ * outside the video block are copied unchanged.  A caller rearranges q, k and v,
+ * runs the diagonal mode with half width w*F + F - 1 on them (every pair of
+ * positions at most w apart, in any two frames) and rearranges the output back.
+ * src, dst: DEVICE bf16 tensors of layout desc, distinct and not overlapping
+ * (SVD_ERR_UNSUPPORTED for src == dst).  SVD_ERR_PARAMS when the video block does
+ * not fit L.  One streaming kernel on hip_stream; no synchronisation, no
+ * allocation. */
+svd_status svd_rearrange_tokens(const void* src, void* dst, const svd_tensor_desc* desc, int32_t first_video_token,
+                                int32_t frame_tokens, int32_t frames, int32_t inverse, void* hip_stream);
+
 /* ---- FP8 variant (Appendix B, Table 4: "Sparse-vDiT + FP8") ----
  * The paper combines the sparse kernels with FP8 quantisation but gives no
  * recipe.  This library's reading: OCP E4M3 operands with fixed power-of-two

@@ -28,7 +28,7 @@ EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", 
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
            "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
-           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8", "svd_attn_forward_fp8_group"]
+           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8", "svd_attn_forward_fp8_group", "svd_rearrange_tokens"]
 
 
 class SvdError(RuntimeError):
@@ -91,6 +91,7 @@ def lib():
             "svd_search_layer_workspace_bytes": [descp, C.POINTER(hpp), C.POINTER(C.c_size_t)],
             "svd_search_layer": [vp, vp, vp, descp, C.POINTER(hpp), C.c_double, C.c_double, i32p,
                                  C.POINTER(C.c_double), vp, vp, C.c_size_t, vp],
+            "svd_rearrange_tokens": [vp, vp, descp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp],
             "svd_fp8_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
             "svd_attn_forward_fp8": [vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
             "svd_attn_forward_fp8_group": [vp, C.c_int32, vp, vp, vp, vp, vp, C.c_size_t, vp],
@@ -294,6 +295,16 @@ def svd_attn_forward_planned(plan: Plan, q, k, v, out, stream=None):
     _check(lib().svd_attn_forward_planned(plan.handle, _dev(q), _dev(k), _dev(v), _dev(out), _stream_ptr(stream)),
            "svd_attn_forward_planned")
     return out
+
+
+def svd_rearrange_tokens(src, dst, first_video_token, frame_tokens, frames, inverse=False, stream=None):
+    """src, dst: distinct CUDA bf16 tensors of one [B, H, L, D] layout."""
+    if dst.shape != src.shape or dst.stride() != src.stride():
+        raise ValueError("src and dst must share shape and strides")
+    desc = desc_of(src)
+    _check(lib().svd_rearrange_tokens(_dev(src), _dev(dst), C.byref(desc), int(first_video_token), int(frame_tokens),
+                                      int(frames), 1 if inverse else 0, _stream_ptr(stream)), "svd_rearrange_tokens")
+    return dst
 
 
 def svd_fp8_workspace_bytes(desc) -> int:

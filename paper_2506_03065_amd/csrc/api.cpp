@@ -15,6 +15,7 @@
 #include "attn_kernels.h"
 #include "fp8_kernels.h"
 #include "plan.h"
+#include "rearrange_kernels.h"
 #include "search_kernels.h"
 #include "sparse_vdit.h"
 
@@ -821,6 +822,24 @@ svd_status svd_search_layer(const void* q, const void* k, const void* v, const s
     return SVD_ERR_HIP;
   if (svd_status st = svd_search_select(H, mse.data(), sparsity.data(), lambda, epsilon, table, loss)) return st;
   return svd_select_heads(o_modes, &cdesc, table, out, desc, hip_stream);
+}
+
+// ---- token rearrangement (Section 4.1.2) ----
+
+svd_status svd_rearrange_tokens(const void* src, void* dst, const svd_tensor_desc* desc, int32_t first_video_token,
+                                int32_t frame_tokens, int32_t frames, int32_t inverse, void* hip_stream) {
+  if (!src || !dst || !desc) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  if (!aligned16(src) || !aligned16(dst)) return SVD_ERR_ALIGN;
+  if (first_video_token < 0 || frame_tokens < 1 || frames < 1) return SVD_ERR_PARAMS;
+  if (static_cast<int64_t>(first_video_token) + static_cast<int64_t>(frame_tokens) * frames > desc->L)
+    return SVD_ERR_PARAMS;
+  if (src == dst) return SVD_ERR_UNSUPPORTED;   // rows move: not an in-place operation
+  if (svd::launch_rearrange_tokens(static_cast<const __bf16*>(src), static_cast<__bf16*>(dst), view_of(*desc),
+                                   first_video_token, frame_tokens, frames, inverse != 0,
+                                   static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SVD_ERR_HIP;
+  return SVD_OK;
 }
 
 // ---- FP8 variant (Appendix B) ----
