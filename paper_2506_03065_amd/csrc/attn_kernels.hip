@@ -751,14 +751,13 @@ hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream) {
   if (p.split <= 1 || p.n_items <= 0) return hipSuccess;
   if (!p.partial) return hipErrorInvalidValue;
   const int tiles = p.n_items / p.split;
-  const bool sliced = p.split > 8;   // many chunks: slices of four accumulator rows
   if (p.D == 128) {
-    if (sliced)
-      hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW, 4>), dim3(tiles, 16), dim3(Tile128::NW * 64), 0, stream, p);
-    else
-      hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW, 64>), dim3(tiles, 1), dim3(Tile128::NW * 64), 0, stream, p);
+    // always in slices of four accumulator rows (measured: the merge of the Wan2.1-like
+    // dense group, three chunks, takes 175 us unsliced and about 70 us sliced)
+    hipLaunchKernelGGL((combine_partials_kernel<128, Tile128::NW, 4>), dim3(tiles, 16), dim3(Tile128::NW * 64), 0, stream, p);
   } else if (p.D == 64) {
-    if (sliced)
+    // sliced for many chunks only; for the few chunks of a dense group the unsliced form is as fast
+    if (p.split > 8)
       hipLaunchKernelGGL((combine_partials_kernel<64, Tile64::NW, 4>), dim3(tiles, 8), dim3(Tile64::NW * 64), 0, stream, p);
     else
       hipLaunchKernelGGL((combine_partials_kernel<64, Tile64::NW, 32>), dim3(tiles, 1), dim3(Tile64::NW * 64), 0, stream, p);
