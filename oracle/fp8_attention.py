@@ -9,8 +9,8 @@ What it follows in the paper
 Appendix B (Table 4, "Sparse-vDiT + FP8") combines the sparse kernels of
 Section 4.2 with FP8 quantisation.  The paper gives no recipe: neither the FP8
 format, nor which operands are quantised, nor the granularity of the scales.
-This oracle therefore fixes one (every choice is listed in the design notes as a
-reading) and states it as a quantise-dequantise definition on top of Eq. 1:
+This oracle therefore fixes one (every choice below is a reading of this build,
+not of the paper) and states it as a quantise-dequantise definition on top of Eq. 1:
 
 * format: OCP FP8 E4M3 (4 exponent bits, bias 7, 3 mantissa bits, largest finite
   value 448, subnormals down to 2^-9, no infinities), round to nearest even,

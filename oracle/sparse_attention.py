@@ -22,7 +22,7 @@ What it follows in the paper
   head whose parameters carry text_tokens = T > 0 (text first) keeps the three
   border regions whole: key j < T for every query, every key for query i < T.
 
-Readings where the paper is silent (all listed in the design notes):
+Readings where the paper is silent:
 the band is inclusive (|delta| <= w), several bands form a union, the softmax is
 renormalised over the kept keys, a row without any kept key is an error, modes
 are numbered 0 dense, 1 skip, 2 diagonal, 3 multi-diagonal, 4 vertical-stripe.
