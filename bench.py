@@ -131,6 +131,17 @@ def run_stack(args, torch, np, svd, W):
     del dense_out
     work = [p.work() for p in plans]
     computed = sum(w["computed_flops"] for w in work)
+    # dominant kernel of the stack: the dense group of the first layer (most dense heads)
+    g0 = [gi for gi, g in enumerate(plans[0].groups()) if g["mode"] == 0]
+    roofline = None
+    if g0:
+        run0 = ((lambda: svd.svd_attn_forward_fp8_group(plans[0], g0[0], q, k, v, out, ws8)) if fp8 else
+                (lambda: svd.svd_attn_forward_group(plans[0], g0[0], q, k, v, out)))
+        ms0 = gpu_time_ms(run0, 3, 1, torch)
+        tf0 = plans[0].work(g0[0])["computed_flops"] / 1e9 / ms0
+        peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
+        roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[dense group of layer 0]",
+                    "achieved": round(tf0, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf0 / peak, 4), "traffic": None}
     dense_flops = wl0.dense_flops * n_layers
     cpu = None
     if args.cpu_seconds > 0:
@@ -155,7 +166,7 @@ def run_stack(args, torch, np, svd, W):
         "flop_reduction_block_level": round(dense_flops / computed, 3),
         "per_layer_ms": [round(x, 2) for x in per_layer],
         "plan_create_ms": round(plan_ms, 1),
-        "roofline": None,
+        "roofline": roofline,
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))
