@@ -40,16 +40,7 @@ import numpy as np
 from . import sparse_attention as SA
 
 
-def position_major_index(L, first, frame_tokens, frames):
-    """pi: int64 [L], the index every token has after the rearrangement."""
-    N, F = int(frame_tokens), int(frames)
-    if first < 0 or N < 1 or F < 1 or first + N * F > L:
-        raise ValueError("the video block does not fit the sequence")
-    pi = np.arange(L, dtype=np.int64)
-    v = np.arange(N * F, dtype=np.int64)
-    f, p = v // N, v % N
-    pi[first:first + N * F] = first + p * F + f
-    return pi
+position_major_index = SA.position_major_index   # the index map, stated once in the attention oracle
 
 
 def rearrange(x, first, frame_tokens, frames, inverse=False):

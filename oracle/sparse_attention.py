@@ -22,6 +22,13 @@ What it follows in the paper
   head whose parameters carry text_tokens = T > 0 (text first) keeps the three
   border regions whole: key j < T for every query, every key for query i < T.
 
+* Section 4.1.2 (multi-diagonal pattern): "by rearranging tokens" the evenly
+  spaced diagonals become one diagonal band.  A multi-diagonal head whose
+  parameters carry rearranged = (first, frame_tokens, frames) is that form: with
+  pi the move from frame-major to position-major order of the video block, it
+  keeps (i, j) iff |pi(i) - pi(j)| <= half_width; its offsets are not used and
+  its block lists live in the rearranged order.
+
 Readings where the paper is silent:
 the band is inclusive (|delta| <= w), several bands form a union, the softmax is
 renormalised over the kept keys, a row without any kept key is an error, modes
@@ -60,6 +67,26 @@ def _offsets_of(mode, params):
     return offs
 
 
+def rearranged_of(params):
+    """(first, frame_tokens, frames) of a multi-diagonal head that is computed as a
+    window in position-major order, or None."""
+    r = params.get("rearranged") if params else None
+    return tuple(int(x) for x in r) if r else None
+
+
+def position_major_index(L, first, frame_tokens, frames):
+    """pi: int64 [L].  Section 4.1.1 orders video tokens frame by frame: frame f,
+    position p sits at first + f*N + p.  pi moves it to first + p*F + f
+    (position-major); tokens outside the video block keep their index."""
+    N, F = int(frame_tokens), int(frames)
+    if first < 0 or N < 1 or F < 1 or first + N * F > L:
+        raise ValueError("the video block does not fit the sequence")
+    pi = np.arange(L, dtype=np.int64)
+    v = np.arange(N * F, dtype=np.int64)
+    pi[first:first + N * F] = first + (v % N) * F + v // N
+    return pi
+
+
 def text_tokens_of(params):
     """Length T of the text prefix whose borders the head keeps whole (0: none)."""
     return int(params.get("text_tokens", 0)) if params else 0
@@ -96,6 +123,11 @@ def _pattern_mask(mode, params, L, rows):
         w = int(params["half_width"])
         if w < 0:
             raise ValueError("negative half width")
+        if mode == MODE_MULTIDIAG and rearranged_of(params):
+            if text_tokens_of(params):
+                raise ValueError("a rearranged head takes no text prefix")
+            pi = position_major_index(L, *rearranged_of(params))
+            return np.abs(pi[None, :] - pi[rows][:, None]) <= w
         delta = np.arange(L, dtype=np.int64)[None, :] - rows[:, None]
         mask = np.zeros((rows.size, L), dtype=bool)
         for o in _offsets_of(mode, params):
@@ -176,6 +208,8 @@ def delta_runs(mode, params, L):
     int64 array [n, 2] of inclusive [lo, hi] runs of consecutive kept deltas
     inside [-(L-1), L-1], ascending.  Found by marking every delta.
     """
+    if mode == MODE_MULTIDIAG and rearranged_of(params):   # one band, in the rearranged order
+        mode, params = MODE_DIAG, {"half_width": int(params["half_width"])}
     w = int(params["half_width"])
     deltas = np.arange(-(L - 1), L, dtype=np.int64)
     kept = np.zeros(deltas.size, dtype=bool)
@@ -205,6 +239,10 @@ def query_block_entries(mode, params, L, block_q, block_k, qb, runs=None):
     run_count) as int32 arrays; see block_lists for their meaning."""
     if mode not in BAND_MODES:
         raise ValueError("block lists exist for the band modes only")
+    if mode == MODE_MULTIDIAG and rearranged_of(params):
+        # rows and keys of the list are positions in the rearranged order, where the head is a plain band
+        position_major_index(L, *rearranged_of(params))   # validates the geometry
+        mode, params = MODE_DIAG, {"half_width": int(params["half_width"])}
     T = text_tokens_of(params)
     if T and (T % block_q or T % block_k):
         raise ValueError("the text prefix must be a multiple of both block sizes")
@@ -248,6 +286,8 @@ def block_lists(mode, params, L, block_q, block_k):
     With a text prefix T (a multiple of both block sizes) the query blocks of the
     text rows have no entries (those rows are dense) and every other query block
     lists the T / block_k text tiles, kept whole.
+    For a rearranged multi-diagonal head the lists are those of the plain band in
+    the rearranged order, and row_map gives the original row of every position.
     """
     runs = delta_runs(mode, params, L)
     n_qb = -(-L // block_q)
@@ -259,9 +299,22 @@ def block_lists(mode, params, L, block_q, block_k):
             dst.append(src)
         row_ptr.append(row_ptr[-1] + ent[0].size)
     cat = lambda a: np.concatenate(a).astype(np.int32)
-    return {"row_ptr": np.asarray(row_ptr, dtype=np.int32), "kv_block_idx": cat(parts[0]),
-            "flags": cat(parts[1]), "run_first": cat(parts[2]), "run_count": cat(parts[3]),
-            "runs": runs.astype(np.int32)}
+    out = {"row_ptr": np.asarray(row_ptr, dtype=np.int32), "kv_block_idx": cat(parts[0]),
+           "flags": cat(parts[1]), "run_first": cat(parts[2]), "run_count": cat(parts[3]),
+           "runs": runs.astype(np.int32)}
+    if mode == MODE_MULTIDIAG and rearranged_of(params):
+        out["row_map"] = row_map(L, *rearranged_of(params), block_k)
+    return out
+
+
+def row_map(L, first, frame_tokens, frames, block_k):
+    """Original row of every position of the rearranged order (the inverse of
+    position_major_index), padded with -1 to a multiple of block_k (int32)."""
+    pi = position_major_index(L, first, frame_tokens, frames)
+    padded = -(-L // block_k) * block_k
+    out = np.full(padded, -1, dtype=np.int32)
+    out[pi] = np.arange(L, dtype=np.int32)
+    return out
 
 
 def column_list(params, L, block_k):
@@ -289,6 +342,8 @@ def mask_popcount(mode, params, L, chunk=256):
 
 def _params_key(mode, params):
     if mode in BAND_MODES:
+        if mode == MODE_MULTIDIAG and rearranged_of(params):
+            return (int(params["half_width"]), rearranged_of(params))
         return (int(params["half_width"]), tuple(sorted(set(_offsets_of(mode, params)))), text_tokens_of(params))
     if mode == MODE_VSTRIPE:
         return (tuple(sorted(int(c) for c in params["cols"])), text_tokens_of(params))
@@ -300,13 +355,17 @@ def head_groups(strategy_table, pattern_params):
     group (one launch).  Inside a group, heads whose parameters describe the
     same kept region share one list.
 
-    Returns a list of groups in ascending mode order; a group is a dict with
-    mode, heads (ascending head ids), list_id (per head, ids numbered in order
-    of first appearance) and n_lists.
+    Returns a list of groups in ascending mode order (rearranged multi-diagonal
+    heads after the plain ones); a group is a dict with mode, heads (ascending
+    head ids), list_id (per head, ids numbered in order of first appearance),
+    n_lists and rearranged.
     """
     groups = []
-    for mode in (MODE_DENSE, MODE_SKIP, MODE_DIAG, MODE_MULTIDIAG, MODE_VSTRIPE):
-        heads = [h for h in range(len(strategy_table)) if int(strategy_table[h]) == mode]
+    # rearranged multi-diagonal heads run another loop shape and form a group of their own, after the plain ones
+    for mode, rearranged in ((MODE_DENSE, False), (MODE_SKIP, False), (MODE_DIAG, False), (MODE_MULTIDIAG, False),
+                             (MODE_MULTIDIAG, True), (MODE_VSTRIPE, False)):
+        heads = [h for h in range(len(strategy_table)) if int(strategy_table[h]) == mode
+                 and (mode != MODE_MULTIDIAG or bool(rearranged_of(pattern_params[h])) == rearranged)]
         if not heads:
             continue
         seen = {}
@@ -316,7 +375,7 @@ def head_groups(strategy_table, pattern_params):
             if key not in seen:
                 seen[key] = len(seen)
             list_id.append(seen[key])
-        groups.append({"mode": mode, "heads": heads, "list_id": list_id, "n_lists": len(seen)})
+        groups.append({"mode": mode, "heads": heads, "list_id": list_id, "n_lists": len(seen), "rearranged": rearranged})
     for m in strategy_table:
         if int(m) not in (0, 1, 2, 3, 4):
             raise ValueError("mode id outside 0..4")

@@ -72,3 +72,37 @@ def test_equals_diagonal_attention_on_rearranged_tensors(first, N, F, W):
     rows = [0, first, L - 1, first + N]
     np.testing.assert_allclose(R.attention_head_rearranged(q, k, v, first, N, F, W, rows=rows), direct[rows],
                                rtol=1e-12, atol=1e-14)
+
+
+def test_rearranged_multi_diagonal_head_in_the_attention_oracle():
+    L, first, N, F, W = 70, 6, 8, 7, 9
+    p = {"half_width": W, "rearranged": (first, N, F), "offsets": ()}
+    rows = np.arange(L)
+    np.testing.assert_array_equal(SA.allowed_mask(SA.MODE_MULTIDIAG, p, L, rows), R.window_mask(L, first, N, F, W, rows))
+    rng = np.random.default_rng(5)
+    q, k, v = (rng.standard_normal((L, 8)) for _ in range(3))
+    np.testing.assert_allclose(SA.attention_head(q, k, v, SA.MODE_MULTIDIAG, p),
+                               R.attention_head_rearranged(q, k, v, first, N, F, W), rtol=1e-13, atol=1e-15)
+    # its lists are those of the plain band in the rearranged order; row_map inverts the index map
+    lists = SA.block_lists(SA.MODE_MULTIDIAG, p, L, 16, 8)
+    band = SA.block_lists(SA.MODE_DIAG, {"half_width": W}, L, 16, 8)
+    for key in ("row_ptr", "kv_block_idx", "flags", "run_first", "run_count", "runs"):
+        np.testing.assert_array_equal(lists[key], band[key])
+    pi = SA.position_major_index(L, first, N, F)
+    rm = lists["row_map"]
+    assert rm.size == 72 and rm.dtype == np.int32 and (rm[L:] == -1).all()
+    assert all(rm[pi[i]] == i for i in range(L))
+    with pytest.raises(ValueError):
+        SA.allowed_mask(SA.MODE_MULTIDIAG, dict(p, text_tokens=8), L, rows)
+    with pytest.raises(ValueError):
+        SA.block_lists(SA.MODE_MULTIDIAG, dict(p, rearranged=(first, N, 9)), L, 16, 8)
+
+
+def test_rearranged_heads_form_their_own_group():
+    table = [3, 3, 2, 3, 3]
+    plain = {"half_width": 2, "offsets": (0, 10)}
+    re1 = {"half_width": 5, "rearranged": (0, 10, 4)}
+    re2 = {"half_width": 6, "rearranged": (0, 10, 4)}
+    g = SA.head_groups(table, [plain, re1, {"half_width": 3}, re2, re1])
+    assert [(x["mode"], x["heads"], x["list_id"], x["rearranged"]) for x in g] == \
+        [(2, [2], [0], False), (3, [0], [0], False), (3, [1, 3, 4], [0, 1, 0], True)]
