@@ -81,6 +81,18 @@ typedef struct {
   const int32_t* offsets;    /* mode 3: band centres o (key index minus query index), any order, host */
   int32_t n_cols;            /* mode 4: number of key columns */
   const int32_t* cols;       /* mode 4: key columns in [0, L), any order, no duplicates, host */
+  /* mode 3 in rearranged form (Section 4.1.2: "by rearranging tokens" the evenly
+   * spaced diagonals become one diagonal band).  rearr_frames = F > 0 selects it:
+   * the video block is F frames of rearr_frame_tokens = N tokens starting at token
+   * rearr_first, frame f and position p at rearr_first + f*N + p; with pi the move
+   * to position-major order (rearr_first + p*F + f, other tokens unmoved) the head
+   * keeps (i, j) iff |pi(i) - pi(j)| <= half_width.  half_width = w*F + F - 1 keeps
+   * every pair of positions at most w apart, in any two frames.  offsets are not
+   * read.  The kernels walk the band in the rearranged order and reach the rows of
+   * q, k, v and out through a row map; nothing is copied.  Not combined with a
+   * text prefix (SVD_ERR_UNSUPPORTED); SVD_ERR_PARAMS when the video block does
+   * not fit L.  F = 0: the head is a plain multi-diagonal head. */
+  int32_t rearr_first, rearr_frame_tokens, rearr_frames;
 } svd_head_params;
 
 /* Plan options (a NULL pointer or zeros select the defaults).
@@ -144,6 +156,10 @@ svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups);
 /* heads: ascending head ids of the group; list_id[t]: which list of the group
  * head heads[t] uses (heads with the same kept region share a list; ids are
  * numbered by first appearance); n_lists is 0 for dense and skip groups. */
+/* (Rearranged multi-diagonal heads form a group of their own, after the plain
+ * multi-diagonal group; both report mode 3, svd_plan_group_rearranged tells them
+ * apart.) */
+svd_status svd_plan_group_rearranged(const svd_plan* plan, int32_t group, int32_t* rearranged);
 svd_status svd_plan_group_info(const svd_plan* plan, int32_t group, int32_t* mode, int32_t* n_heads,
                                const int32_t** heads, const int32_t** list_id, int32_t* n_lists);
 /* A list of a band group (modes 2, 3).  row_ptr[n_q_blocks+1] is the CSR
@@ -158,6 +174,12 @@ svd_status svd_plan_band_list(const svd_plan* plan, int32_t group, int32_t list,
                               const int32_t** kv_block_idx, const int32_t** flags,
                               const int32_t** run_first, const int32_t** run_count,
                               int32_t* n_runs, const int32_t** runs);
+/* The row map of a list of a rearranged multi-diagonal group: row_map[r] = original
+ * row of position r of the rearranged order, padded with -1 to padded_len, a
+ * multiple of block_k; the lists of such a group (svd_plan_band_list) are those of
+ * the plain band in the rearranged order.  SVD_ERR_SHAPE for other groups. */
+svd_status svd_plan_row_map(const svd_plan* plan, int32_t group, int32_t list, int32_t* padded_len,
+                            const int32_t** row_map);
 /* A list of a vertical-stripe group (mode 4): the sorted unique columns padded
  * with -1 to padded_len, a multiple of block_k. */
 svd_status svd_plan_column_list(const svd_plan* plan, int32_t group, int32_t list,

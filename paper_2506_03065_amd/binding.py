@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SVD_OK", 1: "SVD_ERR_NULL", 2: "SVD_ERR_SHAPE", 3: "SVD_ERR_
 SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
-           "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_band_list", "svd_plan_column_list",
+           "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
@@ -44,7 +44,8 @@ class TensorDesc(C.Structure):
 
 class HeadParams(C.Structure):
     _fields_ = [("half_width", C.c_int32), ("n_offsets", C.c_int32), ("offsets", C.POINTER(C.c_int32)),
-                ("n_cols", C.c_int32), ("cols", C.POINTER(C.c_int32))]
+                ("n_cols", C.c_int32), ("cols", C.POINTER(C.c_int32)),
+                ("rearr_first", C.c_int32), ("rearr_frame_tokens", C.c_int32), ("rearr_frames", C.c_int32)]
 
 
 class PlanOptions(C.Structure):
@@ -74,6 +75,8 @@ def lib():
             "svd_plan_dense_split": [vp, i32p],
             "svd_plan_num_groups": [vp, i32p],
             "svd_plan_group_info": [vp, C.c_int32, i32p, i32p, i32pp, i32pp, i32p],
+            "svd_plan_group_rearranged": [vp, C.c_int32, i32p],
+            "svd_plan_row_map": [vp, C.c_int32, C.c_int32, i32p, i32pp],
             "svd_plan_band_list": [vp, C.c_int32, C.c_int32, i32p, i32pp, i32pp, i32pp, i32pp, i32pp, i32p, i32pp],
             "svd_plan_column_list": [vp, C.c_int32, C.c_int32, i32p, i32p, i32pp],
             "svd_plan_work": [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
@@ -157,6 +160,8 @@ class _Marshalled:
             self.params[h].offsets = _ptr(offs) if offs.size else None
             self.params[h].n_cols = cols.size
             self.params[h].cols = _ptr(cols) if cols.size else None
+            first, n, f = p.get("rearranged") or (0, 0, 0)
+            self.params[h].rearr_first, self.params[h].rearr_frame_tokens, self.params[h].rearr_frames = int(first), int(n), int(f)
 
 
 def _text_tokens(strategy_table, pattern_params, text_tokens):
@@ -229,9 +234,18 @@ class Plan:
             heads, lid = C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)()
             _check(L_.svd_plan_group_info(self.handle, g, C.byref(mode), C.byref(nh), C.byref(heads),
                                           C.byref(lid), C.byref(nl)), "svd_plan_group_info")
+            rearranged = C.c_int32()
+            _check(L_.svd_plan_group_rearranged(self.handle, g, C.byref(rearranged)), "svd_plan_group_rearranged")
             out.append({"mode": mode.value, "heads": _copy(heads, nh.value).tolist(),
-                        "list_id": _copy(lid, nh.value).tolist(), "n_lists": nl.value})
+                        "list_id": _copy(lid, nh.value).tolist(), "n_lists": nl.value,
+                        "rearranged": bool(rearranged.value)})
         return out
+
+    def row_map(self, group, lst):
+        padded = C.c_int32()
+        rm = C.POINTER(C.c_int32)()
+        _check(lib().svd_plan_row_map(self.handle, group, lst, C.byref(padded), C.byref(rm)), "svd_plan_row_map")
+        return _copy(rm, padded.value)
 
     def band_list(self, group, lst):
         nqb, nruns = C.c_int32(), C.c_int32()

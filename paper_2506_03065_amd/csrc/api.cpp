@@ -201,6 +201,13 @@ std::vector<int32_t> flatten(const svd_tensor_desc& d, const int32_t* table, con
     const int mode = table[h];
     f.push_back(mode);
     if (mode == SVD_DIAG || mode == SVD_MULTIDIAG) f.push_back(pp[h].half_width);
+    if (mode == SVD_MULTIDIAG && pp[h].rearr_frames > 0) {
+      f.push_back(-1);   // marks the rearranged form
+      f.push_back(pp[h].rearr_first);
+      f.push_back(pp[h].rearr_frame_tokens);
+      f.push_back(pp[h].rearr_frames);
+      continue;
+    }
     if (mode == SVD_MULTIDIAG && pp[h].offsets && pp[h].n_offsets > 0) {
       f.push_back(pp[h].n_offsets);
       f.insert(f.end(), pp[h].offsets, pp[h].offsets + pp[h].n_offsets);
@@ -352,6 +359,24 @@ svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups) {
   return SVD_OK;
 }
 
+svd_status svd_plan_group_rearranged(const svd_plan* plan, int32_t group, int32_t* rearranged) {
+  if (!plan || !rearranged) return SVD_ERR_NULL;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  *rearranged = plan->p.groups[group].rearranged ? 1 : 0;
+  return SVD_OK;
+}
+
+svd_status svd_plan_row_map(const svd_plan* plan, int32_t group, int32_t list, int32_t* padded_len,
+                            const int32_t** row_map) {
+  if (!plan) return SVD_ERR_NULL;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  const svd::Group& g = plan->p.groups[group];
+  if (!g.rearranged || list < 0 || list >= static_cast<int32_t>(g.bands.size())) return SVD_ERR_SHAPE;
+  if (padded_len) *padded_len = static_cast<int32_t>(g.bands[list].row_map.size());
+  if (row_map) *row_map = g.bands[list].row_map.data();
+  return SVD_OK;
+}
+
 svd_status svd_plan_group_info(const svd_plan* plan, int32_t group, int32_t* mode, int32_t* n_heads,
                                const int32_t** heads, const int32_t** list_id, int32_t* n_lists) {
   if (!plan) return SVD_ERR_NULL;
@@ -494,7 +519,8 @@ static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const vo
     err = svd::launch_zero_heads(a, stream);
   } else {
     const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
-                      : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+                      : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER
+                      : g.rearranged ? svd::MODE_PBAND : svd::MODE_BAND;
     if (g.mode == SVD_DENSE && sp.dense_split > 1) {
       a.split = sp.dense_split;
       a.n_items *= a.split;
@@ -530,11 +556,12 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
   hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
   // heaviest first: dense, then the band groups, the gathers, and the zero fill
   static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
-  const svd::Group* seq[5];
+  constexpr int kMaxGroups = 6;   // the five modes plus the rearranged multi-diagonal group
+  const svd::Group* seq[kMaxGroups];
   int n = 0;
   for (int mode : order)
     for (const svd::Group& g : p.groups)
-      if (g.mode == mode && n < 5) seq[n++] = &g;
+      if (g.mode == mode && n < kMaxGroups) seq[n++] = &g;
   if (!plan->concurrent || n < 2) {
     for (int i = 0; i < n; ++i)
       if (svd_status st = launch_group(*plan, *seq[i], q, k, v, out, main_stream)) return st;
@@ -874,6 +901,7 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
   a.ws = ws;
   a.list_table = static_cast<int>(g.ws_list_table);
   if (g.mode == SVD_SKIP) return svd::launch_zero_heads(a, stream) == hipSuccess ? SVD_OK : SVD_ERR_HIP;
+  if (g.rearranged) return SVD_ERR_UNSUPPORTED;   // the rearranged form is built for the bf16 path only
   f.Lp = svd::fp8_padded_len(d.L);
   f.k8 = static_cast<uint8_t*>(ws8);
   f.v8t = f.k8 + svd::fp8_scratch_bytes(d.B, d.H, d.L, d.D) / 2;

@@ -9,7 +9,10 @@ namespace svd {
 
 // Kernel-level modes: the five modes of Section 4.2 map to three loop shapes
 // (diagonal and multi-diagonal share the banded one) plus the zero fill.
-enum { MODE_DENSE = 0, MODE_BAND = 1, MODE_GATHER = 2 };
+// MODE_PBAND is the banded loop in a rearranged token order (Section 4.1.2): the
+// band lists index positions of that order and every row of q, k, v and out is
+// reached through the list's row map.
+enum { MODE_DENSE = 0, MODE_BAND = 1, MODE_GATHER = 2, MODE_PBAND = 3 };
 
 // Tile shapes the kernels are instantiated for.  Query tile = NW waves x QB
 // blocks of 32 rows; key tile = BC keys.

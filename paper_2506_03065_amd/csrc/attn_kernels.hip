@@ -87,6 +87,8 @@ using Int = std::integral_constant<int, N>;
 
 template <int D, int NW, int QB, int BC, int OCC, int MODE>
 __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch p) {
+  constexpr bool kBand = MODE == MODE_BAND || MODE == MODE_PBAND;        // walks a CSR list of key tiles
+  constexpr bool kIndirect = MODE == MODE_GATHER || MODE == MODE_PBAND;   // key rows come through an index list
   constexpr int NT = NW * 64;
   constexpr int QW = QB * 32;       // query rows per wave
   constexpr int BR = NW * QW;       // query rows per work-group
@@ -137,7 +139,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   typedef const i32x2 __attribute__((address_space(4)))* const_int2_ptr;
   const_int2_ptr entries = nullptr;   // BAND
   const_int2_ptr runs = nullptr;      // BAND
-  const int* __restrict__ cols = nullptr;      // GATHER
+  const int* __restrict__ cols = nullptr;      // GATHER: the head's columns; PBAND: the row map
   int n_cols = 0;
   if (MODE == MODE_DENSE) {
     const int n_all = (L + BC - 1) / BC;
@@ -145,13 +147,14 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     n_tiles = (chunk + 1) * n_all / p.split - t_base;
   } else {
     const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
-    if (MODE == MODE_BAND) {
+    if (kBand) {
       const int* row_ptr = p.ws + rec[0];
       const int e0 = row_ptr[qblk], e1 = row_ptr[qblk + 1];
       entries = (const_int2_ptr)(uintptr_t)(p.ws + rec[1]) + e0;
       runs = (const_int2_ptr)(uintptr_t)(p.ws + rec[2]);
       n_tiles = e1 - e0;
       if (n_tiles == 0) return;   // rows that another launch computes (text rows of a layer with a text prefix)
+      if (MODE == MODE_PBAND) cols = p.ws + rec[3];
     } else {
       cols = p.ws + rec[0];
       n_tiles = rec[1] / BC;
@@ -170,6 +173,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   for (int qb = 0; qb < QB; ++qb) {
     int row = q0 + qb * 32 + l32;
     row = row < L ? row : L - 1;
+    if (MODE == MODE_PBAND) row = cols[row];   // position of the rearranged order -> row of the tensor
     const __bf16* src = Q + (int64_t)row * p.stride_l + half * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -239,8 +243,8 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     const int r = byte / ROW_BYTES, slot = (byte % ROW_BYTES) >> 4;
     const unsigned ck = (unsigned)(slot ^ swz_k<D>(r)) * 16u, cv = (unsigned)(slot ^ swz_v<D>(r)) * 16u;
     g_r[u] = (unsigned)r * 4u;
-    g_k[u] = MODE == MODE_GATHER ? ck : (unsigned)r * stride_bytes + ck;
-    g_v[u] = MODE == MODE_GATHER ? cv : (unsigned)r * stride_bytes + cv;
+    g_k[u] = kIndirect ? ck : (unsigned)r * stride_bytes + ck;
+    g_v[u] = kIndirect ? cv : (unsigned)r * stride_bytes + cv;
   }
   // buffer resources of this head's K and V (raw buffers: base, byte range, no swizzle)
   const unsigned head_bytes = (unsigned)(L - 1) * stride_bytes + (unsigned)ROW_BYTES;
@@ -253,9 +257,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     const char* src_b = reinterpret_cast<const char*>(IS_K ? K : V);
     const __amdgpu_buffer_rsrc_t rsrc = IS_K ? rsrc_k : rsrc_v;
     unsigned char* dst = (IS_K ? sK : sV) + buf * TILE_BYTES + wave * (LPT * 1024);
-    if (MODE == MODE_GATHER) {
-      // key rows come from the head's column list (-1 = padding: any valid row, masked later)
-      const char* list = reinterpret_cast<const char*>(cols + t * BC);
+    if (kIndirect) {
+      // key rows come from the head's column list, or from the row map at the tile the band
+      // list names (-1 = padding: any valid row, masked later)
+      const char* list = reinterpret_cast<const char*>(cols + (kBand ? entries[t].x : t) * BC);
 #pragma unroll
       for (int u = 0; u < LPT; ++u) {
         int c = *reinterpret_cast<const int*>(list + g_r[u]);
@@ -264,7 +269,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dst + u * 1024), 16, (int)off, 0, 0, 0);
       }
     } else {
-      const int row0 = (MODE == MODE_BAND ? entries[t].x : t + t_base) * BC;
+      const int row0 = (kBand ? entries[t].x : t + t_base) * BC;
       const char* base_b = src_b + (unsigned)row0 * stride_bytes;
       if (INNER || row0 + BC <= L) {
 #pragma unroll
@@ -328,7 +333,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   // (or the end of the sequence) actually crosses are masked element by element.
   auto apply_mask = [&](f32x16 (&s)[KB2][QB], const int t) -> bool {
     bool changed = false;
-    if (MODE == MODE_BAND) {
+    if (kBand) {
       const i32x2 ent = entries[t];
       const int kv0 = ent.x * BC;
       const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
@@ -521,7 +526,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     // partly kept tile?  band lists flag it per entry; the dense and gather loops
     // can only meet one at the very end (keys past L, padding of the column list)
     bool masked;
-    if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+    if (kBand) masked = !(entries[t].y & 1);
     else if (INNER) masked = false;
     else if (MODE == MODE_DENSE) masked = (t + t_base + 1) * BC > L;
     else masked = (t + 1) * BC > n_cols;
@@ -614,7 +619,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     const float inv = 1.0f / l4[qb][0];   // every lane holds the complete sum of its query
     const int row = q0 + qb * 32 + l32;
     if (row < L) {
-      __bf16* dst = O + (int64_t)row * p.stride_l;
+      __bf16* dst = O + (int64_t)(MODE == MODE_PBAND ? cols[row] : row) * p.stride_l;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -714,6 +719,9 @@ hipError_t launch_mode(const AttnLaunch& p, int mode, hipStream_t stream) {
       break;
     case MODE_GATHER:
       hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_GATHER>), grid, block, 0, stream, p);
+      break;
+    case MODE_PBAND:
+      hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_PBAND>), grid, block, 0, stream, p);
       break;
     default:
       return hipErrorInvalidValue;

@@ -185,15 +185,52 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
   for (int32_t h = 0; h < desc.H; ++h)
     if (strategy_table[h] < SVD_DENSE || strategy_table[h] > SVD_VSTRIPE) return SVD_ERR_MODE;
 
-  for (int32_t mode = SVD_DENSE; mode <= SVD_VSTRIPE; ++mode) {
+  // one pass per group: the five modes, and after the plain multi-diagonal heads
+  // those in rearranged form (Section 4.1.2), which run another loop shape
+  static const int32_t pass_mode[6] = {SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_MULTIDIAG, SVD_VSTRIPE};
+  static const bool pass_rearranged[6] = {false, false, false, false, true, false};
+  for (int pass = 0; pass < 6; ++pass) {
+    const int32_t mode = pass_mode[pass];
     Group g;
     g.mode = mode;
+    g.rearranged = pass_rearranged[pass];
     std::map<BandKey, int32_t> band_ids;
     std::map<std::vector<int32_t>, int32_t> col_ids;
     for (int32_t h = 0; h < desc.H; ++h) {
       if (strategy_table[h] != mode) continue;
       const svd_head_params& p = pattern_params[h];
+      if (mode == SVD_MULTIDIAG && (p.rearr_frames > 0) != g.rearranged) continue;
       int32_t id = 0;
+      if (g.rearranged) {
+        // one band of half width w in the position-major order of the video block
+        if (p.half_width < 0 || p.rearr_first < 0 || p.rearr_frame_tokens < 1) return SVD_ERR_PARAMS;
+        const int64_t first = p.rearr_first, N = p.rearr_frame_tokens, F = p.rearr_frames;
+        if (first + N * F > L) return SVD_ERR_PARAMS;
+        if (T > 0) return SVD_ERR_UNSUPPORTED;
+        BandKey key(p.half_width, {p.rearr_first, p.rearr_frame_tokens, p.rearr_frames});
+        auto it = band_ids.find(key);
+        if (it == band_ids.end()) {
+          BandList bl;
+          bl.half_width = p.half_width;
+          bl.offsets.assign(1, 0);
+          bl.runs = merged_runs(bl.offsets, p.half_width, L);
+          build_band_list(&bl, L, block_q, block_k, 0);
+          bl.row_map.assign(static_cast<size_t>(ceil_div(L, block_k) * block_k), -1);
+          for (int64_t i = 0; i < L; ++i) {
+            const int64_t v = i - first;
+            const int64_t pos = (v < 0 || v >= N * F) ? i : first + (v % N) * F + v / N;
+            bl.row_map[static_cast<size_t>(pos)] = static_cast<int32_t>(i);
+          }
+          id = static_cast<int32_t>(g.bands.size());
+          band_ids.emplace(std::move(key), id);
+          g.bands.push_back(std::move(bl));
+        } else {
+          id = it->second;
+        }
+        g.heads.push_back(h);
+        g.list_id.push_back(id);
+        continue;
+      }
       if (mode == SVD_DIAG || mode == SVD_MULTIDIAG) {
         if (p.half_width < 0) return SVD_ERR_PARAMS;
         std::vector<int32_t> offs;
@@ -276,6 +313,10 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
       rec[1] = static_cast<int32_t>(en);
       rec[2] = static_cast<int32_t>(ru);
       rec[3] = static_cast<int32_t>(bl.runs.size() / 2);
+      if (!bl.row_map.empty()) {
+        const size_t rm = append(&img, bl.row_map);
+        img[g.ws_list_table + l * kListRecordWords + 3] = static_cast<int32_t>(rm);   // append may have moved the image
+      }
     }
     for (size_t l = 0; l < g.columns.size(); ++l) {
       const ColumnList& cl = g.columns[l];

@@ -26,6 +26,10 @@ struct BandList {
   std::vector<int32_t> run_count;     // per entry
   double kept_pairs = 0.0;            // element-level count for one head (text borders included)
   double tile_area = 0.0;             // sum over entries of in-range rows * in-range keys
+  // rearranged form (Section 4.1.2): the list above is that of one band in the
+  // position-major order; row_map[r] = original row of position r, -1 padded to
+  // a multiple of block_k.  Empty for plain lists.
+  std::vector<int32_t> row_map;
 };
 
 // One distinct column set (mode 4).
@@ -36,6 +40,7 @@ struct ColumnList {
 
 struct Group {
   int32_t mode = 0;
+  bool rearranged = false;            // mode 3 heads in rearranged form (a group of their own)
   std::vector<int32_t> heads;         // ascending
   std::vector<int32_t> list_id;       // per head of the group
   std::vector<BandList> bands;        // modes 2, 3
@@ -46,6 +51,7 @@ struct Group {
 
 // Per-list record in the device workspace, 4 int32 words.
 //   band list:   {row_ptr offset, entries offset, runs offset, n_runs}
+//                rearranged: {row_ptr offset, entries offset, runs offset, row_map offset}
 //   column list: {cols offset, padded_len, n_cols, 0}
 // Offsets are in int32 words from the workspace base.  A band entry is two
 // words {kv_block_idx, meta}, meta = flag | run_first << 1 | run_count << 16.

@@ -92,3 +92,46 @@ def test_wan_shape_sampled_rows():
     for h in range(2):
         want = R.attention_head_rearranged(f64(q[0, h]), f64(k[0, h]), f64(v[0, h]), 0, N, F, Wd, rows=rows)
         assert_close(f64(out[0, h][torch.as_tensor(rows)]), want, f"rearranged window, Wan shape, head {h}")
+
+
+# ---- the rearranged form inside the strategy table: no copies, rows reached through the row map ----
+
+@pytest.mark.parametrize("L,D,B,first,N,F,w", [(1000, 64, 1, 0, 100, 10, 3), (1300, 128, 2, 256, 87, 12, 2),
+                                                (777, 64, 1, 17, 40, 19, 0), (520, 128, 1, 0, 520, 1, 30)])
+def test_rearranged_heads_in_a_layer_all_rows(L, D, B, first, N, F, w):
+    from parity_util import check_layer, run_planned
+    wl = W.small(L=L, D=D, H=10, seed=21, B=B)
+    params = [dict(p) for p in wl.pattern_params]
+    multi = [h for h in range(wl.H) if wl.strategy_table[h] == W.MULTIDIAG]
+    params[multi[0]] = {"half_width": w * F + F - 1, "offsets": (), "cols": (), "rearranged": (first, N, F)}
+    wl.pattern_params = params
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    out = run_planned(wl, q, k, v)
+    check_layer(wl, q, k, v, out)
+    # the same head through the explicit path: identical kept set, same kernel family
+    h = multi[0]
+    ref = rearranged_window_attention(q[:, h:h + 1].contiguous(), k[:, h:h + 1].contiguous(), v[:, h:h + 1].contiguous(),
+                                      first, N, F, w * F + F - 1)
+    assert_close(f64(out[0, h]), f64(ref[0, 0]), "row-map path against the copy path")
+
+
+def test_rearranged_heads_wan_shape_sampled_rows_and_fp8_refusal():
+    from parity_util import check_layer, run_planned
+    L, D, N, F, w = 75600, 128, 3600, 21, 40
+    table = np.asarray([W.MULTIDIAG, W.MULTIDIAG, W.DIAG], dtype=np.int32)
+    params = [{"half_width": w * F + F - 1, "rearranged": (0, N, F)}, {"half_width": 900, "offsets": (-N, 0, N)},
+              {"half_width": 3600}]
+    wl = W.Workload("wan-rearranged", -1, 1, 3, L, D, N, F, 0, table, params, 77)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    out = run_planned(wl, q, k, v)
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(L - 4, L), [N - 1, N, 20 * N, 20 * N + N - 1],
+                                     np.random.default_rng(3).integers(0, L, 20)]))
+    check_layer(wl, q, k, v, out, rows=rows)
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, table, params), dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, table, params, workspace=ws)
+    ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    with pytest.raises(svd.SvdError) as e:
+        svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
+    assert e.value.status == 9
+    plan.close()

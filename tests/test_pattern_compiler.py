@@ -37,8 +37,8 @@ def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
     plan = _compile(wl, bq, bk)
     got_groups = plan.groups()
     want_groups = O.head_groups(wl.strategy_table, wl.pattern_params)
-    assert [(g["mode"], g["heads"], g["list_id"]) for g in got_groups] == \
-           [(g["mode"], g["heads"], g["list_id"]) for g in want_groups]
+    assert [(g["mode"], g["heads"], g["list_id"], g["rearranged"]) for g in got_groups] == \
+           [(g["mode"], g["heads"], g["list_id"], g["rearranged"]) for g in want_groups]
     for gi, g in enumerate(got_groups):
         if g["mode"] in (svd.SVD_DENSE, svd.SVD_SKIP):
             assert g["n_lists"] == 0
@@ -54,6 +54,10 @@ def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
                 assert got["cols"].dtype == np.int32 and np.array_equal(got["cols"], want)
                 continue
             got = plan.band_list(gi, lst)
+            if g["rearranged"]:
+                got["row_map"] = plan.row_map(gi, lst)
+                want = O.block_lists(g["mode"], p, wl.L, bq, bk)
+                assert np.array_equal(got["row_map"], want["row_map"]) and got["row_map"].dtype == np.int32
             if q_blocks is None:
                 want = O.block_lists(g["mode"], p, wl.L, bq, bk)
                 for key in ("row_ptr", "kv_block_idx", "flags", "run_first", "run_count", "runs"):
@@ -263,3 +267,37 @@ def test_text_prefix_counts_and_validation():
     with pytest.raises(svd.SvdError) as e:
         _compile(_one_head(O.MODE_MULTIDIAG, {"half_width": 1, "offsets": (50,)}, 600), 256, 128)
     assert e.value.status == 7
+
+
+# ---- multi-diagonal heads in rearranged form (Section 4.1.2) ----
+
+@pytest.mark.parametrize("L,bq,bk,first,N,F,w", [(600, 64, 32, 0, 60, 10, 25), (1000, 256, 64, 40, 96, 10, 50),
+                                                  (333, 16, 8, 13, 32, 10, 0), (1000, 256, 128, 0, 1000, 1, 7)])
+def test_rearranged_heads_lists_and_row_map_bit_exact(L, bq, bk, first, N, F, w):
+    wl = W.small(L=L, D=64, H=10, seed=3)
+    params = [dict(p) for p in wl.pattern_params]
+    multi = [h for h in range(wl.H) if wl.strategy_table[h] == W.MULTIDIAG]
+    params[multi[0]] = {"half_width": w, "offsets": (), "cols": (), "rearranged": (first, N, F)}
+    wl.pattern_params = params
+    _assert_plan_matches_oracle(wl, bq, bk)
+    plan = _compile(wl, bq, bk)
+    groups = plan.groups()
+    assert [g["rearranged"] for g in groups if g["mode"] == W.MULTIDIAG] == [False, True]
+    sp = plan.head_sparsity()
+    assert abs(sp[multi[0]] - (1.0 - O.mask_popcount(W.MULTIDIAG, params[multi[0]], L) / L ** 2)) < 1e-12
+    plan.close()
+
+
+def test_rearranged_heads_validation():
+    desc = svd.tensor_desc(1, 1, 512, 64)
+    table = [W.MULTIDIAG]
+    for geo, status in (((0, 100, 6), 6), ((-1, 10, 4), 6), ((0, 0, 4), 6), ((500, 4, 4), 6)):
+        with pytest.raises(svd.SvdError) as e:
+            svd.svd_plan_create(desc, table, [{"half_width": 3, "rearranged": geo}], 256, 128)
+        assert e.value.status == status, geo
+    with pytest.raises(svd.SvdError) as e:      # not combined with a text prefix
+        svd.svd_plan_create(desc, table, [{"half_width": 3, "rearranged": (256, 64, 4), "text_tokens": 256}], 256, 128)
+    assert e.value.status == 9
+    with pytest.raises(svd.SvdError) as e:
+        svd.svd_plan_create(desc, table, [{"half_width": -1, "rearranged": (0, 64, 4)}], 256, 128)
+    assert e.value.status == 6
