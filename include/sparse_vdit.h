@@ -89,7 +89,8 @@ typedef struct {
    * keeps (i, j) iff |pi(i) - pi(j)| <= half_width.  half_width = w*F + F - 1 keeps
    * every pair of positions at most w apart, in any two frames.  offsets are not
    * read.  The kernels walk the band in the rearranged order and reach the rows of
-   * q, k, v and out through a row map; nothing is copied.  Not combined with a
+   * q, k, v and out through a row map; nothing is copied (the FP8 variant writes
+   * its quantised keys and values in the rearranged order).  Not combined with a
    * text prefix (SVD_ERR_UNSUPPORTED); SVD_ERR_PARAMS when the video block does
    * not fit L.  F = 0: the head is a plain multi-diagonal head. */
   int32_t rearr_first, rearr_frame_tokens, rearr_frames;

@@ -901,12 +901,13 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
   a.ws = ws;
   a.list_table = static_cast<int>(g.ws_list_table);
   if (g.mode == SVD_SKIP) return svd::launch_zero_heads(a, stream) == hipSuccess ? SVD_OK : SVD_ERR_HIP;
-  if (g.rearranged) return SVD_ERR_UNSUPPORTED;   // the rearranged form is built for the bf16 path only
   f.Lp = svd::fp8_padded_len(d.L);
+  f.map_len = (d.L + p.block_k - 1) / p.block_k * p.block_k;
   f.k8 = static_cast<uint8_t*>(ws8);
   f.v8t = f.k8 + svd::fp8_scratch_bytes(d.B, d.H, d.L, d.D) / 2;
   const int kmode = g.mode == SVD_DENSE ? svd::MODE_DENSE
-                    : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER : svd::MODE_BAND;
+                    : g.mode == SVD_VSTRIPE ? svd::MODE_GATHER
+                    : g.rearranged ? svd::MODE_PBAND : svd::MODE_BAND;
   // the pre-pass of a group runs right before its attention launch, so the
   // quantised arrays of the group are read back while they are fresh in L2
   if (svd::launch_quantise_kv(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;

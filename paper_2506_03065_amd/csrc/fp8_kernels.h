@@ -19,12 +19,14 @@ namespace svd {
 //                                   the keys, so P needs no shuffle)
 // Lp = L rounded up to a multiple of 128; keys past the head's key count are
 // zero.  For a vertical-stripe head the arrays hold the head's gathered columns
-// in list order, so the kernel walks them like a short dense head.
+// in list order, so the kernel walks them like a short dense head; for a
+// multi-diagonal head in rearranged form they hold the keys in the rearranged order.
 struct Fp8Launch {
   AttnLaunch a;          // q, out, shapes, lists, split as for the bf16 kernels (k, v: the bf16 sources of the pre-pass)
   uint8_t* k8;
   uint8_t* v8t;
   int Lp;
+  int map_len;           // PBAND: entries of the row map (L rounded up to the key tile)
 };
 
 inline int fp8_padded_len(int L) { return (L + 127) / 128 * 128; }

@@ -18,8 +18,11 @@
 //                        two products, lazy reference) on the FP8 matrix
 //                        instructions v_mfma_f32_32x32x64_f8f6f4 (both products)
 //                        and v_mfma_f32_16x16x128_f8f6f4 (row sums of P).  Modes:
-//                        DENSE, BAND, and GATHER = the dense loop over a
-//                        compacted head.
+//                        DENSE, BAND, GATHER = the dense loop over a compacted
+//                        head, and PBAND = the banded loop of a multi-diagonal
+//                        head in rearranged form (Section 4.1.2): the pre-pass
+//                        writes K8 and V8 in the rearranged order, Q rows and O
+//                        rows go through the list's row map.
 // Operand layout of the 32x32x64 instruction: lane l supplies row (column) l % 32
 // with the 32 contraction indices 32 * (l / 32) .. + 31 in its 32 bytes; the
 // result has the layout of the 32x32 bf16 instructions, so masks, maxima and the
@@ -94,10 +97,14 @@ __global__ void __launch_bounds__(256) quantise_kv_kernel(const Fp8Launch pp, co
   const int head = p.heads ? p.heads[hg] : hg;
   const int* cols = nullptr;
   int n_pad = pp.Lp;
-  if (gather) {
+  if (gather == 1) {          // vertical-stripe head: its column list
     const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
     cols = p.ws + rec[0];
     n_pad = rec[1];
+  } else if (gather == 2) {   // rearranged head: key j of the arrays is row row_map[j] of the tensors
+    const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
+    cols = p.ws + rec[3];
+    n_pad = pp.map_len;
   }
   if (G * 64 >= n_pad) return;
   const int64_t base = (int64_t)b * p.stride_b + (int64_t)head * p.stride_h;
@@ -165,6 +172,7 @@ __global__ void __launch_bounds__(256) quantise_kv_kernel(const Fp8Launch pp, co
 template <int D, int NW, int BC, int OCC, int MODE>
 __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Launch pp) {
   const AttnLaunch& p = pp.a;
+  constexpr bool kBand = MODE == MODE_BAND || MODE == MODE_PBAND;   // walks a CSR list of key tiles
   constexpr int BR = NW * 32;        // query rows per work-group (one 32-row block per wave)
   constexpr int KB2 = BC / 32;       // 32-key blocks per tile
   constexpr int G64 = BC / 64;       // 64-key contraction steps of the second product
@@ -213,19 +221,21 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   typedef const i32x2 __attribute__((address_space(4)))* const_int2_ptr;
   const_int2_ptr entries = nullptr;   // BAND
   const_int2_ptr runs = nullptr;      // BAND
+  const int* __restrict__ row_map = nullptr;   // PBAND: row of the tensors for every position of the rearranged order
   if (MODE == MODE_DENSE) {
     const int n_all = (L + BC - 1) / BC;
     t_base = chunk * n_all / p.split;
     n_tiles = (chunk + 1) * n_all / p.split - t_base;
   } else {
     const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
-    if (MODE == MODE_BAND) {
+    if (kBand) {
       const int* row_ptr = p.ws + rec[0];
       const int e0 = row_ptr[qblk], e1 = row_ptr[qblk + 1];
       entries = (const_int2_ptr)(uintptr_t)(p.ws + rec[1]) + e0;
       runs = (const_int2_ptr)(uintptr_t)(p.ws + rec[2]);
       n_tiles = e1 - e0;
       if (n_tiles == 0) return;   // rows that another launch computes (text rows of a layer with a text prefix)
+      if (MODE == MODE_PBAND) row_map = p.ws + rec[3];
     } else {
       n_tiles = rec[1] / BC;
       n_keys = rec[2];
@@ -239,6 +249,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   {
     int row = q0 + l32;
     row = row < L ? row : L - 1;
+    if (MODE == MODE_PBAND) row = row_map[row];   // the pre-pass moved K and V; Q and O go through the map
     const __bf16* src = Q + (int64_t)row * p.stride_l + half * 32;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -306,7 +317,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
     constexpr bool IS_K = decltype(is_k_tag)::value != 0;
     const __amdgpu_buffer_rsrc_t rsrc = IS_K ? rsrc_k : rsrc_v;
     unsigned char* dst = (IS_K ? sK : sV) + buf * TILE_BYTES + wave * (LPT * 1024);
-    const int tile = MODE == MODE_BAND ? entries[t].x : t + t_base;
+    const int tile = kBand ? entries[t].x : t + t_base;
 #pragma unroll
     for (int u = 0; u < LPT; ++u)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dst + u * 1024), 16, (int)(IS_K ? g_k[u] : g_v[u]),
@@ -346,7 +357,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   // element by element.
   auto apply_mask = [&](f32x16 (&s)[KB2], const int t) -> bool {
     bool changed = false;
-    if (MODE == MODE_BAND) {
+    if (kBand) {
       const i32x2 ent = entries[t];
       const int kv0 = ent.x * BC;
       const int r0 = (ent.y >> 1) & 0x7fff, rn = ent.y >> 16;
@@ -509,7 +520,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       if (has2) load_tile(Int<1>{}, PAR, t + 2);
       if (has1) load_tile(Int<0>{}, PAR ^ 1, t + 1);
       bool masked;
-      if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+      if (kBand) masked = !(entries[t].y & 1);
       else if (INNER) masked = false;
       else masked = (t + t_base + 1) * BC > n_keys;
       if (masked && apply_mask(s_cur, t)) tile_max(s_cur);
@@ -600,7 +611,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       if (has2) load_tile(Int<1>{}, PAR, t + 2);   // K(t+2) takes the place of K(t), read in the last stage
       load_tile(Int<0>{}, PAR, t);                 // V(t) takes the place of V(t-2)
       bool masked;
-      if (MODE == MODE_BAND) masked = !(entries[t].y & 1);
+      if (kBand) masked = !(entries[t].y & 1);
       else if (INNER) masked = false;
       else masked = (t + t_base + 1) * BC > n_keys;
       if (masked && apply_mask(s_cur, t)) tile_max(s_cur);
@@ -695,7 +706,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   const float inv = 1.0f / l4[0];
   const int row = q0 + l32;
   if (row < L) {
-    __bf16* dst = O + (int64_t)row * p.stride_l;
+    __bf16* dst = O + (int64_t)(MODE == MODE_PBAND ? row_map[row] : row) * p.stride_l;
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -725,6 +736,9 @@ hipError_t launch_mode_fp8(const Fp8Launch& p, int mode, hipStream_t stream) {
     case MODE_GATHER:
       hipLaunchKernelGGL((attn_fwd_fp8_kernel<D, NW, BC, OCC, MODE_GATHER>), grid, block, 0, stream, p);
       break;
+    case MODE_PBAND:
+      hipLaunchKernelGGL((attn_fwd_fp8_kernel<D, NW, BC, OCC, MODE_PBAND>), grid, block, 0, stream, p);
+      break;
     default:
       return hipErrorInvalidValue;
   }
@@ -737,7 +751,8 @@ hipError_t launch_quantise_kv(const Fp8Launch& p, int mode, hipStream_t stream) 
   if (p.a.n_heads <= 0) return hipSuccess;
   if (!p.k8 || !p.v8t || p.Lp != fp8_padded_len(p.a.L)) return hipErrorInvalidValue;
   const dim3 grid(p.Lp / 64, p.a.n_heads * p.a.B), block(256);
-  const int gather = mode == MODE_GATHER ? 1 : 0;
+  const int gather = mode == MODE_GATHER ? 1 : mode == MODE_PBAND ? 2 : 0;
+  if (gather == 2 && (p.map_len < 1 || p.map_len > p.Lp)) return hipErrorInvalidValue;
   if (p.a.D == 128) hipLaunchKernelGGL(quantise_kv_kernel<128>, grid, block, 0, stream, p, gather);
   else if (p.a.D == 64) hipLaunchKernelGGL(quantise_kv_kernel<64>, grid, block, 0, stream, p, gather);
   else return hipErrorInvalidValue;

@@ -113,9 +113,13 @@ def test_rearranged_heads_in_a_layer_all_rows(L, D, B, first, N, F, w):
     ref = rearranged_window_attention(q[:, h:h + 1].contiguous(), k[:, h:h + 1].contiguous(), v[:, h:h + 1].contiguous(),
                                       first, N, F, w * F + F - 1)
     assert_close(f64(out[0, h]), f64(ref[0, 0]), "row-map path against the copy path")
+    # FP8 variant: the pre-pass writes K8 and V8 in the rearranged order
+    from test_gpu_fp8 import check_layer_fp8, run_fp8
+    out8, _ = run_fp8(wl, q, k, v)
+    check_layer_fp8(wl, q, k, v, out8)
 
 
-def test_rearranged_heads_wan_shape_sampled_rows_and_fp8_refusal():
+def test_rearranged_heads_wan_shape_sampled_rows():
     from parity_util import check_layer, run_planned
     L, D, N, F, w = 75600, 128, 3600, 21, 40
     table = np.asarray([W.MULTIDIAG, W.MULTIDIAG, W.DIAG], dtype=np.int32)
@@ -127,11 +131,6 @@ def test_rearranged_heads_wan_shape_sampled_rows_and_fp8_refusal():
     rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(L - 4, L), [N - 1, N, 20 * N, 20 * N + N - 1],
                                      np.random.default_rng(3).integers(0, L, 20)]))
     check_layer(wl, q, k, v, out, rows=rows)
-    desc = svd.desc_of(q)
-    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, table, params), dtype=torch.uint8, device=DEV)
-    plan = svd.svd_plan_create(desc, table, params, workspace=ws)
-    ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
-    with pytest.raises(svd.SvdError) as e:
-        svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
-    assert e.value.status == 9
-    plan.close()
+    from test_gpu_fp8 import check_layer_fp8, run_fp8
+    out8, _ = run_fp8(wl, q, k, v)
+    check_layer_fp8(wl, q, k, v, out8, rows=rows)
