@@ -264,6 +264,8 @@ def run_rearranged(args, torch, np, svd, W):
     ms_fused = gpu_time_ms(lambda: svd.svd_attn_forward_planned(fused, q, k, v, out), args.steps, args.warmup, torch)
     torch.cuda.synchronize()
     max_diff = float((out.float() - out_copy.float()).abs().max())
+    ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    ms_fused8 = gpu_time_ms(lambda: svd.svd_attn_forward_fp8(fused, q, k, v, out, ws8), args.steps, args.warmup, torch)
     tensor_bytes = q.numel() * 2
     wd, wm = diag.work(), multi.work()
     result = {
@@ -273,6 +275,7 @@ def run_rearranged(args, torch, np, svd, W):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "rearranged window, Wan2.1-like shape", "B": 1, "H": H, "L": L, "D": D,
                    "frame_tokens": N, "frames": F, "position_half_width": w, "band_half_width": Wd},
+        "fp8_row_map_ms": round(ms_fused8, 4),
         "copy_path_ms": round(ms, 4),
         "max_abs_diff_row_map_vs_copy_path": max_diff,
         "row_map_tflops": round(wd["computed_flops"] / 1e9 / ms_fused, 1),
