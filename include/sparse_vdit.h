@@ -20,8 +20,13 @@
  *
  * The softmax is renormalised over the kept keys.  Heads of one layer that
  * share a mode are fused into one kernel launch (Section 4.2, last paragraph).
- * The per-head mode table is an input: the offline search that produces it
- * (Section 4.2, Eq. 2-3, Algorithm 1) is not part of this library.
+ * The per-head mode table is an input of the forward pass.  Around it the
+ * library also offers: one layer of the offline search that produces the table
+ * (Section 4.2, Eq. 2-3, Algorithm 1: svd_search_layer and its parts), an FP8
+ * variant of the forward pass (Appendix B: svd_attn_forward_fp8), dense borders
+ * for a text prefix (Section 4.1.1: plan option text_tokens), and the
+ * multi-diagonal mode in rearranged form (Section 4.1.2: head parameters
+ * rearr_*, svd_rearrange_tokens).
  *
  * Conventions for every entry point
  *  - Tensors q, k, v, out are DEVICE pointers to bf16 (bfloat16) data described
@@ -32,7 +37,7 @@
  *  - strategy_table and pattern_params are HOST pointers; they are read during
  *    the call and not kept.  The same table applies to every batch entry.
  *  - The library never allocates or frees device memory and never synchronises
- *    the device.  Plans place their index lists in a caller-provided DEVICE
+ *    the device (svd_search_layer excepted, which returns results to the host).  Plans place their index lists in a caller-provided DEVICE
  *    workspace that must stay alive and untouched while the plan is in use.
  *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *    Kernels are enqueued on it and the call returns without waiting.
