@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SVD_OK", 1: "SVD_ERR_NULL", 2: "SVD_ERR_SHAPE", 3: "SVD_ERR_
 SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
-           "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
+           "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_group_blocks", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
@@ -76,6 +76,7 @@ def lib():
             "svd_plan_num_groups": [vp, i32p],
             "svd_plan_group_info": [vp, C.c_int32, i32p, i32p, i32pp, i32pp, i32p],
             "svd_plan_group_rearranged": [vp, C.c_int32, i32p],
+            "svd_plan_group_blocks": [vp, C.c_int32, i32p, i32p],
             "svd_plan_row_map": [vp, C.c_int32, C.c_int32, i32p, i32pp],
             "svd_plan_band_list": [vp, C.c_int32, C.c_int32, i32p, i32pp, i32pp, i32pp, i32pp, i32pp, i32p, i32pp],
             "svd_plan_column_list": [vp, C.c_int32, C.c_int32, i32p, i32p, i32pp],
@@ -236,9 +237,11 @@ class Plan:
                                           C.byref(lid), C.byref(nl)), "svd_plan_group_info")
             rearranged = C.c_int32()
             _check(L_.svd_plan_group_rearranged(self.handle, g, C.byref(rearranged)), "svd_plan_group_rearranged")
+            gbq, gbk = C.c_int32(), C.c_int32()
+            _check(L_.svd_plan_group_blocks(self.handle, g, C.byref(gbq), C.byref(gbk)), "svd_plan_group_blocks")
             out.append({"mode": mode.value, "heads": _copy(heads, nh.value).tolist(),
                         "list_id": _copy(lid, nh.value).tolist(), "n_lists": nl.value,
-                        "rearranged": bool(rearranged.value)})
+                        "rearranged": bool(rearranged.value), "block_q": gbq.value, "block_k": gbk.value})
         return out
 
     def row_map(self, group, lst):

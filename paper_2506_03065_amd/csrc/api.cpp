@@ -67,6 +67,13 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
   return SVD_OK;
 }
 
+// The small query tile is offered to the band groups only when the caller left
+// the block shape to the library (an explicit shape applies to every group).
+int32_t small_block_q(const svd_tensor_desc& desc, const svd_plan_options* opt) {
+  if (opt && (opt->block_q || opt->block_k)) return 0;
+  return svd::kernel_small_block_q(desc.D);
+}
+
 // Compute units of the current device, 0 when there is none (host-only use).
 int device_compute_units() {
   int dev = 0, n_cu = 0;
@@ -261,7 +268,7 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
   Plan tmp;
   if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk,
-                                        options ? options->text_tokens : 0, &tmp))
+                                        options ? options->text_tokens : 0, small_block_q(*desc, options), &tmp))
     return st;
   const int n_cu = device_compute_units();
   const int split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), n_cu, options) : 1;
@@ -283,7 +290,8 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
   if (!sp) return SVD_ERR_HIP;
   svd_status st = SVD_OK;
   try {
-    st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, options ? options->text_tokens : 0, &sp->p);
+    st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, options ? options->text_tokens : 0,
+                           small_block_q(*desc, options), &sp->p);
   } catch (...) {
     st = SVD_ERR_UNSUPPORTED;
   }
@@ -329,7 +337,7 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
             if (g.mode == mode && !heavy) heavy = &g;
         }
         if (heavy) {
-          const long long items = static_cast<long long>(sp->p.n_q_blocks) * heavy->heads.size() * desc->B *
+          const long long items = static_cast<long long>(heavy->n_q_blocks) * heavy->heads.size() * desc->B *
                                   (heavy->mode == SVD_DENSE ? sp->dense_split : 1);
           const long long tail = items % n_cu;
           sp->concurrent = tail != 0 && 2 * tail < n_cu;
@@ -356,6 +364,14 @@ svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split) {
 svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups) {
   if (!plan || !n_groups) return SVD_ERR_NULL;
   *n_groups = static_cast<int32_t>(plan->p.groups.size());
+  return SVD_OK;
+}
+
+svd_status svd_plan_group_blocks(const svd_plan* plan, int32_t group, int32_t* block_q, int32_t* block_k) {
+  if (!plan) return SVD_ERR_NULL;
+  if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
+  if (block_q) *block_q = plan->p.groups[group].block_q;
+  if (block_k) *block_k = plan->p.block_k;
   return SVD_OK;
 }
 
@@ -400,7 +416,7 @@ svd_status svd_plan_band_list(const svd_plan* plan, int32_t group, int32_t list,
   const svd::Group& g = plan->p.groups[group];
   if (list < 0 || list >= static_cast<int32_t>(g.bands.size())) return SVD_ERR_SHAPE;
   const svd::BandList& bl = g.bands[list];
-  if (n_q_blocks) *n_q_blocks = plan->p.n_q_blocks;
+  if (n_q_blocks) *n_q_blocks = g.n_q_blocks;
   if (row_ptr) *row_ptr = bl.row_ptr.data();
   if (kv_block_idx) *kv_block_idx = bl.kv_block_idx.data();
   if (flags) *flags = bl.flags.data();
@@ -507,13 +523,14 @@ static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const vo
   const Plan& p = sp.p;
   const int* ws = static_cast<const int*>(p.device_workspace);
   svd::AttnLaunch a = base_launch(p.desc, q, k, v, out);
-  a.n_q_blocks = p.n_q_blocks;
+  a.n_q_blocks = g.n_q_blocks;
   a.n_heads = static_cast<int>(g.heads.size());
   a.n_items = a.n_q_blocks * a.n_heads * a.B;
   a.heads = ws + g.ws_heads;
   a.list_id = ws + g.ws_list_id;
   a.ws = ws;
   a.list_table = static_cast<int>(g.ws_list_table);
+  const bool small_q = g.block_q != p.block_q;   // band group compiled for the small query tile
   hipError_t err;
   if (g.mode == SVD_SKIP) {
     err = svd::launch_zero_heads(a, stream);
@@ -526,7 +543,7 @@ static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const vo
       a.n_items *= a.split;
       a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.partial_offset);
     }
-    err = svd::launch_attention(a, kmode, stream);
+    err = svd::launch_attention(a, kmode, stream, small_q);
     if (err == hipSuccess && a.split > 1) err = svd::launch_combine(a, stream);
     if (err == hipSuccess && has_text_rows(p, g)) {
       // Section 4.1.1: text queries see every key.  Their rows (the first
@@ -893,7 +910,7 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
   svd::Fp8Launch f{};
   svd::AttnLaunch& a = f.a;
   a = base_launch(d, q, k, v, out);
-  a.n_q_blocks = p.n_q_blocks;
+  a.n_q_blocks = g.n_q_blocks;
   a.n_heads = static_cast<int>(g.heads.size());
   a.n_items = a.n_q_blocks * a.n_heads * a.B;
   a.heads = ws + g.ws_heads;
@@ -916,7 +933,7 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
     a.n_items *= a.split;
     a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.partial_offset);
   }
-  if (svd::launch_attention_fp8(f, kmode, stream) != hipSuccess) return SVD_ERR_HIP;
+  if (svd::launch_attention_fp8(f, kmode, stream, g.block_q != p.block_q) != hipSuccess) return SVD_ERR_HIP;
   if (a.split > 1 && svd::launch_combine(a, stream) != hipSuccess) return SVD_ERR_HIP;
   if (has_text_rows(p, g)) {
     // text rows: dense over every key; a stripe head's arrays hold its columns

@@ -23,10 +23,23 @@ enum { MODE_DENSE = 0, MODE_BAND = 1, MODE_GATHER = 2, MODE_PBAND = 3 };
 #ifndef SVD_T64
 #define SVD_T64 8, 1, 128, 2
 #endif
+// Small query tile (half the waves, two work-groups per compute unit) for band
+// groups whose bands are narrow: with 128 instead of 256 query rows per tile the
+// listed tiles hug the band more closely, which saves more work than the halved
+// reuse of a K/V tile costs.  Same key tile, so one plan geometry along the keys.
+#ifndef SVD_T128S
+#define SVD_T128S 4, 1, 64, 2
+#endif
+#ifndef SVD_T64S
+#define SVD_T64S 4, 1, 128, 2
+#endif
 template <int NW_, int QB_, int BC_, int OCC_>
 struct TileShape { static constexpr int NW = NW_, QB = QB_, BC = BC_, OCC = OCC_; };
 using Tile128 = TileShape<SVD_T128>;   // D = 128
 using Tile64 = TileShape<SVD_T64>;     // D = 64
+using Tile128s = TileShape<SVD_T128S>;
+using Tile64s = TileShape<SVD_T64S>;
+static_assert(Tile128s::BC == Tile128::BC && Tile64s::BC == Tile64::BC, "the small query tile keeps the key tile");
 
 struct AttnLaunch {
   const __bf16* q;
@@ -55,7 +68,11 @@ struct AttnLaunch {
 size_t partial_floats(int D, int n_items);
 
 void kernel_blocks(int D, int* block_q, int* block_k);
-hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream);
+// Query rows of the small tile (band modes only).
+int kernel_small_block_q(int D);
+// small_q: the launch uses the small query tile (MODE_BAND and MODE_PBAND only;
+// n_q_blocks and the lists must have been built for it).
+hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, bool small_q = false);
 hipError_t launch_zero_heads(const AttnLaunch& p, hipStream_t stream);
 // Merges the chunks of a split dense launch (same AttnLaunch) into `out`.
 hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream);

@@ -729,7 +729,26 @@ hipError_t launch_mode(const AttnLaunch& p, int mode, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// The band modes on the small query tile.
+template <int D, int NW, int QB, int BC, int OCC>
+hipError_t launch_band_small(const AttnLaunch& p, int mode, hipStream_t stream) {
+  const int per_xcd = (p.n_items + 7) / 8;
+  const dim3 grid(per_xcd * 8), block(NW * 64);
+  if (mode == MODE_BAND) {
+    hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_BAND>), grid, block, 0, stream, p);
+  } else if (mode == MODE_PBAND) {
+    hipLaunchKernelGGL((attn_fwd_kernel<D, NW, QB, BC, OCC, MODE_PBAND>), grid, block, 0, stream, p);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
+
+int kernel_small_block_q(int D) {
+  return D == 128 ? Tile128s::NW * Tile128s::QB * 32 : Tile64s::NW * Tile64s::QB * 32;
+}
 
 void kernel_blocks(int D, int* block_q, int* block_k) {
   if (D == 128) {
@@ -741,9 +760,14 @@ void kernel_blocks(int D, int* block_q, int* block_k) {
   }
 }
 
-hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream) {
+hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, bool small_q) {
   if (p.n_items <= 0) return hipSuccess;
   if (p.split < 1 || (p.split > 1 && (mode != MODE_DENSE || !p.partial))) return hipErrorInvalidValue;
+  if (small_q) {
+    if (p.D == 128) return launch_band_small<128, Tile128s::NW, Tile128s::QB, Tile128s::BC, Tile128s::OCC>(p, mode, stream);
+    if (p.D == 64) return launch_band_small<64, Tile64s::NW, Tile64s::QB, Tile64s::BC, Tile64s::OCC>(p, mode, stream);
+    return hipErrorInvalidValue;
+  }
   if (p.D == 128)
     return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC, Tile128::OCC>(p, mode, stream);
   if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC, Tile64::OCC>(p, mode, stream);

@@ -39,6 +39,7 @@ inline size_t fp8_scratch_bytes(int B, int H, int L, int D) {
 hipError_t launch_quantise_kv(const Fp8Launch& p, int mode, hipStream_t stream);
 // Attention of one group on the quantised arrays; split dense launches are merged
 // with launch_combine of the bf16 kernels (same partial layout).
-hipError_t launch_attention_fp8(const Fp8Launch& p, int mode, hipStream_t stream);
+// small_q as for launch_attention.
+hipError_t launch_attention_fp8(const Fp8Launch& p, int mode, hipStream_t stream, bool small_q = false);
 
 }  // namespace svd

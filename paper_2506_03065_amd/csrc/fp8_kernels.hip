@@ -759,10 +759,27 @@ hipError_t launch_quantise_kv(const Fp8Launch& p, int mode, hipStream_t stream) 
   return hipGetLastError();
 }
 
-hipError_t launch_attention_fp8(const Fp8Launch& p, int mode, hipStream_t stream) {
+hipError_t launch_attention_fp8(const Fp8Launch& p, int mode, hipStream_t stream, bool small_q) {
   if (p.a.n_items <= 0) return hipSuccess;
   if (!p.k8 || !p.v8t || p.Lp != fp8_padded_len(p.a.L)) return hipErrorInvalidValue;
   if (p.a.split < 1 || (p.a.split > 1 && (mode != MODE_DENSE || !p.a.partial))) return hipErrorInvalidValue;
+  if (small_q) {   // band modes on the small query tile
+    if (mode != MODE_BAND && mode != MODE_PBAND) return hipErrorInvalidValue;
+    const int per_xcd = (p.a.n_items + 7) / 8;
+    const dim3 grid(per_xcd * 8);
+    if (p.a.D == 128) {
+      using T = Tile128s;
+      if (mode == MODE_BAND) hipLaunchKernelGGL((attn_fwd_fp8_kernel<128, T::NW, T::BC, T::OCC, MODE_BAND>), grid, dim3(T::NW * 64), 0, stream, p);
+      else hipLaunchKernelGGL((attn_fwd_fp8_kernel<128, T::NW, T::BC, T::OCC, MODE_PBAND>), grid, dim3(T::NW * 64), 0, stream, p);
+    } else if (p.a.D == 64) {
+      using T = Tile64s;
+      if (mode == MODE_BAND) hipLaunchKernelGGL((attn_fwd_fp8_kernel<64, T::NW, T::BC, T::OCC, MODE_BAND>), grid, dim3(T::NW * 64), 0, stream, p);
+      else hipLaunchKernelGGL((attn_fwd_fp8_kernel<64, T::NW, T::BC, T::OCC, MODE_PBAND>), grid, dim3(T::NW * 64), 0, stream, p);
+    } else {
+      return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   // the tiles are those of the bf16 kernels, so one plan serves both
   static_assert(Tile128::QB == 1 && Tile64::QB == 1, "the FP8 kernel keeps one 32-row block per wave");
   if (p.a.D == 128) return launch_mode_fp8<128, Tile128::NW, Tile128::BC, Tile128::OCC>(p, mode, stream);

@@ -166,7 +166,7 @@ svd_status validate_desc(const svd_tensor_desc* desc) {
 
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
-                        int32_t text_tokens, Plan* plan) {
+                        int32_t text_tokens, int32_t block_q_small, Plan* plan) {
   if (!strategy_table || !pattern_params || !plan) return SVD_ERR_NULL;
   if (svd_status st = validate_desc(&desc)) return st;
   if (block_q < 1 || block_k < 1) return SVD_ERR_UNSUPPORTED;
@@ -289,7 +289,32 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
       g.heads.push_back(h);
       g.list_id.push_back(id);
     }
-    if (!g.heads.empty()) plan->groups.push_back(std::move(g));
+    if (g.heads.empty()) continue;
+    g.block_q = block_q;
+    if (!g.bands.empty() && block_q_small > 0 && block_q_small < block_q && T % block_q_small == 0) {
+      // the same lists on the small query tile: taken when they cover clearly less area
+      std::vector<BandList> alt;
+      for (const BandList& bl : g.bands) {
+        BandList a;
+        a.half_width = bl.half_width;
+        a.offsets = bl.offsets;
+        a.runs = bl.runs;
+        a.row_map = bl.row_map;
+        build_band_list(&a, L, block_q_small, block_k, T);
+        alt.push_back(std::move(a));
+      }
+      double area = 0.0, area_small = 0.0;
+      for (size_t t = 0; t < g.heads.size(); ++t) {
+        area += g.bands[g.list_id[t]].tile_area;
+        area_small += alt[g.list_id[t]].tile_area;
+      }
+      if (area_small < 0.96 * area) {
+        g.bands.swap(alt);
+        g.block_q = block_q_small;
+      }
+    }
+    g.n_q_blocks = static_cast<int32_t>(ceil_div(L, g.block_q));
+    plan->groups.push_back(std::move(g));
   }
 
   // Image of the device workspace.

@@ -41,6 +41,9 @@ struct ColumnList {
 struct Group {
   int32_t mode = 0;
   bool rearranged = false;            // mode 3 heads in rearranged form (a group of their own)
+  // query rows per tile of this group's lists and launches: the plan's block_q,
+  // or the small query tile for band groups with narrow bands
+  int32_t block_q = 0, n_q_blocks = 0;
   std::vector<int32_t> heads;         // ascending
   std::vector<int32_t> list_id;       // per head of the group
   std::vector<BandList> bands;        // modes 2, 3
@@ -77,9 +80,11 @@ struct Plan {
 // are computed densely by the caller of the kernels), every other query block
 // lists the text key tiles, kept whole, ahead of its band tiles, and the column
 // lists gain the text columns.
+// block_q_small > 0: band groups (modes 2 and 3) whose lists cover at least 4 %
+// less area with that many query rows per tile are compiled for it.
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
-                        int32_t text_tokens, Plan* plan);
+                        int32_t text_tokens, int32_t block_q_small, Plan* plan);
 
 svd_status validate_desc(const svd_tensor_desc* desc);
 

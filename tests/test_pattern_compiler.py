@@ -301,3 +301,52 @@ def test_rearranged_heads_validation():
     with pytest.raises(svd.SvdError) as e:
         svd.svd_plan_create(desc, table, [{"half_width": -1, "rearranged": (0, 64, 4)}], 256, 128)
     assert e.value.status == 6
+
+
+# ---- small query tile for band groups with narrow bands ----
+
+def test_default_plan_gives_narrow_band_groups_the_small_query_tile():
+    L, D = 3000, 64
+    table = np.asarray([W.DENSE, W.DIAG, W.MULTIDIAG, W.VSTRIPE, W.MULTIDIAG], dtype=np.int32)
+    params = [{}, {"half_width": 1400}, {"half_width": 20, "offsets": (-600, 0, 600)}, {"cols": tuple(range(0, L, 9))},
+              {"half_width": 30, "rearranged": (0, 300, 10)}]
+    wl = W.Workload("tiles", -1, 1, len(table), L, D, 600, 5, 0, table, params, 3)
+    desc = svd.tensor_desc(1, wl.H, L, D)
+    plan = svd.svd_plan_create(desc, table, params)                # block shape left to the library
+    bq, bk = svd.svd_default_blocks(D)
+    small = {g["mode"]: g["block_q"] for g in plan.groups() if not g["rearranged"]}
+    assert small[W.DENSE] == bq and small[W.VSTRIPE] == bq
+    assert small[W.DIAG] == bq                                      # a wide band gains too little
+    assert small[W.MULTIDIAG] == bq // 2                            # narrow bands: half the query rows per tile
+    for gi, g in enumerate(plan.groups()):
+        assert g["block_k"] == bk
+        if g["mode"] in (W.DIAG, W.MULTIDIAG):
+            if g["rearranged"]:
+                assert g["block_q"] == bq // 2
+            head = g["heads"][0]
+            got = plan.band_list(gi, 0)
+            want = O.block_lists(g["mode"], params[head], L, g["block_q"], bk)
+            for key in ("row_ptr", "kv_block_idx", "flags", "run_first", "run_count", "runs"):
+                assert np.array_equal(got[key], want[key]), (g["mode"], key)
+    # the work counts follow the chosen tiles
+    area = 0.0
+    for gi, g in enumerate(plan.groups()):
+        for h in g["heads"]:
+            mode, p = int(table[h]), params[h]
+            if mode == W.DENSE:
+                area += L * L
+            elif mode == W.VSTRIPE:
+                area += L * len(p["cols"])
+            else:
+                lists = O.block_lists(mode, p, L, g["block_q"], bk)
+                rows = np.diff(lists["row_ptr"])
+                for qb, n in enumerate(rows):
+                    r = min(L, (qb + 1) * g["block_q"]) - qb * g["block_q"]
+                    kbs = lists["kv_block_idx"][lists["row_ptr"][qb]:lists["row_ptr"][qb + 1]]
+                    area += sum(r * (min(L, (kb + 1) * bk) - kb * bk) for kb in kbs)
+    assert abs(plan.work()["computed_flops"] - 4.0 * D * area) <= 1e-6 * 4.0 * D * area
+    plan.close()
+    # an explicit block shape applies to every group
+    plan = svd.svd_plan_create(desc, table, params, bq, bk)
+    assert {g["block_q"] for g in plan.groups()} == {bq}
+    plan.close()
