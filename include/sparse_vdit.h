@@ -164,9 +164,10 @@ svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups);
  * numbered by first appearance); n_lists is 0 for dense and skip groups. */
 /* Block shape of one group's lists and launches.  block_k is the plan's; block_q
  * is the plan's too, except for a band group (modes 2, 3) of a plan created
- * without an explicit block shape: when its lists cover at least 4 % less area
+ * without an explicit block shape: when its lists cover at least 1 % less area
  * with the kernels' small query tile (128 rows instead of 256: the listed tiles
- * hug narrow bands more closely), the group is compiled and launched with it.
+ * hug the bands more closely, and two work-groups share a compute unit), the
+ * group is compiled and launched with it.
  * svd_plan_band_list reports the matching number of query blocks. */
 svd_status svd_plan_group_blocks(const svd_plan* plan, int32_t group, int32_t* block_q, int32_t* block_k);
 /* (Rearranged multi-diagonal heads form a group of their own, after the plain

@@ -763,18 +763,20 @@ hipError_t launch_attention_fp8(const Fp8Launch& p, int mode, hipStream_t stream
   if (p.a.n_items <= 0) return hipSuccess;
   if (!p.k8 || !p.v8t || p.Lp != fp8_padded_len(p.a.L)) return hipErrorInvalidValue;
   if (p.a.split < 1 || (p.a.split > 1 && (mode != MODE_DENSE || !p.a.partial))) return hipErrorInvalidValue;
-  if (small_q) {   // band modes on the small query tile
-    if (mode != MODE_BAND && mode != MODE_PBAND) return hipErrorInvalidValue;
+  if (small_q) {   // small query tile: the band modes, and the compacted stripe heads (no list depends on it)
+    if (mode != MODE_BAND && mode != MODE_PBAND && mode != MODE_GATHER) return hipErrorInvalidValue;
     const int per_xcd = (p.a.n_items + 7) / 8;
     const dim3 grid(per_xcd * 8);
     if (p.a.D == 128) {
       using T = Tile128s;
       if (mode == MODE_BAND) hipLaunchKernelGGL((attn_fwd_fp8_kernel<128, T::NW, T::BC, T::OCC, MODE_BAND>), grid, dim3(T::NW * 64), 0, stream, p);
-      else hipLaunchKernelGGL((attn_fwd_fp8_kernel<128, T::NW, T::BC, T::OCC, MODE_PBAND>), grid, dim3(T::NW * 64), 0, stream, p);
+      else if (mode == MODE_PBAND) hipLaunchKernelGGL((attn_fwd_fp8_kernel<128, T::NW, T::BC, T::OCC, MODE_PBAND>), grid, dim3(T::NW * 64), 0, stream, p);
+      else hipLaunchKernelGGL((attn_fwd_fp8_kernel<128, T::NW, T::BC, T::OCC, MODE_GATHER>), grid, dim3(T::NW * 64), 0, stream, p);
     } else if (p.a.D == 64) {
       using T = Tile64s;
       if (mode == MODE_BAND) hipLaunchKernelGGL((attn_fwd_fp8_kernel<64, T::NW, T::BC, T::OCC, MODE_BAND>), grid, dim3(T::NW * 64), 0, stream, p);
-      else hipLaunchKernelGGL((attn_fwd_fp8_kernel<64, T::NW, T::BC, T::OCC, MODE_PBAND>), grid, dim3(T::NW * 64), 0, stream, p);
+      else if (mode == MODE_PBAND) hipLaunchKernelGGL((attn_fwd_fp8_kernel<64, T::NW, T::BC, T::OCC, MODE_PBAND>), grid, dim3(T::NW * 64), 0, stream, p);
+      else hipLaunchKernelGGL((attn_fwd_fp8_kernel<64, T::NW, T::BC, T::OCC, MODE_GATHER>), grid, dim3(T::NW * 64), 0, stream, p);
     } else {
       return hipErrorInvalidValue;
     }

@@ -292,7 +292,8 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
     if (g.heads.empty()) continue;
     g.block_q = block_q;
     if (!g.bands.empty() && block_q_small > 0 && block_q_small < block_q && T % block_q_small == 0) {
-      // the same lists on the small query tile: taken when they cover clearly less area
+      // the same lists on the small query tile: taken unless the bands are so wide that it saves
+      // less than 1 % of the area (then the halved reuse of a K/V tile costs more than it brings)
       std::vector<BandList> alt;
       for (const BandList& bl : g.bands) {
         BandList a;
@@ -308,7 +309,7 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
         area += g.bands[g.list_id[t]].tile_area;
         area_small += alt[g.list_id[t]].tile_area;
       }
-      if (area_small < 0.96 * area) {
+      if (area_small < 0.99 * area) {
         g.bands.swap(alt);
         g.block_q = block_q_small;
       }

@@ -80,7 +80,7 @@ struct Plan {
 // are computed densely by the caller of the kernels), every other query block
 // lists the text key tiles, kept whole, ahead of its band tiles, and the column
 // lists gain the text columns.
-// block_q_small > 0: band groups (modes 2 and 3) whose lists cover at least 4 %
+// block_q_small > 0: band groups (modes 2 and 3) whose lists cover at least 1 %
 // less area with that many query rows per tile are compiled for it.
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,

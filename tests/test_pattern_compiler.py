@@ -308,7 +308,7 @@ def test_rearranged_heads_validation():
 def test_default_plan_gives_narrow_band_groups_the_small_query_tile():
     L, D = 3000, 64
     table = np.asarray([W.DENSE, W.DIAG, W.MULTIDIAG, W.VSTRIPE, W.MULTIDIAG], dtype=np.int32)
-    params = [{}, {"half_width": 1400}, {"half_width": 20, "offsets": (-600, 0, 600)}, {"cols": tuple(range(0, L, 9))},
+    params = [{}, {"half_width": 2990}, {"half_width": 20, "offsets": (-600, 0, 600)}, {"cols": tuple(range(0, L, 9))},
               {"half_width": 30, "rearranged": (0, 300, 10)}]
     wl = W.Workload("tiles", -1, 1, len(table), L, D, 600, 5, 0, table, params, 3)
     desc = svd.tensor_desc(1, wl.H, L, D)
@@ -316,7 +316,7 @@ def test_default_plan_gives_narrow_band_groups_the_small_query_tile():
     bq, bk = svd.svd_default_blocks(D)
     small = {g["mode"]: g["block_q"] for g in plan.groups() if not g["rearranged"]}
     assert small[W.DENSE] == bq and small[W.VSTRIPE] == bq
-    assert small[W.DIAG] == bq                                      # a wide band gains too little
+    assert small[W.DIAG] == bq                                      # a band as wide as the map gains nothing
     assert small[W.MULTIDIAG] == bq // 2                            # narrow bands: half the query rows per tile
     for gi, g in enumerate(plan.groups()):
         assert g["block_k"] == bk
