@@ -65,9 +65,10 @@ def cpu_baseline(wl, q, k, v, out, budget_s, torch, np, fp8=False):
     rows = np.sort(gen.choice(wl.L, size=n_rows, replace=False))
     spent, heads_done, max_err, sum_err, n_err = 0.0, 0, 0.0, 0.0, 0
     f64 = lambda t: t.cpu().to(torch.float64).numpy()
+    b = wl.B - 1      # the last batch element
     for h in range(wl.H):
         mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
-        qh, kh, vh = f64(q[0, h][torch.as_tensor(rows)]), f64(k[0, h]), f64(v[0, h])
+        qh, kh, vh = f64(q[b, h][torch.as_tensor(rows)]), f64(k[b, h]), f64(v[b, h])
         full_q = np.zeros((wl.L, wl.D))
         full_q[rows] = qh
         t0 = time.perf_counter()
@@ -77,7 +78,7 @@ def cpu_baseline(wl, q, k, v, out, budget_s, torch, np, fp8=False):
             want = O.attention_head(full_q, kh, vh, mode, p, rows=rows)
         spent += time.perf_counter() - t0
         heads_done += 1
-        got = f64(out[0, h][torch.as_tensor(rows)])
+        got = f64(out[b, h][torch.as_tensor(rows)])
         err = np.abs(got - want)
         max_err, sum_err, n_err = max(max_err, float(err.max())), sum_err + float(err.sum()), n_err + err.size
         if spent > budget_s:
@@ -307,6 +308,10 @@ def main():
     ap.add_argument("--workload", default="cogvideox1.5")
     ap.add_argument("--precision", default="bf16", choices=["bf16", "fp8"],
                     help="bf16 (the headline metric) or the FP8 E4M3 variant of the same layer")
+    ap.add_argument("--layout", default="bhld", choices=["bhld", "blhd"],
+                    help="storage order of q, k, v, out: head-major [B,H,L,D] (default) or the model's token-major "
+                         "[B,L,H,D] (Eq. 1's head concatenation then needs no copy); the kernels take either through strides")
+    ap.add_argument("--batch", type=int, default=None, help="batch size B (default: the workload's, 1); 2 = a CFG pair")
     ap.add_argument("--dense-reps", type=int, default=2, help="timed passes of the all-heads dense baseline (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=25.0, help="budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -342,8 +347,15 @@ def main():
         run_rearranged(args, torch, np, svd, W)
         return
     wl = W.BY_NAME[args.workload]()
+    if args.batch is not None:
+        if args.batch < 1:
+            print("--batch must be at least 1", file=sys.stderr)
+            sys.exit(2)
+        wl.B = args.batch
     t0 = time.perf_counter()
     q, k, v = (t.to(dev) for t in W.make_qkv(wl))
+    if args.layout == "blhd":      # token-major storage, seen through a [B,H,L,D] view
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
     gen_s = time.perf_counter() - t0
     out = torch.empty_like(q)
     desc = svd.desc_of(q)
@@ -433,7 +445,7 @@ def main():
         "vs_baseline": None,
         "dtype": "fp8-e4m3 (fp32 accumulation)" if fp8 else "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "precision": args.precision, "text_tokens_with_dense_borders": int(wl.pattern_params[int((wl.strategy_table >= 2).argmax())].get("text_tokens", 0)) if (wl.strategy_table >= 2).any() else 0, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
+        "config": {"workload": wl.name, "precision": args.precision, "layout": args.layout, "text_tokens_with_dense_borders": int(wl.pattern_params[int((wl.strategy_table >= 2).argmax())].get("text_tokens", 0)) if (wl.strategy_table >= 2).any() else 0, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
