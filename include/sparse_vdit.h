@@ -66,7 +66,7 @@ enum {
   SVD_ERR_PARAMS = 6,        /* negative width, no/duplicate offsets, column out of range or duplicate */
   SVD_ERR_EMPTY_PATTERN = 7, /* some query row would keep no key */
   SVD_ERR_WORKSPACE = 8,     /* workspace missing or too small */
-  SVD_ERR_UNSUPPORTED = 9,   /* block shape the kernels do not implement */
+  SVD_ERR_UNSUPPORTED = 9,   /* block shape the kernels do not implement, or a tensor beyond the size limits */
   SVD_ERR_HIP = 10           /* a HIP call (copy, launch) failed */
 };
 
@@ -77,6 +77,8 @@ typedef struct {
   int32_t B, H, L, D;                     /* D in {64, 128} */
   int64_t stride_b, stride_h, stride_l;   /* in elements; the D axis has stride 1 */
 } svd_tensor_desc;
+/* Size limits (SVD_ERR_UNSUPPORTED beyond them): the rows of one head span less
+ * than 4 GiB (L * stride_l * 2 < 2^32), L < 2^24, and a row stride below 16 MiB. */
 
 /* Parameters of one head (pattern_params is an array of H of these).  Only the
  * fields of the head's mode are read. */

@@ -161,6 +161,8 @@ svd_status validate_desc(const svd_tensor_desc* desc) {
   // the kernels address the rows of one head with 32-bit byte offsets
   if (static_cast<double>(desc->L) * static_cast<double>(desc->stride_l) * 2.0 >= 4294967296.0)
     return SVD_ERR_UNSUPPORTED;
+  // the gather path forms row offsets with a 24-bit multiply: row index and row stride in bytes below 2^24
+  if (desc->L >= (1 << 24) || desc->stride_l * 2 >= (1 << 24)) return SVD_ERR_UNSUPPORTED;
   return SVD_OK;
 }
 

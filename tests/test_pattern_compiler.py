@@ -172,6 +172,10 @@ def test_validation_errors():
     assert mk([0, 0], ok, svd.tensor_desc(1, 2, 0, 64)) == 2               # empty sequence
     assert mk([0, 0], ok, svd.tensor_desc(1, 2, 100, 64, stride_l=68)) == 4   # row alignment
     assert mk([0, 0], ok, svd.tensor_desc(1, 2, 100, 64, stride_l=32)) == 2
+    # size limits: 32-bit byte offsets inside a head, 24-bit row index and row stride
+    assert _status(svd.svd_plan_workspace_bytes, svd.tensor_desc(1, 2, 1 << 22, 64, stride_l=512), [0, 0], ok) == 9
+    assert _status(svd.svd_plan_workspace_bytes, svd.tensor_desc(1, 2, 100, 64, stride_l=1 << 23), [0, 0], ok) == 9
+    assert _status(svd.svd_plan_workspace_bytes, svd.tensor_desc(1, 2, 100, 64, stride_l=(1 << 23) - 8), [0, 0], ok) == 0
     assert _status(svd.svd_plan_workspace_bytes, d, [2, 9], ok) == 5
     assert svd.svd_plan_workspace_bytes(d, [2, 4], ok) > 0
     with pytest.raises(svd.SvdError):
