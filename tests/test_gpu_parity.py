@@ -25,7 +25,8 @@ def test_tiny_all_rows():
 
 @pytest.mark.parametrize("L,D,H,seed,B", [(333, 64, 5, 7, 1), (200, 128, 5, 11, 1), (1000, 64, 5, 3, 1),
                                            (1000, 128, 5, 4, 1), (77, 128, 4, 5, 1), (31, 64, 4, 6, 1),
-                                           (520, 128, 10, 8, 2), (700, 64, 5, 9, 2)])
+                                           (520, 128, 10, 8, 2), (700, 64, 5, 9, 2),
+                                           (1, 64, 5, 12, 1), (2, 128, 5, 13, 2), (16, 64, 5, 14, 1)])
 def test_small_ragged_all_rows(L, D, H, seed, B):
     wl = W.small(L=L, D=D, H=H, seed=seed, B=B)
     q, k, v = _cuda(W.make_qkv(wl))
