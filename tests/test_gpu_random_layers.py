@@ -45,7 +45,7 @@ def random_layer(seed):
     return wl, split
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", list(range(12)) + [23, 45])   # the last two: narrow-band heads with the largest single-element deviations seen
 def test_random_layer(seed):
     wl, split = random_layer(seed)
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
