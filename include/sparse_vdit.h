@@ -161,9 +161,6 @@ svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split);
 /* Inspection of a compiled plan (host copies owned by the plan, valid until
  * svd_plan_destroy).  Groups are ordered by ascending mode id. */
 svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups);
-/* heads: ascending head ids of the group; list_id[t]: which list of the group
- * head heads[t] uses (heads with the same kept region share a list; ids are
- * numbered by first appearance); n_lists is 0 for dense and skip groups. */
 /* Block shape of one group's lists and launches.  block_k is the plan's; block_q
  * is the plan's too, except for a band group (modes 2, 3) of a plan created
  * without an explicit block shape: when its lists cover at least 1 % less area
@@ -176,6 +173,9 @@ svd_status svd_plan_group_blocks(const svd_plan* plan, int32_t group, int32_t* b
  * multi-diagonal group; both report mode 3, svd_plan_group_rearranged tells them
  * apart.) */
 svd_status svd_plan_group_rearranged(const svd_plan* plan, int32_t group, int32_t* rearranged);
+/* heads: ascending head ids of the group; list_id[t]: which list of the group
+ * head heads[t] uses (heads with the same kept region share a list; ids are
+ * numbered by first appearance); n_lists is 0 for dense and skip groups. */
 svd_status svd_plan_group_info(const svd_plan* plan, int32_t group, int32_t* mode, int32_t* n_heads,
                                const int32_t** heads, const int32_t** list_id, int32_t* n_lists);
 /* A list of a band group (modes 2, 3).  row_ptr[n_q_blocks+1] is the CSR
