@@ -27,12 +27,14 @@ FP8_MFMA_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 matrix peak
 # summarised under profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: the
 # factors a 1 GiB streaming kernel in the same runs gives).  Counters cannot be
 # read from inside this process, so the figure is carried here per workload.
-# Dense group of the CogVideoX1.5-like layer = the attention kernel over three
-# key-range chunks plus the merge kernel: (2*325302 + 243360) + (2*68979 + 21631) KiB.
-PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 325302 + 243360 + 2 * 68979 + 21631) * 1024}}
-# FP8 variant, dense group of the HunyuanVideo-like layer = pre-pass + attention kernel:
-# (2*28892 + 28864) + (2*273879 + 91146) KiB.
-PMC_TRAFFIC_BYTES_FP8 = {"hunyuanvideo": {"dense": (2 * 28892 + 28864 + 2 * 273879 + 91146) * 1024}}
+# Dense group of the CogVideoX1.5- and Wan2.1-like layers = the attention kernel
+# over three key-range chunks plus the merge kernel; of the HunyuanVideo-like
+# layer = the attention kernel alone (no split).  KiB: FETCH_SIZE, WRITE_SIZE.
+PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 325297 + 243360 + 2 * 68996 + 21675) * 1024},
+                     "wan2.1": {"dense": (2 * 438455 + 248640 + 2 * 141972 + 81966) * 1024},
+                     "hunyuanvideo": {"dense": (2 * 477092 + 32472) * 1024}}
+# FP8 variant, dense group of the HunyuanVideo-like layer = pre-pass + attention kernel.
+PMC_TRAFFIC_BYTES_FP8 = {"hunyuanvideo": {"dense": (2 * 28893 + 28864 + 2 * 273903 + 91222) * 1024}}
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
