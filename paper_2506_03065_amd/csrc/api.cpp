@@ -242,7 +242,7 @@ const char* svd_status_string(svd_status s) {
     case SVD_ERR_PARAMS: return "bad pattern parameters";
     case SVD_ERR_EMPTY_PATTERN: return "a query row keeps no key";
     case SVD_ERR_WORKSPACE: return "workspace missing or too small";
-    case SVD_ERR_UNSUPPORTED: return "unsupported block shape";
+    case SVD_ERR_UNSUPPORTED: return "unsupported block shape, option combination or tensor size";
     case SVD_ERR_HIP: return "HIP error";
     default: return "unknown status";
   }
@@ -588,25 +588,30 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
   // to the side streams; join: the caller's stream waits for every side stream
   if (hipEventRecord(plan->fork, main_stream) != hipSuccess) return SVD_ERR_HIP;
   bool used[kSideStreams] = {false, false, false};
-  for (int i = 0; i < n; ++i) {
+  svd_status status = SVD_OK;
+  for (int i = 0; i < n && status == SVD_OK; ++i) {
     hipStream_t s = main_stream;
     if (i > 0) {
       const int k_side = (i - 1) % kSideStreams;
       s = plan->side[k_side];
       if (!used[k_side]) {
-        if (hipStreamWaitEvent(s, plan->fork, 0) != hipSuccess) return SVD_ERR_HIP;
+        if (hipStreamWaitEvent(s, plan->fork, 0) != hipSuccess) {
+          status = SVD_ERR_HIP;
+          break;
+        }
         used[k_side] = true;
       }
     }
-    if (svd_status st = launch_group(*plan, *seq[i], q, k, v, out, s)) return st;
+    status = launch_group(*plan, *seq[i], q, k, v, out, s);
   }
+  // joined also after a failed launch, so that whatever was enqueued stays ordered on the caller's stream
   for (int i = 0; i < kSideStreams; ++i) {
     if (!used[i]) continue;
     if (hipEventRecord(plan->join[i], plan->side[i]) != hipSuccess ||
         hipStreamWaitEvent(main_stream, plan->join[i], 0) != hipSuccess)
-      return SVD_ERR_HIP;
+      status = status == SVD_OK ? SVD_ERR_HIP : status;
   }
-  return SVD_OK;
+  return status;
 }
 
 svd_status svd_attn_forward_group(const svd_plan* plan, int32_t group, const void* q, const void* k,

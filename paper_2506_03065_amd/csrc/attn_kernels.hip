@@ -504,6 +504,10 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
     scores(Int<0>{}, s_a);
     tile_max(s_a);
   }
+  // The first stage requests K(2) into the buffer of K(0) at once: every wave must
+  // have read K(0) before any wave gets there (the stages end with a barrier, the
+  // prologue needs its own).
+  __syncthreads();
 
   // One pipeline stage.  On entry s_cur holds the raw scores of tile t; LDS holds
   // K(t+1) in K buffer (t+1)&1 and V(t) in V buffer t&1, while K(t+2) and V(t+1)

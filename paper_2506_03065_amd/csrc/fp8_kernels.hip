@@ -506,6 +506,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       scores(Int<0>{}, s_a);
       tile_max(s_a);
     }
+    __syncthreads();   // K(0) has been read by every wave before the first stage requests K(2) into its buffer
 
     // One pipeline stage (see the bf16 kernel): on entry s_cur holds the raw scores
     // of tile t; LDS holds K(t+1) and V(t); K(t+2) and V(t+1) are requested here.
@@ -589,6 +590,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       scores(Int<0>{}, s_a);
       tile_max(s_a);
     }
+    __syncthreads();   // K(0) has been read by every wave before the first stage requests K(2) into its buffer
 
     // One pipeline stage, three tiles deep.  On entry s_cur holds the raw scores of
     // tile t and pf_prev the probabilities of tile t - 1; LDS holds K(t+1) and

@@ -13,6 +13,17 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+def _difference(rep, out, eager, wl):
+    """Failure message: where a replay differs from the eager result."""
+    diff = out.view(torch.int16) != eager.view(torch.int16)
+    idx = diff.nonzero()[:4000]
+    heads = sorted({(int(i[0]), int(i[1])) for i in idx})
+    rows = sorted({int(i[2]) for i in idx})
+    return (f"replay {rep} differs from the eager result: {int(diff.sum())} elements, "
+            f"{int(torch.isnan(out.float()).sum())} NaN, (batch, head) {heads[:8]} "
+            f"modes {[int(wl.strategy_table[h]) for _, h in heads[:8]]}, rows {rows[:4]}..{rows[-4:]}")
+
+
 @pytest.mark.parametrize("L,D,split", [(1500, 64, 0), (900, 128, 2)])
 def test_captured_forward_replays_to_the_eager_bits(L, D, split):
     wl = W.small(L=L, D=D, H=6, seed=71, B=2)
@@ -42,7 +53,7 @@ def test_captured_forward_replays_to_the_eager_bits(L, D, split):
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), _difference(rep, out, eager, wl)
     del graph
     plan.close()
 
@@ -79,6 +90,6 @@ def test_captured_fp8_forward_replays_to_the_eager_bits():
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), _difference(rep, out, eager, wl)
     del graph
     plan.close()
