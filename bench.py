@@ -33,8 +33,10 @@ FP8_MFMA_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 matrix peak
 PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 325297 + 243360 + 2 * 68996 + 21675) * 1024},
                      "wan2.1": {"dense": (2 * 438455 + 248640 + 2 * 141972 + 81966) * 1024},
                      "hunyuanvideo": {"dense": (2 * 477092 + 32472) * 1024}}
-# FP8 variant, dense group of the HunyuanVideo-like layer = pre-pass + attention kernel.
-PMC_TRAFFIC_BYTES_FP8 = {"hunyuanvideo": {"dense": (2 * 28893 + 28864 + 2 * 273903 + 91222) * 1024}}
+# FP8 variant, dense group = pre-pass + attention kernel (+ merge kernel where the dense heads are split).
+PMC_TRAFFIC_BYTES_FP8 = {"hunyuanvideo": {"dense": (2 * 28893 + 28864 + 2 * 273903 + 91222) * 1024},
+                         "cogvideox1.5": {"dense": (2 * 21628 + 21600 + 2 * 156250 + 137904 + 2 * 68996 + 21612) * 1024},
+                         "wan2.1": {"dense": (2 * 37829 + 37824 + 2 * 363409 + 485389 + 2 * 141849 + 81669) * 1024}}
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
