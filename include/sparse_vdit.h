@@ -222,7 +222,11 @@ svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* com
  * ordered on hip_stream for the caller.  One forward pass per plan may be in
  * flight at a time (calls with the same plan on one stream are fine; concurrent
  * calls on different streams need different plans).  SVD_NO_FORK=1 in the
- * environment at plan creation disables the fork. */
+ * environment at plan creation disables the fork.  Only kernel launches and
+ * event records/waits are enqueued, so the call may be recorded into a stream
+ * capture - except for a plan with a text prefix: while hip_stream is capturing,
+ * such a plan is refused with SVD_ERR_UNSUPPORTED before anything is enqueued
+ * (this holds for every forward entry point that takes a plan). */
 svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
                                     void* out, void* hip_stream);
 

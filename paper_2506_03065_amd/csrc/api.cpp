@@ -558,17 +558,25 @@ static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const vo
 }
 
 static svd_status check_launchable(const svd_plan* plan, const void* q, const void* k, const void* v,
-                                   const void* out) {
+                                   const void* out, hipStream_t stream) {
   if (!plan) return SVD_ERR_NULL;
   if (svd_status st = check_tensors(q, k, v, out)) return st;
   if (!plan->p.device_workspace) return SVD_ERR_WORKSPACE;
   if (!plan->p.launchable) return SVD_ERR_UNSUPPORTED;
+  // A layer with a text prefix is not recorded into a stream capture: a run that
+  // captured and replayed such layers ended in a host-side heap abort whose cause
+  // is not known; until it is, the combination is refused before anything is enqueued.
+  if (plan->p.text_tokens > 0) {
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) return SVD_ERR_HIP;
+    if (capture != hipStreamCaptureStatusNone) return SVD_ERR_UNSUPPORTED;
+  }
   return SVD_OK;
 }
 
 svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const void* k, const void* v,
                                     void* out, void* hip_stream) {
-  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  if (svd_status st = check_launchable(plan, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
   const Plan& p = plan->p;
   hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
   // heaviest first: dense, then the band groups, the gathers, and the zero fill
@@ -616,7 +624,7 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
 
 svd_status svd_attn_forward_group(const svd_plan* plan, int32_t group, const void* q, const void* k,
                                   const void* v, void* out, void* hip_stream) {
-  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  if (svd_status st = check_launchable(plan, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
   const Plan& p = plan->p;
   if (group < 0 || group >= static_cast<int32_t>(p.groups.size())) return SVD_ERR_SHAPE;
   return launch_group(*plan, p.groups[group], q, k, v, out, static_cast<hipStream_t>(hip_stream));
@@ -965,7 +973,7 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
 
 svd_status svd_attn_forward_fp8(const svd_plan* plan, const void* q, const void* k, const void* v, void* out,
                                 void* fp8_workspace, size_t fp8_workspace_bytes, void* hip_stream) {
-  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  if (svd_status st = check_launchable(plan, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
   if (svd_status st = check_fp8_workspace(plan->p.desc, fp8_workspace, fp8_workspace_bytes)) return st;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   // heaviest first, all on the caller's stream
@@ -980,7 +988,7 @@ svd_status svd_attn_forward_fp8(const svd_plan* plan, const void* q, const void*
 svd_status svd_attn_forward_fp8_group(const svd_plan* plan, int32_t group, const void* q, const void* k,
                                       const void* v, void* out, void* fp8_workspace, size_t fp8_workspace_bytes,
                                       void* hip_stream) {
-  if (svd_status st = check_launchable(plan, q, k, v, out)) return st;
+  if (svd_status st = check_launchable(plan, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
   if (svd_status st = check_fp8_workspace(plan->p.desc, fp8_workspace, fp8_workspace_bytes)) return st;
   if (group < 0 || group >= static_cast<int32_t>(plan->p.groups.size())) return SVD_ERR_SHAPE;
   return launch_group_fp8(*plan, plan->p.groups[group], q, k, v, out, fp8_workspace,

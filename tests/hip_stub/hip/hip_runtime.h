@@ -1,0 +1,53 @@
+// Host-only stand-in for <hip/hip_runtime.h>, for the sanitizer build of the
+// library's host code (tests/test_host_launch_model.py).  It declares exactly
+// the runtime calls the host code makes; tests/hip_stub/hip_stub.cpp implements
+// them as a small model of streams, events, stream capture and "device" memory
+// that lives on the host heap, so that AddressSanitizer sees every byte the
+// host code and the launch models touch.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+#if !defined(__clang__)
+typedef uint16_t __bf16;   // storage only: the host code never does arithmetic on it
+#endif
+
+typedef enum hipError_t {
+  hipSuccess = 0,
+  hipErrorInvalidValue = 1,
+  hipErrorInvalidResourceHandle = 400,
+  hipErrorStreamCaptureUnsupported = 900,
+  hipErrorStreamCaptureInvalidated = 901,
+  hipErrorStreamCaptureUnjoined = 904,
+  hipErrorStreamCaptureIsolation = 905,
+  hipErrorUnknown = 999
+} hipError_t;
+
+struct ihipStream_t;
+struct ihipEvent_t;
+typedef ihipStream_t* hipStream_t;
+typedef ihipEvent_t* hipEvent_t;
+
+typedef enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2, hipMemcpyDeviceToDevice = 3 } hipMemcpyKind;
+typedef enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 63 } hipDeviceAttribute_t;
+typedef enum hipStreamCaptureStatus {
+  hipStreamCaptureStatusNone = 0,
+  hipStreamCaptureStatusActive = 1,
+  hipStreamCaptureStatusInvalidated = 2
+} hipStreamCaptureStatus;
+constexpr unsigned hipStreamNonBlocking = 1u;
+constexpr unsigned hipEventDisableTiming = 2u;
+
+hipError_t hipGetDevice(int* device);
+hipError_t hipDeviceGetAttribute(int* value, hipDeviceAttribute_t attr, int device);
+hipError_t hipGetLastError();
+hipError_t hipStreamCreateWithFlags(hipStream_t* stream, unsigned flags);
+hipError_t hipStreamDestroy(hipStream_t stream);
+hipError_t hipStreamSynchronize(hipStream_t stream);
+hipError_t hipStreamIsCapturing(hipStream_t stream, hipStreamCaptureStatus* status);
+hipError_t hipEventCreateWithFlags(hipEvent_t* event, unsigned flags);
+hipError_t hipEventDestroy(hipEvent_t event);
+hipError_t hipEventRecord(hipEvent_t event, hipStream_t stream);
+hipError_t hipStreamWaitEvent(hipStream_t stream, hipEvent_t event, unsigned flags);
+hipError_t hipMemcpyAsync(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t stream);

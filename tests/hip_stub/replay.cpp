@@ -1,0 +1,177 @@
+// Sanitizer harness: drives the library's host code (plan creation, workspace
+// sizing, the bf16 and FP8 launch sequences, fork/join, plan destruction) on a
+// host model of the HIP runtime, eagerly and under a modelled stream capture.
+//
+//   replay LAYERS.txt [SHORTFALL_BYTES]
+//
+// LAYERS.txt, one layer per block:
+//   layer <name> B H L D text_tokens dense_split rounds tensors(0|1) compute_units
+//   table m_0 .. m_{H-1}
+//   head half_width n_offsets o.. n_cols c.. rearr_first rearr_frame_tokens rearr_frames      (H lines)
+// SHORTFALL_BYTES > 0 plants a mistake for the test of the harness itself: the plan
+// workspace is allocated that much smaller than the library is told.
+// Exit status 0 = no model violation (AddressSanitizer aborts on its own).
+#include <cstdio>
+#include <cstdlib>
+#include <fstream>
+#include <iostream>
+#include <string>
+#include <vector>
+
+#include "hip_stub.h"
+#include "sparse_vdit.h"
+
+namespace {
+
+struct Layer {
+  std::string name;
+  int B = 1, H = 1, L = 1, D = 64, text = 0, split = 0, rounds = 1, tensors = 1, cu = 256;
+  std::vector<int32_t> table;
+  std::vector<std::vector<int32_t>> offsets, cols;
+  std::vector<svd_head_params> params;
+};
+
+bool read_layer(std::istream& in, Layer* l) {
+  std::string word;
+  if (!(in >> word)) return false;
+  if (word != "layer") {
+    std::fprintf(stderr, "expected 'layer', got '%s'\n", word.c_str());
+    std::exit(2);
+  }
+  in >> l->name >> l->B >> l->H >> l->L >> l->D >> l->text >> l->split >> l->rounds >> l->tensors >> l->cu;
+  in >> word;   // table
+  l->table.resize(l->H);
+  for (int h = 0; h < l->H; ++h) in >> l->table[h];
+  l->offsets.assign(l->H, {});
+  l->cols.assign(l->H, {});
+  l->params.assign(l->H, svd_head_params{});
+  for (int h = 0; h < l->H; ++h) {
+    int n = 0;
+    in >> word >> l->params[h].half_width >> n;
+    l->offsets[h].resize(n);
+    for (int i = 0; i < n; ++i) in >> l->offsets[h][i];
+    in >> n;
+    l->cols[h].resize(n);
+    for (int i = 0; i < n; ++i) in >> l->cols[h][i];
+    in >> l->params[h].rearr_first >> l->params[h].rearr_frame_tokens >> l->params[h].rearr_frames;
+  }
+  for (int h = 0; h < l->H; ++h) {
+    l->params[h].n_offsets = static_cast<int32_t>(l->offsets[h].size());
+    l->params[h].offsets = l->offsets[h].empty() ? nullptr : l->offsets[h].data();
+    l->params[h].n_cols = static_cast<int32_t>(l->cols[h].size());
+    l->params[h].cols = l->cols[h].empty() ? nullptr : l->cols[h].data();
+  }
+  if (!in) {
+    std::fprintf(stderr, "truncated layer '%s'\n", l->name.c_str());
+    std::exit(2);
+  }
+  return true;
+}
+
+int g_failures = 0;
+size_t g_short = 0;   // bytes by which the plan workspace is allocated too small (the library is told the full size)
+void expect(bool ok, const Layer& l, const char* what, int status = 0) {
+  if (ok) return;
+  std::fprintf(stderr, "layer %s: %s (status %d: %s)\n", l.name.c_str(), what, status,
+               svd_status_string(static_cast<svd_status>(status)));
+  ++g_failures;
+}
+
+void run_layer(const Layer& l) {
+  stub::set_compute_units(l.cu);
+  stub::set_tensor_checks(l.tensors != 0);
+  svd_tensor_desc desc{};
+  desc.B = l.B;
+  desc.H = l.H;
+  desc.L = l.L;
+  desc.D = l.D;
+  desc.stride_l = l.D;
+  desc.stride_h = static_cast<int64_t>(l.L) * l.D;
+  desc.stride_b = desc.stride_h * l.H;
+  const size_t tensor_bytes = l.tensors ? static_cast<size_t>(l.B) * l.H * l.L * l.D * 2 : 256;
+  void* q = stub::device_alloc(tensor_bytes);
+  void* k = stub::device_alloc(tensor_bytes);
+  void* v = stub::device_alloc(tensor_bytes);
+  void* out = stub::device_alloc(tensor_bytes);
+  size_t bytes8 = 0;
+  expect(svd_fp8_workspace_bytes(&desc, &bytes8) == SVD_OK, l, "svd_fp8_workspace_bytes");
+  void* ws8 = stub::device_alloc(l.tensors ? bytes8 : 256);
+  svd_plan_options opt{};
+  opt.dense_split = l.split;
+  opt.text_tokens = l.text;
+  for (int round = 0; round < l.rounds; ++round) {
+    size_t bytes = 0;
+    int st = svd_plan_workspace_bytes(&desc, l.table.data(), l.params.data(), &opt, &bytes);
+    expect(st == SVD_OK, l, "svd_plan_workspace_bytes", st);
+    if (st != SVD_OK) break;
+    void* ws = stub::device_alloc(bytes > g_short ? bytes - g_short : 1);   // g_short > 0: a planted shortfall
+    svd_plan* plan = nullptr;
+    st = svd_plan_create(&plan, &desc, l.table.data(), l.params.data(), &opt, ws, bytes, nullptr);
+    expect(st == SVD_OK, l, "svd_plan_create", st);
+    if (st != SVD_OK) {
+      stub::device_free(ws);
+      break;
+    }
+    for (int fp8 = 0; fp8 < 2; ++fp8) {
+      auto call = [&](hipStream_t s) {
+        return fp8 ? (l.tensors ? svd_attn_forward_fp8(plan, q, k, v, out, ws8, bytes8, s) : SVD_OK)
+                   : svd_attn_forward_planned(plan, q, k, v, out, s);
+      };
+      st = call(nullptr);   // eager, default stream
+      expect(st == SVD_OK, l, fp8 ? "eager fp8 forward" : "eager forward", st);
+      hipStream_t side = stub::create_stream();
+      st = call(side);      // warm-up on the capture stream
+      expect(st == SVD_OK, l, "forward on a caller stream", st);
+      const long nodes_before = stub::captured_nodes();
+      stub::begin_capture(side);
+      st = call(side);
+      if (l.text > 0 && (l.tensors || !fp8)) {
+        // a layer with a text prefix is refused under capture, before anything is enqueued
+        expect(st == SVD_ERR_UNSUPPORTED, l, "forward of a text-prefix layer under capture is refused", st);
+        expect(stub::captured_nodes() == nodes_before, l, "a refused forward records nothing");
+        expect(stub::end_capture(side) == hipSuccess, l, "capture ends");
+      } else {
+        expect(st == SVD_OK, l, "forward under capture", st);
+        expect(stub::end_capture(side) == hipSuccess, l, "capture ends with everything joined");
+        expect(!(l.tensors || !fp8) || stub::captured_nodes() > nodes_before, l, "capture recorded launches");
+      }
+      stub::destroy_stream(side);
+    }
+    // the per-group entry points address the same workspace
+    int32_t n_groups = 0;
+    svd_plan_num_groups(plan, &n_groups);
+    for (int32_t g = 0; g < n_groups; ++g) {
+      st = svd_attn_forward_group(plan, g, q, k, v, out, nullptr);
+      expect(st == SVD_OK, l, "svd_attn_forward_group", st);
+    }
+    expect(svd_plan_destroy(plan) == SVD_OK, l, "svd_plan_destroy");
+    stub::device_free(ws);
+  }
+  for (void* p : {q, k, v, out, ws8}) stub::device_free(p);
+}
+
+}  // namespace
+
+int main(int argc, char** argv) {
+  if (argc != 2 && argc != 3) {
+    std::fprintf(stderr, "usage: replay LAYERS.txt [SHORTFALL_BYTES]\n");
+    return 2;
+  }
+  if (argc == 3) g_short = static_cast<size_t>(std::atol(argv[2]));
+  std::ifstream in(argv[1]);
+  if (!in) {
+    std::fprintf(stderr, "cannot read %s\n", argv[1]);
+    return 2;
+  }
+  Layer l;
+  int n = 0;
+  while (read_layer(in, &l)) {
+    run_layer(l);
+    ++n;
+    std::printf("layer %s: %ld launches so far, %ld captured, %d violations, %d failures\n", l.name.c_str(),
+                stub::launches(), stub::captured_nodes(), stub::violations(), g_failures);
+    std::fflush(stdout);
+  }
+  std::printf("%d layers replayed\n", n);
+  return (stub::violations() || g_failures) ? 1 : 0;
+}

@@ -93,3 +93,36 @@ def test_captured_fp8_forward_replays_to_the_eager_bits():
         assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), _difference(rep, out, eager, wl)
     del graph
     plan.close()
+
+
+@pytest.mark.skip(reason="capture of a layer with a text prefix is switched off in the library (it returns "
+                         "SVD_ERR_UNSUPPORTED before enqueuing anything): a capture-and-replay run over random "
+                         "layers ended in a host-side heap abort at its first layer with a split text-row launch "
+                         "(L 998, D 128, 256 text tokens, five-way dense split); the library's host code replays "
+                         "that sequence cleanly under AddressSanitizer on a model of the runtime "
+                         "(tests/test_host_launch_model.py), so the cause is not known and the case stays off the GPU")
+def test_captured_text_prefix_forward_replays_to_the_eager_bits():
+    from test_gpu_random_layers import random_layer
+    wl, split = random_layer(2)     # L 998, D 128, text 256, dense_split 5
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, dense_split=split),
+                     dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, dense_split=split)
+    eager = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_planned(plan, q, k, v, eager)
+    torch.cuda.synchronize()
+    out = torch.full_like(q, float("nan"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        svd.svd_attn_forward_planned(plan, q, k, v, out)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), _difference(rep, out, eager, wl)
+    del graph
+    plan.close()
