@@ -5,8 +5,16 @@ A step is one forward pass of the whole layer: the fused launch of every mode
 group of the per-head strategy table plus the zero fill of skipped heads, on
 Q/K/V already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cogvideox1.5|hunyuanvideo|hunyuanvideo+text|wan2.1|stack|search|rearranged]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--workload all|cogvideox1.5|hunyuanvideo|hunyuanvideo+text|wan2.1|stack|search|rearranged]
                     [--precision bf16|fp8]
+
+The default, --workload all, times the HunyuanVideo-shaped layer (the largest
+single-GPU configuration) as the headline and, in the same run, the
+CogVideoX1.5- and Wan2.1-shaped layers and the 40-layer stack as sub-records
+under "other_workloads", each with its own roofline, CPU-oracle leg and check
+against the oracle; a calibration leg measures what the chip sustains on a loop
+of bf16 matrix instructions and on a streaming copy.
 
 --precision fp8 times the FP8 (E4M3) variant of the same layer: a step then also
 contains the quantisation pre-pass of K and V (the inputs stay bf16).
@@ -23,20 +31,38 @@ if ROOT not in sys.path:
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 FP8_MFMA_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 matrix peak
-# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc passes
-# summarised under profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: the
-# factors a 1 GiB streaming kernel in the same runs gives).  Counters cannot be
-# read from inside this process, so the figure is carried here per workload.
-# Dense group of the CogVideoX1.5- and Wan2.1-like layers = the attention kernel
-# over three key-range chunks plus the merge kernel; of the HunyuanVideo-like
-# layer = the attention kernel alone (no split).  KiB: FETCH_SIZE, WRITE_SIZE.
-PMC_TRAFFIC_BYTES = {"cogvideox1.5": {"dense": (2 * 325297 + 243360 + 2 * 68996 + 21675) * 1024},
-                     "wan2.1": {"dense": (2 * 438455 + 248640 + 2 * 141972 + 81966) * 1024},
-                     "hunyuanvideo": {"dense": (2 * 477092 + 32472) * 1024}}
-# FP8 variant, dense group = pre-pass + attention kernel (+ merge kernel where the dense heads are split).
-PMC_TRAFFIC_BYTES_FP8 = {"hunyuanvideo": {"dense": (2 * 28893 + 28864 + 2 * 273903 + 91222) * 1024},
-                         "cogvideox1.5": {"dense": (2 * 21628 + 21600 + 2 * 156250 + 137904 + 2 * 68996 + 21612) * 1024},
-                         "wan2.1": {"dense": (2 * 37829 + 37824 + 2 * 363409 + 485389 + 2 * 141849 + 81669) * 1024}}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SOURCES = ("attn_kernels.hip", "attn_kernels.h", "fp8_kernels.hip", "api.cpp")
+
+
+def kernel_source_stamp():
+    """Short hash of the kernel and launch sources: a traffic record is only valid for the sources it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2506_03065_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(precision, workload, group):
+    """HBM bytes per launch of a group's kernels from profiles/traffic.json (written by
+    `python -m paper_2506_03065_amd.traffic_record` from two rocprofv3 --pmc runs, FETCH_SIZE and
+    WRITE_SIZE, scaled by what the same counters read for the library's copy probe).  Counters cannot be
+    read from inside this process.  None when there is no record or it was taken on other kernel sources."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None, "no record"
+    entry = rec.get("records", {}).get(precision, {}).get(workload, {}).get(group)
+    if entry is None:
+        return None, "no record"
+    if entry.get("kernel_source_stamp") != kernel_source_stamp():
+        return None, "record is stale (kernel sources changed since the counter run)"
+    return entry.get("bytes"), entry.get("source")
+
+
 MODE_NAMES = {0: "dense", 1: "skip", 2: "diagonal", 3: "multi-diagonal", 4: "vertical-stripe"}
 
 
@@ -94,7 +120,7 @@ def cpu_baseline(wl, q, k, v, out, budget_s, torch, np, fp8=False):
                       f"already widened; scaled by L/rows and H/heads"}, max_err, sum_err / max(n_err, 1)
 
 
-def run_stack(args, torch, np, svd, W):
+def run_stack(args, torch, np, svd, W, cpu_seconds=None, calib=None, dense_reps=1):
     """The 40-layer stack at the Wan2.1-like shape: one plan per layer, built once;
     a step is one forward pass of all 40 attention layers (the same Q/K/V serve
     every layer: kernel time does not depend on the values)."""
@@ -130,9 +156,9 @@ def run_stack(args, torch, np, svd, W):
         torch.cuda.synchronize()
     steps, warmup = max(1, min(args.steps, 3)), max(1, min(args.warmup, 1))
     ms_per_step = gpu_time_ms(step, steps, warmup, torch)
-    per_layer = [gpu_time_ms(lambda p=p: layer_fwd(p), 2, 1, torch) for p in plans]
+    per_layer = [gpu_time_ms(lambda p=p: layer_fwd(p), 1, 0, torch) for p in plans]
     dense_out = torch.empty_like(q)
-    dense_ms = gpu_time_ms(lambda: svd.svd_dense_attn_forward(q, k, v, dense_out), max(1, args.dense_reps), 1, torch)
+    dense_ms = gpu_time_ms(lambda: svd.svd_dense_attn_forward(q, k, v, dense_out), max(1, dense_reps), 1, torch)
     del dense_out
     work = [p.work() for p in plans]
     computed = sum(w["computed_flops"] for w in work)
@@ -147,13 +173,15 @@ def run_stack(args, torch, np, svd, W):
         peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
         roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[dense group of layer 0]",
                     "achieved": round(tf0, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf0 / peak, 4), "traffic": None}
+        add_measured_peak(roofline, calib, fp8)
     dense_flops = wl0.dense_flops * n_layers
-    cpu = None
-    if args.cpu_seconds > 0:
+    cpu, max_err, mean_err = None, None, None
+    cpu_seconds = args.cpu_seconds if cpu_seconds is None else cpu_seconds
+    if cpu_seconds > 0:
         mid = layers[n_layers // 2]
         layer_fwd(plans[n_layers // 2])
         torch.cuda.synchronize()
-        cpu, max_err, mean_err = cpu_baseline(mid, q, k, v, out, args.cpu_seconds, torch, np, fp8=fp8)
+        cpu, max_err, mean_err = cpu_baseline(mid, q, k, v, out, cpu_seconds, torch, np, fp8=fp8)
         cpu["value"] *= n_layers
         cpu["sample"] += f"; layer {n_layers // 2} of the stack, times {n_layers} layers"
     dense_heads = [int((wl.strategy_table == 0).sum()) for wl in layers]
@@ -173,8 +201,11 @@ def run_stack(args, torch, np, svd, W):
         "plan_create_ms": round(plan_ms, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "check_vs_oracle": {"max_abs_err": max_err, "mean_abs_err": mean_err, "layer": n_layers // 2},
     }
-    print(json.dumps(result))
+    for plan in plans:
+        plan.close()
+    return result
 
 
 def run_search(args, torch, np, svd, W):
@@ -304,58 +335,47 @@ def run_rearranged(args, torch, np, svd, W):
     fused.close()
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cogvideox1.5")
-    ap.add_argument("--precision", default="bf16", choices=["bf16", "fp8"],
-                    help="bf16 (the headline metric) or the FP8 E4M3 variant of the same layer")
-    ap.add_argument("--layout", default="bhld", choices=["bhld", "blhd"],
-                    help="storage order of q, k, v, out: head-major [B,H,L,D] (default) or the model's token-major "
-                         "[B,L,H,D] (Eq. 1's head concatenation then needs no copy); the kernels take either through strides")
-    ap.add_argument("--batch", type=int, default=None, help="batch size B (default: the workload's, 1); 2 = a CFG pair")
-    ap.add_argument("--dense-reps", type=int, default=2, help="timed passes of the all-heads dense baseline (0 = skip)")
-    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="budget of the CPU-oracle leg (0 = skip)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain streaming kernel (1 GiB read, 1 GiB written) so that a rocprofv3 "
-                         "--pmc run of this command holds a dispatch of known HBM traffic")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
 
-    import numpy as np
-    import torch
-    from paper_2506_03065_amd import binding as svd
-    from paper_2506_03065_amd import workloads as W
+def add_measured_peak(roofline, calib, fp8):
+    """frac_of_measured_peak beside frac: the same rate against what a loop of nothing but bf16 matrix
+    instructions sustained in this run (the FP8 kernels are not put against a bf16 loop)."""
+    if roofline is None or not calib or fp8 or roofline.get("unit") != "TFLOP/s":
+        return
+    roofline["measured_peak"] = calib["measured_mfma_peak_tflops"]
+    roofline["frac_of_measured_peak"] = round(roofline["achieved"] / calib["measured_mfma_peak_tflops"], 4)
 
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    svd.lib()   # fails loudly if the HIP library is not built
+
+def calibrate(torch, svd):
+    """Measured ceilings: the matrix-instruction loop (two work-groups of eight waves per compute unit and
+    round, about 60 ms) and the library's streaming copy of 1 GiB, HIP events on the launch stream."""
     dev = "cuda:0"
-    torch.cuda.set_device(0)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    wgs, iters = 2 * n_cu, 20000
+    scratch = torch.empty(wgs * 512, dtype=torch.float32, device=dev)
+    flops = svd.svd_probe_mfma(scratch, iters, wgs)
+    t_warm = time.perf_counter()
+    while time.perf_counter() - t_warm < 1.0:      # the sustained rate, not the first launch's boost clock
+        svd.svd_probe_mfma(scratch, iters, wgs)
+        torch.cuda.synchronize()
+    ms = gpu_time_ms(lambda: svd.svd_probe_mfma(scratch, iters, wgs), 5, 1, torch)
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    ms_copy = gpu_time_ms(lambda: svd.svd_probe_copy(src, dst), 5, 2, torch)
+    nbytes = 2.0 * src.numel() * 4
+    del src, dst, scratch
+    torch.cuda.empty_cache()
+    return {"measured_mfma_peak_tflops": round(flops / 1e9 / ms, 1),
+            "mfma_probe": f"v_mfma_f32_32x32x16_bf16 loop, {wgs} work-groups x 512 threads, {iters} x 8 per wave, {ms:.2f} ms",
+            "measured_hbm_gbs": round(nbytes / 1e6 / ms_copy, 1),
+            "copy_probe": f"1 GiB read + 1 GiB written, {ms_copy:.3f} ms",
+            "compute_units": n_cu}
+
+
+def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None):
+    """One layer workload: the timed steps, the per-group launches, the dense baseline, the CPU-oracle leg."""
+    dev = "cuda:0"
     fp8 = args.precision == "fp8"
-    if fp8 and args.workload in ("search", "rearranged"):
-        print("--precision fp8: this workload is built in bf16 only", file=sys.stderr)
-        sys.exit(2)
-    if args.workload == "stack":
-        run_stack(args, torch, np, svd, W)
-        return
-    if args.workload == "search":
-        run_search(args, torch, np, svd, W)
-        return
-    if args.workload == "rearranged":
-        run_rearranged(args, torch, np, svd, W)
-        return
-    wl = W.BY_NAME[args.workload]()
-    if args.batch is not None:
-        if args.batch < 1:
-            print("--batch must be at least 1", file=sys.stderr)
-            sys.exit(2)
-        wl.B = args.batch
+    from paper_2506_03065_amd import workloads as W
     t0 = time.perf_counter()
     q, k, v = (t.to(dev) for t in W.make_qkv(wl))
     if args.layout == "blhd":      # token-major storage, seen through a [B,H,L,D] view
@@ -377,7 +397,7 @@ def main():
     if fp8:
         ws8 = torch.empty(svd.svd_fp8_workspace_bytes(desc), dtype=torch.uint8, device=dev)
         step = lambda: svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
-    t_warm = time.perf_counter()          # bring the clocks up before the W warm-up steps
+    t_warm = time.perf_counter()          # bring the clocks to their sustained level before the W warm-up steps
     while time.perf_counter() - t_warm < 1.5:
         step()
         torch.cuda.synchronize()
@@ -408,16 +428,18 @@ def main():
     compute_groups = [g for g in groups if g["mode"] != "skip"]
     dom = max(compute_groups, key=lambda g: g["ms"])
     peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
+    traffic, traffic_source = recorded_traffic(args.precision, wl.name, dom["mode"])
     roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[{dom['mode']} group]",
                 "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(dom["tflops"] / peak, 4),
-                "traffic": (PMC_TRAFFIC_BYTES_FP8 if fp8 else PMC_TRAFFIC_BYTES).get(wl.name, {}).get(dom["mode"])}
+                "traffic": traffic, "traffic_source": traffic_source}
+    add_measured_peak(roofline, calib, fp8)
     bf16_ms = gpu_time_ms(step16, max(3, args.steps // 2), 1, torch) if fp8 else None
 
     # ---- in-house dense kernel on all heads: the speed-up baseline ----
     dense_ms = None
-    if args.dense_reps > 0:
+    if dense_reps > 0:
         dense_out = torch.empty_like(q)
-        dense_ms = gpu_time_ms(lambda: svd.svd_dense_attn_forward(q, k, v, dense_out), args.dense_reps, 1, torch)
+        dense_ms = gpu_time_ms(lambda: svd.svd_dense_attn_forward(q, k, v, dense_out), dense_reps, 1 if dense_reps > 1 else 0, torch)
         del dense_out
     step()
     torch.cuda.synchronize()
@@ -426,16 +448,17 @@ def main():
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        torch.mul(src, 2.0, out=dst)      # vectorized elementwise kernel: reads 2^30 B, writes 2^30 B
+        svd.svd_probe_copy(src, dst)      # the library's streaming copy: reads 2^30 B, writes 2^30 B
         torch.cuda.synchronize()
         del src, dst
 
     cpu, max_err, mean_err = (None, None, None)
-    if args.cpu_seconds > 0:
-        cpu, max_err, mean_err = cpu_baseline(wl, q, k, v, out, args.cpu_seconds, torch, np, fp8=fp8)
+    if cpu_seconds > 0:
+        cpu, max_err, mean_err = cpu_baseline(wl, q, k, v, out, cpu_seconds, torch, np, fp8=fp8)
 
     dense_flops = wl.dense_flops
     computed_tflops = work["computed_flops"] / 1e9 / ms_per_step
+    text = int(wl.pattern_params[int((wl.strategy_table >= 2).argmax())].get("text_tokens", 0)) if (wl.strategy_table >= 2).any() else 0
     result = {
         "metric": "sparse-attn layer latency" + (" (FP8 variant, pre-pass included)" if fp8 else ""),
         "value": round(ms_per_step, 4),
@@ -449,7 +472,8 @@ def main():
         "vs_baseline": None,
         "dtype": "fp8-e4m3 (fp32 accumulation)" if fp8 else "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "precision": args.precision, "layout": args.layout, "text_tokens_with_dense_borders": int(wl.pattern_params[int((wl.strategy_table >= 2).argmax())].get("text_tokens", 0)) if (wl.strategy_table >= 2).any() else 0, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
+        "config": {"workload": wl.name, "precision": args.precision, "layout": args.layout,
+                   "text_tokens_with_dense_borders": text, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
@@ -457,6 +481,7 @@ def main():
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),
         "computed_tile_tflops": round(computed_tflops, 1),
         "computed_tile_frac_of_bf16_peak": round(computed_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+        "computed_tile_frac_of_measured_mfma_peak": round(computed_tflops / calib["measured_mfma_peak_tflops"], 4) if calib and not fp8 else None,
         "computed_tile_frac_of_fp8_peak": round(computed_tflops / FP8_MFMA_PEAK_TFLOPS, 4) if fp8 else None,
         "bf16_same_plan_ms": round(bf16_ms, 4) if bf16_ms else None,
         "speedup_vs_bf16_sparse": round(bf16_ms / ms_per_step, 3) if bf16_ms else None,
@@ -473,9 +498,103 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "check_vs_oracle": {"max_abs_err": max_err, "mean_abs_err": mean_err},
-        "paper_context": "end-to-end speedups 1.76x/1.85x (A800) and 1.58x (H800) in the paper's Table 2; "
-                         "no kernel-level numbers are published",
     }
+    plan.close()
+    del q, k, v, out, ws
+    torch.cuda.empty_cache()
+    return result
+
+
+def brief(rec):
+    """The sub-record of a workload that is not the headline."""
+    keys = ("config", "ms_per_step", "steps", "computed_tile_tflops", "computed_tile_frac_of_bf16_peak",
+            "computed_tile_frac_of_measured_mfma_peak", "dense_all_heads_ms", "speedup_vs_dense_kernel",
+            "flop_reduction_block_level", "flop_reduction_element_level", "groups", "roofline", "cpu_baseline",
+            "check_vs_oracle", "plan_create_ms")
+    out = {"ms": rec["ms_per_step"]}
+    out.update({k: rec[k] for k in keys if k in rec})
+    return out
+
+
+PAPER_CONTEXT = ("end-to-end speedups 1.76x/1.85x (A800) and 1.58x (H800) in the paper's Table 2; "
+                 "no kernel-level numbers are published")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="all",
+                    help="all (default): the HunyuanVideo-shaped layer as the headline plus the CogVideoX1.5- and "
+                         "Wan2.1-shaped layers and the 40-layer stack as sub-records; or one workload by name")
+    ap.add_argument("--precision", default="bf16", choices=["bf16", "fp8"],
+                    help="bf16 (the headline metric) or the FP8 E4M3 variant of the same layer")
+    ap.add_argument("--layout", default="bhld", choices=["bhld", "blhd"],
+                    help="storage order of q, k, v, out: head-major [B,H,L,D] (default) or the model's token-major "
+                         "[B,L,H,D] (Eq. 1's head concatenation then needs no copy); the kernels take either through strides")
+    ap.add_argument("--batch", type=int, default=None, help="batch size B (default: the workload's, 1); 2 = a CFG pair")
+    ap.add_argument("--dense-reps", type=int, default=None,
+                    help="timed passes of the all-heads dense baseline (0 = skip; default 2, 1 per layer with --workload all)")
+    ap.add_argument("--cpu-seconds", type=float, default=None,
+                    help="budget of the CPU-oracle leg (0 = skip; default 25, with --workload all 20 for the headline "
+                         "and 8 for each other workload)")
+    ap.add_argument("--no-calibrate", action="store_true",
+                    help="skip the calibration leg (matrix-instruction loop and streaming copy)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run the library's streaming copy once (1 GiB read, 1 GiB written) so that a rocprofv3 "
+                         "--pmc run of this command holds a dispatch of known HBM traffic")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_03065_amd import binding as svd
+    from paper_2506_03065_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    svd.lib()   # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    fp8 = args.precision == "fp8"
+    if fp8 and args.workload in ("search", "rearranged"):
+        print("--precision fp8: this workload is built in bf16 only", file=sys.stderr)
+        sys.exit(2)
+    if args.batch is not None and args.batch < 1:
+        print("--batch must be at least 1", file=sys.stderr)
+        sys.exit(2)
+    everything = args.workload == "all"
+    if args.workload == "search":
+        run_search(args, torch, np, svd, W)
+        return
+    if args.workload == "rearranged":
+        run_rearranged(args, torch, np, svd, W)
+        return
+    calib = None if args.no_calibrate else calibrate(torch, svd)
+    cpu_head = args.cpu_seconds if args.cpu_seconds is not None else (20.0 if everything else 25.0)
+    cpu_other = args.cpu_seconds if args.cpu_seconds is not None else 8.0
+    dense_reps = args.dense_reps if args.dense_reps is not None else (1 if everything else 2)
+    if args.workload == "stack":
+        result = run_stack(args, torch, np, svd, W, cpu_head, calib, dense_reps)
+    else:
+        wl = W.BY_NAME["hunyuanvideo" if everything else args.workload]()
+        if args.batch is not None:
+            wl.B = args.batch
+        result = measure_layer(wl, args, torch, np, svd, cpu_head, dense_reps, calib)
+    if everything:
+        others = {}
+        for name in ("cogvideox1.5", "wan2.1"):
+            wl = W.BY_NAME[name]()
+            if args.batch is not None:
+                wl.B = args.batch
+            others[name] = brief(measure_layer(wl, args, torch, np, svd, cpu_other, dense_reps, calib))
+        others["stack"] = brief(run_stack(args, torch, np, svd, W, cpu_other, calib, dense_reps))
+        result["other_workloads"] = others
+    result["calibration"] = calib
+    result["paper_context"] = PAPER_CONTEXT
     print(json.dumps(result))
 
 

@@ -352,6 +352,20 @@ svd_status svd_attn_forward_fp8_group(const svd_plan* plan, int32_t group, const
                                       const void* v, void* out, void* fp8_workspace, size_t fp8_workspace_bytes,
                                       void* hip_stream);
 
+/* ---- Calibration probes for the benchmark's roofline (no part of the method) ----
+ * The published matrix peak assumes the peak clock; under load the power limit
+ * grants less.  svd_probe_mfma runs a loop of nothing but the bf16 matrix
+ * instruction of the attention kernels' two products (v_mfma_f32_32x32x16_bf16,
+ * eight independent accumulators per wave, work_groups of 512 threads, two waves
+ * per SIMD) and returns the FLOPs of the launch through *flops (HOST); timing is
+ * the caller's.  device_scratch: DEVICE, work_groups * 512 floats at least.
+ * svd_probe_copy copies bytes (a multiple of 16) from src to dst (DEVICE, 16-byte
+ * aligned, not overlapping) with one plain streaming kernel: bytes read and bytes
+ * written of known size, for the HBM ceiling and for scaling hardware counters. */
+svd_status svd_probe_mfma(void* device_scratch, size_t scratch_bytes, int32_t iters, int32_t work_groups,
+                          double* flops, void* hip_stream);
+svd_status svd_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* svd_status_string(svd_status status);
 

@@ -28,7 +28,7 @@ EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", 
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
            "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
-           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8", "svd_attn_forward_fp8_group", "svd_rearrange_tokens"]
+           "svd_fp8_workspace_bytes", "svd_attn_forward_fp8", "svd_attn_forward_fp8_group", "svd_rearrange_tokens", "svd_probe_mfma", "svd_probe_copy"]
 
 
 class SvdError(RuntimeError):
@@ -96,6 +96,8 @@ def lib():
             "svd_search_layer": [vp, vp, vp, descp, C.POINTER(hpp), C.c_double, C.c_double, i32p,
                                  C.POINTER(C.c_double), vp, vp, C.c_size_t, vp],
             "svd_rearrange_tokens": [vp, vp, descp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp],
+            "svd_probe_mfma": [vp, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp],
+            "svd_probe_copy": [vp, vp, C.c_size_t, vp],
             "svd_fp8_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
             "svd_attn_forward_fp8": [vp, vp, vp, vp, vp, vp, C.c_size_t, vp],
             "svd_attn_forward_fp8_group": [vp, C.c_int32, vp, vp, vp, vp, vp, C.c_size_t, vp],
@@ -366,6 +368,22 @@ def svd_dense_attn_forward(q, k, v, out, stream=None):
     _check(lib().svd_dense_attn_forward(_dev(q), _dev(k), _dev(v), _dev(out), C.byref(desc), _stream_ptr(stream)),
            "svd_dense_attn_forward")
     return out
+
+
+# ---- calibration probes of the benchmark ----
+
+def svd_probe_mfma(scratch, iters, work_groups, stream=None) -> float:
+    """Launches the matrix-instruction loop; returns the FLOPs of the launch.  scratch: CUDA float32, work_groups * 512 elements."""
+    flops = C.c_double()
+    _check(lib().svd_probe_mfma(_dev(scratch), scratch.numel() * scratch.element_size(), int(iters), int(work_groups),
+                                C.byref(flops), _stream_ptr(stream)), "svd_probe_mfma")
+    return flops.value
+
+
+def svd_probe_copy(src, dst, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib().svd_probe_copy(_dev(src), _dev(dst), nbytes, _stream_ptr(stream)), "svd_probe_copy")
+    return dst
 
 
 # ---- offline search step (Section 4.2, Eq. 2-3, Algorithm 1) ----

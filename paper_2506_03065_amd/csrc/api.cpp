@@ -15,6 +15,7 @@
 #include "attn_kernels.h"
 #include "fp8_kernels.h"
 #include "plan.h"
+#include "probe_kernels.h"
 #include "rearrange_kernels.h"
 #include "search_kernels.h"
 #include "sparse_vdit.h"
@@ -897,6 +898,29 @@ svd_status svd_rearrange_tokens(const void* src, void* dst, const svd_tensor_des
                                    static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return SVD_ERR_HIP;
   return SVD_OK;
+}
+
+// ---- calibration probes of the benchmark ----
+
+svd_status svd_probe_mfma(void* device_scratch, size_t scratch_bytes, int32_t iters, int32_t work_groups,
+                          double* flops, void* hip_stream) {
+  if (!device_scratch || !flops) return SVD_ERR_NULL;
+  if (iters < 1 || work_groups < 1) return SVD_ERR_SHAPE;
+  if (scratch_bytes < static_cast<size_t>(work_groups) * 512 * sizeof(float) ||
+      (reinterpret_cast<uintptr_t>(device_scratch) & 3u))
+    return SVD_ERR_WORKSPACE;
+  return svd::launch_mfma_probe(static_cast<float*>(device_scratch), scratch_bytes / sizeof(float), iters, work_groups,
+                                flops, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? SVD_OK
+             : SVD_ERR_HIP;
+}
+
+svd_status svd_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst) return SVD_ERR_NULL;
+  if (bytes == 0 || bytes % 16) return SVD_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(dst)) return SVD_ERR_ALIGN;
+  return svd::launch_copy_probe(src, dst, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SVD_OK
+                                                                                                     : SVD_ERR_HIP;
 }
 
 // ---- FP8 variant (Appendix B) ----

@@ -13,6 +13,7 @@
 #include "attn_kernels.h"
 #include "fp8_kernels.h"
 #include "hip_stub.h"
+#include "probe_kernels.h"
 #include "rearrange_kernels.h"
 #include "search_kernels.h"
 
@@ -318,6 +319,21 @@ hipError_t launch_select_heads(const __bf16* const*, const TensorView& sv, const
                                hipStream_t stream) {
   if (sv.H > kMaxSelectHeads) return hipErrorInvalidValue;
   stub::note_launch(stream, "select_heads_kernel");
+  return hipSuccess;
+}
+
+hipError_t launch_mfma_probe(float* out, size_t out_floats, int iters, int work_groups, double* flops, hipStream_t stream) {
+  if (!out || iters < 1 || work_groups < 1 || out_floats < (size_t)work_groups * 512) return hipErrorInvalidValue;
+  stub::note_launch(stream, "mfma_probe_kernel");
+  touch_write(out, (size_t)work_groups * 512 * sizeof(float), "probe output", 0x77);
+  if (flops) *flops = 2.0 * 32 * 32 * 16 * 8 * (double)iters * 8.0 * work_groups;
+  return hipSuccess;
+}
+
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream) {
+  stub::note_launch(stream, "copy_probe_kernel");
+  touch_read(src, bytes, "copy source");
+  touch_write(dst, bytes, "copy destination", 0x78);
   return hipSuccess;
 }
 
