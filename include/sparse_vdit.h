@@ -67,7 +67,8 @@ enum {
   SVD_ERR_EMPTY_PATTERN = 7, /* some query row would keep no key */
   SVD_ERR_WORKSPACE = 8,     /* workspace missing or too small */
   SVD_ERR_UNSUPPORTED = 9,   /* block shape the kernels do not implement, or a tensor beyond the size limits */
-  SVD_ERR_HIP = 10           /* a HIP call (copy, launch) failed */
+  SVD_ERR_HIP = 10,          /* a HIP call (copy, launch) failed */
+  SVD_ERR_STATIC_LIMIT = 11  /* sparse_vdit_attn_forward_static: the layer does not fit the library's static buffer */
 };
 
 /* Mode ids = M_0..M_4 of Section 4.2, sparse modes in the order of Section 4.1.2. */
@@ -244,6 +245,29 @@ svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
                                     const svd_head_params* pattern_params, void* out,
                                     const svd_tensor_desc* desc, void* device_workspace,
                                     size_t workspace_bytes, void* hip_stream);
+
+/* The one-shot form for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP stream capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same result as sparse_vdit_attn_forward, but the
+ * compiled lists and the partial results of split dense heads live in a buffer of
+ * SVD_STATIC_SCRATCH_BYTES (64 MiB) that is part of the library's device image:
+ * every GPU the library runs on holds its own copy until the process ends.  The
+ * call allocates no device memory and creates no streams or events; the groups of
+ * the layer run one after the other on hip_stream.  A layer whose split dense
+ * heads do not fit the buffer runs them unsplit; a layer whose lists alone do not
+ * fit is refused with SVD_ERR_STATIC_LIMIT (nothing is enqueued).  The plan of the
+ * previous call on the device is reused when table, parameters and descriptor are
+ * identical; otherwise the new lists are copied into the buffer on hip_stream and
+ * the call waits for that copy - which a capturing stream cannot record
+ * (SVD_ERR_UNSUPPORTED), so the first call for a layer belongs before the capture.
+ * All calls on one GPU share the buffer, and it keeps what the last call left in
+ * it (nothing in it needs to start at zero): calls that overlap in time on one
+ * GPU race, whatever their streams.  No text prefix (the call takes no options). */
+#define SVD_STATIC_SCRATCH_BYTES (64u << 20)
+svd_status sparse_vdit_attn_forward_static(const void* q, const void* k, const void* v,
+                                           const int32_t* strategy_table,
+                                           const svd_head_params* pattern_params, void* out,
+                                           const svd_tensor_desc* desc, void* hip_stream);
 
 /* Eq. 1 for all H heads with the same kernel family: the dense baseline the
  * sparse layer's speed-up is measured against.  Needs no workspace. */

@@ -19,12 +19,12 @@ LIB_PATH = os.path.join(_HERE, "libsparse_vdit.so")
 SVD_OK = 0
 STATUS_NAMES = {0: "SVD_OK", 1: "SVD_ERR_NULL", 2: "SVD_ERR_SHAPE", 3: "SVD_ERR_DTYPE", 4: "SVD_ERR_ALIGN",
                 5: "SVD_ERR_MODE", 6: "SVD_ERR_PARAMS", 7: "SVD_ERR_EMPTY_PATTERN", 8: "SVD_ERR_WORKSPACE",
-                9: "SVD_ERR_UNSUPPORTED", 10: "SVD_ERR_HIP"}
+                9: "SVD_ERR_UNSUPPORTED", 10: "SVD_ERR_HIP", 11: "SVD_ERR_STATIC_LIMIT"}
 SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
            "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_group_blocks", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
-           "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward",
+           "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward", "sparse_vdit_attn_forward_static",
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
            "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
@@ -85,6 +85,7 @@ def lib():
             "svd_attn_forward_planned": [vp, vp, vp, vp, vp, vp],
             "svd_attn_forward_group": [vp, C.c_int32, vp, vp, vp, vp, vp],
             "sparse_vdit_attn_forward": [vp, vp, vp, i32p, hpp, vp, descp, vp, C.c_size_t, vp],
+            "sparse_vdit_attn_forward_static": [vp, vp, vp, i32p, hpp, vp, descp, vp],
             "svd_dense_attn_forward": [vp, vp, vp, vp, descp, vp],
             "svd_head_mse_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
             "svd_head_mse": [vp, vp, descp, vp, vp, C.c_size_t, vp],
@@ -360,6 +361,15 @@ def sparse_vdit_attn_forward(q, k, v, strategy_table, pattern_params, out, works
                                           C.byref(desc), _dev(workspace),
                                           workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
            "sparse_vdit_attn_forward")
+    return out
+
+
+def sparse_vdit_attn_forward_static(q, k, v, strategy_table, pattern_params, out, stream=None):
+    desc = desc_of(q)
+    m = _Marshalled(strategy_table, pattern_params)
+    _check(lib().sparse_vdit_attn_forward_static(_dev(q), _dev(k), _dev(v), _ptr(m.table), m.params, _dev(out),
+                                                 C.byref(desc), _stream_ptr(stream)),
+           "sparse_vdit_attn_forward_static")
     return out
 
 

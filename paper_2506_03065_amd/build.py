@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libsparse_vdit.so")
-SOURCES = ["attn_kernels.hip", "fp8_kernels.hip", "search_kernels.hip", "rearrange_kernels.hip", "probe_kernels.hip", "api.cpp", "pattern_compiler.cpp"]
+SOURCES = ["attn_kernels.hip", "fp8_kernels.hip", "search_kernels.hip", "rearrange_kernels.hip", "static_scratch.hip", "probe_kernels.hip", "api.cpp", "pattern_compiler.cpp"]
 
 
 def hipcc_path() -> str:

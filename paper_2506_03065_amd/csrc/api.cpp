@@ -19,6 +19,7 @@
 #include "rearrange_kernels.h"
 #include "search_kernels.h"
 #include "sparse_vdit.h"
+#include "static_scratch.h"
 
 // A launchable plan owns a few side streams and events.  The groups of a layer
 // are independent (they write different heads); when the last, partial round of
@@ -245,6 +246,7 @@ const char* svd_status_string(svd_status s) {
     case SVD_ERR_WORKSPACE: return "workspace missing or too small";
     case SVD_ERR_UNSUPPORTED: return "unsupported block shape, option combination or tensor size";
     case SVD_ERR_HIP: return "HIP error";
+    case SVD_ERR_STATIC_LIMIT: return "the layer's lists need more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -277,10 +279,12 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   return SVD_OK;
 }
 
-svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
-                           const int32_t* strategy_table, const svd_head_params* pattern_params,
-                           const svd_plan_options* options, void* device_workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+// with_side_streams = false: the plan creates no streams or events of its own and
+// runs its groups one after the other on the caller's stream.
+static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
+                              const int32_t* strategy_table, const svd_head_params* pattern_params,
+                              const svd_plan_options* options, void* device_workspace,
+                              size_t workspace_bytes, void* hip_stream, bool with_side_streams) {
   if (!plan || !desc || !strategy_table || !pattern_params) return SVD_ERR_NULL;
   *plan = nullptr;
   if (svd_status st = svd::validate_desc(desc)) return st;
@@ -320,7 +324,7 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
     sp->p.launchable = native;
     // SVD_NO_FORK=1 in the environment keeps every group on the caller's stream
     const char* no_fork = std::getenv("SVD_NO_FORK");
-    if (native && !(no_fork && no_fork[0] == '1')) {
+    if (native && with_side_streams && !(no_fork && no_fork[0] == '1')) {
       bool ok = hipEventCreateWithFlags(&sp->fork, hipEventDisableTiming) == hipSuccess;
       for (int i = 0; ok && i < kSideStreams; ++i)
         ok = hipStreamCreateWithFlags(&sp->side[i], hipStreamNonBlocking) == hipSuccess &&
@@ -348,6 +352,14 @@ svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
   }
   *plan = sp;
   return SVD_OK;
+}
+
+svd_status svd_plan_create(svd_plan** plan, const svd_tensor_desc* desc,
+                           const int32_t* strategy_table, const svd_head_params* pattern_params,
+                           const svd_plan_options* options, void* device_workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  return create_plan(plan, desc, strategy_table, pattern_params, options, device_workspace, workspace_bytes,
+                     hip_stream, true);
 }
 
 svd_status svd_plan_destroy(svd_plan* plan) {
@@ -678,6 +690,77 @@ svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
     g_oneshot.workspace_bytes = workspace_bytes;
   }
   return svd_attn_forward_planned(g_oneshot.plan, q, k, v, out, hip_stream);
+}
+
+// The one-shot call for callers that cannot allocate device memory: the plan's
+// workspace is the library's own static buffer of the current device.  The cache
+// is per device (each device has its own buffer); no stream, event or device
+// memory is created here.
+namespace {
+constexpr int kMaxStaticDevices = 64;
+struct StaticShot {
+  svd_plan* plan = nullptr;
+  svd_tensor_desc desc{};
+  std::vector<int32_t> table, flat;
+  hipStream_t last_stream = nullptr;
+  bool used = false;
+};
+std::mutex g_static_mu;
+StaticShot g_static[kMaxStaticDevices];
+}  // namespace
+
+svd_status sparse_vdit_attn_forward_static(const void* q, const void* k, const void* v,
+                                           const int32_t* strategy_table,
+                                           const svd_head_params* pattern_params, void* out,
+                                           const svd_tensor_desc* desc, void* hip_stream) {
+  if (!desc || !strategy_table || !pattern_params) return SVD_ERR_NULL;
+  if (svd_status st = svd::validate_desc(desc)) return st;
+  if (svd_status st = check_tensors(q, k, v, out)) return st;
+  for (int h = 0; h < desc->H; ++h)
+    if (strategy_table[h] < SVD_DENSE || strategy_table[h] > SVD_VSTRIPE) return SVD_ERR_MODE;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return SVD_ERR_HIP;
+  if (dev < 0 || dev >= kMaxStaticDevices) return SVD_ERR_UNSUPPORTED;
+  void* scratch = nullptr;
+  size_t scratch_bytes = 0;
+  if (svd::static_scratch(&scratch, &scratch_bytes) != hipSuccess) return SVD_ERR_HIP;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  StaticShot& c = g_static[dev];
+  std::vector<int32_t> table(strategy_table, strategy_table + desc->H);
+  std::vector<int32_t> flat = flatten(*desc, strategy_table, pattern_params);
+  const bool hit = c.plan && std::memcmp(&c.desc, desc, sizeof(*desc)) == 0 && c.table == table && c.flat == flat;
+  if (!hit) {
+    // A new plan overwrites the lists in the buffer.  That is a copy and a
+    // synchronisation, which a capturing stream cannot record; and whatever the
+    // previous call enqueued on another stream must have finished with the buffer.
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) return SVD_ERR_HIP;
+    if (capture != hipStreamCaptureStatusNone) return SVD_ERR_UNSUPPORTED;
+    if (c.used && c.last_stream != stream && hipDeviceSynchronize() != hipSuccess) return SVD_ERR_HIP;
+    // the split of the dense heads is the library's choice unless its partial results
+    // do not fit the buffer: then the dense heads run unsplit
+    svd_plan_options opt{};
+    size_t need = 0;
+    if (svd_status st = svd_plan_workspace_bytes(desc, strategy_table, pattern_params, &opt, &need)) return st;
+    if (need > scratch_bytes) {
+      opt.dense_split = 1;
+      if (svd_status st = svd_plan_workspace_bytes(desc, strategy_table, pattern_params, &opt, &need)) return st;
+    }
+    if (need > scratch_bytes) return SVD_ERR_STATIC_LIMIT;
+    svd_plan* fresh = nullptr;
+    if (svd_status st = create_plan(&fresh, desc, strategy_table, pattern_params, &opt, scratch, scratch_bytes,
+                                    hip_stream, false))
+      return st;
+    if (c.plan) svd_plan_destroy(c.plan);
+    c.plan = fresh;
+    c.desc = *desc;
+    c.table.swap(table);
+    c.flat.swap(flat);
+  }
+  c.last_stream = stream;
+  c.used = true;
+  return svd_attn_forward_planned(c.plan, q, k, v, out, hip_stream);
 }
 
 // ---------------------------------------------------------------------------

@@ -45,6 +45,7 @@ hipError_t hipGetLastError();
 hipError_t hipStreamCreateWithFlags(hipStream_t* stream, unsigned flags);
 hipError_t hipStreamDestroy(hipStream_t stream);
 hipError_t hipStreamSynchronize(hipStream_t stream);
+hipError_t hipDeviceSynchronize();
 hipError_t hipStreamIsCapturing(hipStream_t stream, hipStreamCaptureStatus* status);
 hipError_t hipEventCreateWithFlags(hipEvent_t* event, unsigned flags);
 hipError_t hipEventDestroy(hipEvent_t event);

@@ -34,6 +34,7 @@ int g_cu = 256;
 bool g_tensor_checks = true;
 int g_violations = 0;
 long g_launches = 0, g_nodes = 0, g_seq = 0;
+int g_captures = 0;                        // captures in progress
 std::map<const char*, size_t> g_allocs;
 ihipStream_t g_null_stream;               // the default stream
 
@@ -92,6 +93,7 @@ void begin_capture(hipStream_t s) {
   st->origin = st;
   st->forked.clear();
   st->unjoined.clear();
+  ++g_captures;
 }
 
 hipError_t end_capture(hipStream_t s) {
@@ -106,6 +108,7 @@ hipError_t end_capture(hipStream_t s) {
   st->forked.clear();
   st->unjoined.clear();
   st->origin = nullptr;
+  --g_captures;
   if (unjoined) violation("capture ended with forked work that was not joined back");
   return unjoined ? hipErrorStreamCaptureUnjoined : hipSuccess;
 }
@@ -149,6 +152,13 @@ hipError_t hipStreamSynchronize(hipStream_t stream) {
   if (!alive(st)) stub::violation("hipStreamSynchronize on a dead stream");
   if (st->origin) {
     stub::violation("hipStreamSynchronize on a capturing stream");
+    return hipErrorStreamCaptureUnsupported;
+  }
+  return hipSuccess;
+}
+hipError_t hipDeviceSynchronize() {
+  if (g_captures > 0) {
+    stub::violation("hipDeviceSynchronize while a capture is active");
     return hipErrorStreamCaptureUnsupported;
   }
   return hipSuccess;

@@ -16,6 +16,7 @@
 #include "probe_kernels.h"
 #include "rearrange_kernels.h"
 #include "search_kernels.h"
+#include "static_scratch.h"
 
 namespace svd {
 namespace {
@@ -109,7 +110,7 @@ void model_item(const AttnLaunch& p, const Fp8Launch* f8, int mode, bool small_q
     }
   }
   // query rows (clamped to L - 1 on load, stored only below L)
-  for (int r = 0; r < BR; ++r) {
+  for (int r = 0; r < BR && (stub::tensor_checks() || mode == MODE_PBAND); ++r) {
     int row = qblk * BR + r;
     const bool store = row < L && !(mode == MODE_DENSE && p.split > 1);
     row = row < L ? row : L - 1;
@@ -149,6 +150,7 @@ void model_item(const AttnLaunch& p, const Fp8Launch* f8, int mode, bool small_q
       touch_read(f8->v8t + base8 + (size_t)tile * BC * p.D, (size_t)BC * p.D, "v8t tile", true);
       continue;
     }
+    if (!stub::tensor_checks() && mode != MODE_GATHER && mode != MODE_PBAND) continue;   // no workspace word involved
     for (int r = 0; r < BC; ++r) {
       int row = tile * BC + r;
       if (mode == MODE_GATHER || mode == MODE_PBAND) {
@@ -296,6 +298,14 @@ hipError_t launch_attention_fp8(const Fp8Launch& p, int mode, hipStream_t stream
   if (p.a.n_items <= 0) return hipSuccess;
   if (!p.k8 || !p.v8t || p.Lp != fp8_padded_len(p.a.L)) return hipErrorInvalidValue;
   return model_attention(p.a, &p, mode, stream, small_q);
+}
+
+// The library's static buffer: here one exact-size "device" allocation for the one modelled device.
+hipError_t static_scratch(void** ptr, size_t* bytes) {
+  static void* buffer = stub::device_alloc(kStaticScratchBytes);
+  *ptr = buffer;
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
 }
 
 // ---- search step and rearrangement: streaming kernels, ranges only ----

@@ -147,6 +147,33 @@ void run_layer(const Layer& l) {
     expect(svd_plan_destroy(plan) == SVD_OK, l, "svd_plan_destroy");
     stub::device_free(ws);
   }
+  if (l.text == 0) {
+    // the entry point that allocates nothing: a miss (copy of the lists into the library's buffer),
+    // a hit, and a hit under capture; a miss under capture is refused
+    int st = sparse_vdit_attn_forward_static(q, k, v, l.table.data(), l.params.data(), out, &desc, nullptr);
+    expect(st == SVD_OK || st == SVD_ERR_STATIC_LIMIT, l, "static one-shot forward", st);
+    if (st == SVD_OK) {
+      st = sparse_vdit_attn_forward_static(q, k, v, l.table.data(), l.params.data(), out, &desc, nullptr);
+      expect(st == SVD_OK, l, "static one-shot forward, cached plan", st);
+      hipStream_t side = stub::create_stream();
+      stub::begin_capture(side);
+      st = sparse_vdit_attn_forward_static(q, k, v, l.table.data(), l.params.data(), out, &desc, side);
+      expect(st == SVD_OK, l, "static one-shot forward under capture, cached plan", st);
+      expect(stub::end_capture(side) == hipSuccess, l, "capture ends");
+      if (l.H > 1) {   // another table: a miss, which a capturing stream cannot take
+        std::vector<int32_t> other(l.table);
+        std::vector<svd_head_params> pp(l.params);
+        other[0] = other[0] == SVD_SKIP ? SVD_DENSE : SVD_SKIP;
+        stub::begin_capture(side);
+        st = sparse_vdit_attn_forward_static(q, k, v, other.data(), pp.data(), out, &desc, side);
+        expect(st == SVD_ERR_UNSUPPORTED, l, "static one-shot forward under capture with a new table is refused", st);
+        expect(stub::end_capture(side) == hipSuccess, l, "capture ends");
+        st = sparse_vdit_attn_forward_static(q, k, v, other.data(), pp.data(), out, &desc, side);
+        expect(st == SVD_OK, l, "static one-shot forward with a new table on another stream", st);
+      }
+      stub::destroy_stream(side);
+    }
+  }
   for (void* p : {q, k, v, out, ws8}) stub::device_free(p);
 }
 
