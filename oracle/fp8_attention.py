@@ -32,12 +32,23 @@ not of the paper) and states it as a quantise-dequantise definition on top of Eq
 Masks, modes and the zero output of M_1 are taken from the bf16 oracle's
 definitions; only the arithmetic of a row differs.
 
+Several results are correct for a row whose probabilities sit on a rounding
+boundary: P8 is a rounding decision on a score that an fp32 implementation sums
+in an order of its own, so a probability within the score's error bound of the
+midpoint between two E4M3 values may take either neighbour.
+attention_rows_fp8_alternatives states that set: per row the results of every
+combination of the heaviest such decisions, plus a bound on what the lighter
+ones can move.
+
 Pins (tests/test_oracle_fp8.py): the rounding against the format's own code
 table (brute-force nearest value, ties to even) and against a library
 conversion; the attention against closed forms (constant V, zero Q), a
 pure-Python loop over the code table, invariance under an integer shift of the
-reference, and closeness to the unquantised oracle.  No function here is
-"parity unpinned".
+reference, and closeness to the unquantised oracle; the score-error bound against
+fp32 sums taken in random orders with truncation; the set of alternatives against
+a hand-worked row, against rows without any ambiguity, and against the results
+of simulated implementations whose scores are off by up to the bound.  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -99,47 +110,120 @@ def quantise_v(v):
     return round_e4m3(np.asarray(v, dtype=np.float64))
 
 
-WEIGHT_FLOOR = 5e-3   # share of the row sum below which a probability is too light to matter for the margin
-
-
-def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0, with_margin=False):
+def attention_rows_fp8(q8_rows, k8, v8, mask, shift=0):
     """The quantised row arithmetic of the header for operands already in E4M3.
 
     q8_rows [R, D], k8 [L, D], v8 [L, D] float64 holding E4M3 values, mask [R, L].
     shift: integer added to the reference (0 in the definition; the tests use it
     to show that the result does not depend on it).
-    with_margin: also return, per row, the smallest rounding_margin of the
-    probabilities that carry more than WEIGHT_FLOOR of the row's weight: how far
-    the row's result is from depending on the last bits of a score.  (A lighter
-    probability that rounds the other way moves the row by less than
-    WEIGHT_FLOOR / 8 * |v - o|.)
     """
     if not mask.any(axis=1).all():
         raise ValueError("a query row keeps no key")
     s2 = q8_rows @ k8.T
     s2[~mask] = -np.inf
     m = np.ceil(s2.max(axis=1, keepdims=True)) - P_HEADROOM + int(shift)
+    p8 = round_e4m3(np.exp2(s2 - m))
+    return (p8 @ v8) / p8.sum(axis=1, keepdims=True)
+
+
+def score_error_bound(q8_rows, k8):
+    """Bound on |s2 of an fp32 implementation - exact s2|, per (row, key).
+
+    A product of two E4M3 values has an 8-bit significand and is exact in fp32.
+    Summing the d products of a score in fp32, in any order and with rounding or
+    truncation at every step, commits at most 2 units in the last place
+    (2 * 2^-24 relative) on a partial sum that never exceeds sum_d |q8 k8| in
+    magnitude, d times at most: |error| <= d * 2^-23 * sum_d |q8_d k8_d|.
+    A matrix unit that aligns the products of a step to the largest one keeps to
+    this bound as long as it carries 24 bits below that one.
+    """
+    d = q8_rows.shape[-1]
+    return d * 2.0 ** -23 * (np.abs(q8_rows) @ np.abs(k8).T)
+
+
+EXP2_REL_ERR = 2.0 ** -21    # relative error granted to the implementation's exp2 (a few fp32 ulp)
+MAX_FLIPS = 6                # rounding decisions enumerated per row (2^6 candidate results)
+
+
+def attention_rows_fp8_alternatives(q8_rows, k8, v8, mask, max_flips=MAX_FLIPS):
+    """The set of correct results of attention_rows_fp8, row by row.
+
+    A probability p = 2^(s2 - m) is AMBIGUOUS when the relative distance of p to a
+    midpoint between two E4M3 values is at most log(2) * score_error_bound +
+    EXP2_REL_ERR: an fp32 implementation may then round it to either neighbour.
+    Returns (out, candidates, slack):
+      out         [R, D]  the nominal result (every decision taken on the exact score);
+      candidates  list of R arrays [n_r, D]: the results for every combination of the
+                  max_flips ambiguous probabilities with the largest |change of P8|
+                  (n_r = 2^k, row 0 = the nominal result; n_r = 1 without ambiguity);
+      slack       [R, D]  element-wise bound on what flipping any subset of the
+                  remaining (lighter) ambiguous probabilities moves a candidate by.
+    A result is correct iff it lies within slack (plus the accumulation error of
+    the implementation) of one of the row's candidates.
+    """
+    if not mask.any(axis=1).all():
+        raise ValueError("a query row keeps no key")
+    s2 = q8_rows @ k8.T
+    s2[~mask] = -np.inf
+    m = np.ceil(s2.max(axis=1, keepdims=True)) - P_HEADROOM
     p = np.exp2(s2 - m)
     p8 = round_e4m3(p)
-    den = p8.sum(axis=1, keepdims=True)
-    out = (p8 @ v8) / den
-    if not with_margin:
-        return out
-    margin = np.where(p8 > WEIGHT_FLOOR * den, rounding_margin(p), np.inf).min(axis=1)
-    return out, margin
+    den = p8.sum(axis=1)
+    num = p8 @ v8
+    out = num / den[:, None]
+    rel = math.log(2.0) * score_error_bound(q8_rows, k8) + EXP2_REL_ERR
+    ambiguous = mask & (rounding_margin(p) <= rel)
+    candidates = [out[r:r + 1] for r in range(out.shape[0])]
+    slack = np.zeros_like(out)
+    for r in np.nonzero(ambiguous.any(axis=1))[0]:
+        j = np.nonzero(ambiguous[r])[0]
+        pj, ej = p[r, j], rel[r, j]
+        up, down = round_e4m3(pj * (1.0 + 2.0 * ej)), round_e4m3(pj * (1.0 - 2.0 * ej))   # the two neighbours
+        other = np.where(up != p8[r, j], up, down)
+        dp = other - p8[r, j]
+        keep = dp != 0
+        j, dp = j[keep], dp[keep]
+        order = np.argsort(-np.abs(dp), kind="stable")
+        j, dp = j[order], dp[order]
+        top_j, top_dp = j[:max_flips], dp[:max_flips]
+        k_top = top_j.size
+        bits = (np.arange(1 << k_top)[:, None] >> np.arange(k_top)[None, :]) & 1      # [2^k, k], row 0 = no flip
+        num_c = num[r][None, :] + (bits * top_dp[None, :]) @ v8[top_j]
+        den_c = den[r] + bits @ top_dp
+        cand = num_c / den_c[:, None]
+        candidates[r] = cand
+        rest_j, rest_dp = j[max_flips:], np.abs(dp[max_flips:])
+        if rest_j.size:
+            reach = np.abs(v8[rest_j]) + np.abs(cand).max(axis=0)[None, :]
+            slack[r] = (rest_dp[:, None] * reach).sum(axis=0) / (den_c.min() - rest_dp.sum())
+    return out, candidates, slack
 
 
-def attention_head_fp8(q, k, v, mode, params, rows=None, chunk=128, with_margin=False):
-    """One head in the FP8 variant, all rows or the given rows.  q, k, v: [L, D].
-    with_margin: also return the per-row margin of attention_rows_fp8."""
+def attention_head_fp8_alternatives(q, k, v, mode, params, rows=None, chunk=128):
+    """attention_rows_fp8_alternatives for one head (all rows or the given rows): (out, candidates, slack)."""
     L, d = q.shape
     rows = np.arange(L, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
     out = np.zeros((rows.size, d), dtype=np.float64)
-    margin = np.full(rows.size, np.inf)
+    slack = np.zeros_like(out)
+    candidates = [out[r:r + 1] for r in range(rows.size)]
     if mode != SA.MODE_SKIP:
         q8, k8, v8 = quantise_q(q), quantise_k(k), quantise_v(v)
         for s in range(0, rows.size, chunk):
             r = rows[s:s + chunk]
-            out[s:s + chunk], margin[s:s + chunk] = attention_rows_fp8(
-                q8[r], k8, v8, SA.allowed_mask(mode, params, L, r), with_margin=True)
-    return (out, margin) if with_margin else out
+            o, c, sl = attention_rows_fp8_alternatives(q8[r], k8, v8, SA.allowed_mask(mode, params, L, r))
+            out[s:s + chunk], slack[s:s + chunk] = o, sl
+            candidates[s:s + chunk] = c
+    return out, candidates, slack
+
+
+def attention_head_fp8(q, k, v, mode, params, rows=None, chunk=128):
+    """One head in the FP8 variant, all rows or the given rows.  q, k, v: [L, D]."""
+    L, d = q.shape
+    rows = np.arange(L, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    out = np.zeros((rows.size, d), dtype=np.float64)
+    if mode != SA.MODE_SKIP:
+        q8, k8, v8 = quantise_q(q), quantise_k(k), quantise_v(v)
+        for s in range(0, rows.size, chunk):
+            r = rows[s:s + chunk]
+            out[s:s + chunk] = attention_rows_fp8(q8[r], k8, v8, SA.allowed_mask(mode, params, L, r))
+    return out

@@ -8,7 +8,7 @@ from oracle import fp8_attention as F8
 from oracle import sparse_attention as O
 from paper_2506_03065_amd import binding as svd
 from paper_2506_03065_amd import workloads as W
-from parity_util import MEAN_ABS, REL_L2, assert_close, f64
+from parity_util import MAX_ABS, MAX_OVER_RMS, MEAN_ABS, REL_L2, assert_close, f64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -32,39 +32,46 @@ def run_fp8(wl, q, k, v, dense_split=0, out=None):
     return out, ws8
 
 
-# A probability closer than this (relatively) to a midpoint between two E4M3 values
-# may round either way.  The matrix unit adds the 64 products of a step with fewer
-# guard bits than a chain of fp32 additions would have, and the oracle sums in
-# float64: the two scores were seen to differ by up to 4e-5 (a P moved at a margin
-# of 2.8e-5), hence 1e-4.
-MARGIN = 1e-4
+def best_candidates(got, candidates, slack):
+    """Per row, the correct result (see attention_rows_fp8_alternatives) closest to `got`, and what is left of
+    |got - it| after the row's slack: the deviation that no admissible rounding decision explains."""
+    want = np.empty_like(got)
+    excess = np.empty_like(got)
+    for r, cand in enumerate(candidates):
+        over = np.maximum(np.abs(got[r][None, :] - cand) - slack[r][None, :], 0.0)
+        best = int(np.argmin(over.max(axis=1)))
+        want[r], excess[r] = cand[best], over[best]
+    return want, excess
 
 
-def check_layer_fp8(wl, q, k, v, out, rows=None, heads=None):
-    """Against the FP8 oracle.  Rows in which every probability of weight (more
-    than 5e-3 of the row sum) is further than MARGIN from a rounding decision must
-    meet the bar of the bf16 path element by element.  In the other rows a P may
-    sit one E4M3 step (relative 2^-3) away, which moves the row by at most
-    weight / 8 * |v - o|: they are held to 0.25 * max|V|, and all rows together
-    to the mean and relative-L2 bars."""
+def check_layer_fp8(wl, q, k, v, out, rows=None, heads=None, slack_share=0.25):
+    """Against the FP8 oracle.  Where several results are correct - a probability within the fp32 score-error
+    bound of a midpoint between two E4M3 values may round either way - the oracle lists them: every combination
+    of the (up to six) heaviest such decisions of a row, plus an element-wise bound (slack) on what the lighter
+    ones can move.  A row passes iff, for ONE of its candidates, every element lies within slack plus the
+    element bar of the bf16 path; the bars are those of parity_util, applied to what exceeds the slack."""
     qc, kc, vc, oc = q.cpu(), k.cpu(), v.cpu(), out.cpu()
     for b in range(wl.B):
         for h in (range(wl.H) if heads is None else heads):
             mode, p = int(wl.strategy_table[h]), wl.pattern_params[h]
             what = f"fp8 {wl.name} b{b} h{h} mode{mode}"
-            want, margin = F8.attention_head_fp8(f64(qc[b, h]), f64(kc[b, h]), f64(vc[b, h]), mode, p, rows=rows,
-                                                 with_margin=True)
+            nominal, candidates, slack = F8.attention_head_fp8_alternatives(f64(qc[b, h]), f64(kc[b, h]), f64(vc[b, h]),
+                                                                            mode, p, rows=rows)
             got = f64(oc[b, h]) if rows is None else f64(oc[b, h][torch.as_tensor(rows)])
-            sure = margin > MARGIN
-            assert sure.mean() >= 0.5, f"{what}: only {sure.mean():.2f} of the rows are decided"
-            assert_close(got[sure], want[sure], what)
             assert np.isfinite(got).all(), f"{what}: non-finite output"
-            diff = np.abs(got - want)
-            assert diff.max() <= 0.25 * np.abs(f64(vc[b, h])).max() + 1e-3, f"{what}: max abs {diff.max():.3e}"
-            assert diff.mean() <= MEAN_ABS, f"{what}: mean abs {diff.mean():.3e}"
-            if (want ** 2).sum() > 0:
-                rel = float(np.sqrt((diff ** 2).sum() / (want ** 2).sum()))
+            want, excess = best_candidates(got, candidates, slack)
+            rms = float(np.sqrt((nominal ** 2).mean()))
+            # the slack must stay a part of the element bar (a quarter; the whole bar for score profiles built to
+            # have large score errors), or the check would be empty
+            assert slack.max() <= slack_share * (MAX_OVER_RMS * rms + 1e-3), f"{what}: slack {slack.max():.3e} vs rms {rms:.3e}"
+            assert excess.max() <= MAX_ABS, f"{what}: max abs {excess.max():.3e}"
+            assert excess.mean() <= MEAN_ABS, f"{what}: mean abs {excess.mean():.3e}"
+            if rms > 0:
+                rel = float(np.sqrt((excess ** 2).sum() / (nominal ** 2).sum()))
                 assert rel <= REL_L2, f"{what}: relative L2 {rel:.3e}"
+                assert excess.max() <= MAX_OVER_RMS * rms + 1e-3, f"{what}: max abs {excess.max():.3e} vs rms {rms:.3e}"
+            else:
+                assert not got.any(), f"{what}: expected exact zeros"
 
 
 def decode(bytes_u8):
@@ -187,7 +194,9 @@ def test_peaked_scores_move_the_reference(D, profile):
     k = (0.3 * k.float() + sign * gain[None, None, :, None] * u).to(torch.bfloat16)
     q, k, v = _cuda([q, k, v])
     out, _ = run_fp8(wl, q, k, v)
-    check_layer_fp8(wl, q, k, v, out)
+    # queries and keys share a large common component here: sum |q8 k8| and with it the fp32 error bound of a
+    # score are an order of magnitude above those of unit-variance inputs, so more decisions are open per row
+    check_layer_fp8(wl, q, k, v, out, slack_share=1.0)
 
 
 @pytest.mark.parametrize("L,D,split", [(1000, 64, 3), (1000, 128, 5), (130, 64, 8)])

@@ -53,15 +53,30 @@ def test_benchmark_shape_sampled_rows_and_closed_form(name):
         assert_close(f64(out0[0, h]), want, f"{name} zero-q head {h} mode {mode}")
 
 
-@pytest.mark.parametrize("layer", [0, 20, 39])
+_STACK_QKV = {}
+
+
+def _stack_qkv(wl):
+    """Every layer of the stack draws Q, K, V from the same seed: generated once."""
+    if wl.seed not in _STACK_QKV:
+        _STACK_QKV.clear()
+        _STACK_QKV[wl.seed] = [t.to(DEV) for t in W.make_qkv(wl)]
+    return _STACK_QKV[wl.seed]
+
+
+@pytest.mark.parametrize("layer", [0, 5, 10, 15, 20, 25, 30, 35, 39])
 def test_stack_layers(layer):
-    """Layers of the 40-layer stack (Wan2.1 shape, dense share falling with depth)."""
+    """Layers of the 40-layer stack (Wan2.1 shape, dense share falling with depth): every head on sampled rows.
+    (All 40 tables are compiled against the oracle's groups and lists on the CPU, tests/test_pattern_compiler.py.)"""
     wl = W.stack_layer(layer)
     counts = W.stack_layer_counts(layer)
-    assert sum(counts.values()) == wl.H and counts[W.DENSE] == {0: 32, 20: 18, 39: 4}[layer]
-    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    assert sum(counts.values()) == wl.H and counts[W.DENSE] == int(round(40 * (0.8 - 0.7 * layer / 39)))
+    q, k, v = _stack_qkv(wl)
     out = run_planned(wl, q, k, v)
-    rows = W.sample_rows(wl, n_random=16)
-    heads = sorted({int(np.nonzero(wl.strategy_table == m)[0][0]) for m in range(5) if (wl.strategy_table == m).any()}
-                   | set(range(0, wl.H, 7)))
-    check_layer(wl, q, k, v, out, rows=rows, heads=heads)
+    rows = W.sample_rows(wl, n_random=16, seed=layer)
+    check_layer(wl, q, k, v, out, rows=rows)
+    for h in range(wl.H):
+        if wl.strategy_table[h] == W.SKIP:
+            assert not out[0, h].view(torch.int16).any()
+    if layer == 39:
+        _STACK_QKV.clear()

@@ -174,3 +174,100 @@ def test_close_to_the_unquantised_oracle(mode, params):
     assert rel < 0.08, rel      # E4M3 carries 4 significant bits: a few percent is the expected level
     # and a wrong mask, a transposed operand or a dropped scale would give an error of order one
     assert rel > 1e-4
+
+
+# ---- the set of correct results (attention_rows_fp8_alternatives) ----
+
+def test_score_error_bound_covers_fp32_sums_in_any_order():
+    """fp32 sums of the d exact products, in random orders, rounded or truncated at every step, stay inside the bound."""
+    rng = np.random.default_rng(5)
+    for d in (64, 128):
+        q8 = F8.quantise_q(rng.standard_normal((16, d)) * 2.0)
+        k8 = F8.quantise_k(rng.standard_normal((40, d)) * 2.0)
+        bound = F8.score_error_bound(q8, k8)
+        exact = q8 @ k8.T
+        assert (bound > 0).all() and bound.max() < 1e-3
+        for trial in range(6):
+            perm = rng.permutation(d)
+            acc = np.zeros((16, 40), dtype=np.float32)
+            for t in perm:
+                term = (q8[:, t:t + 1] * k8[None, :, t]).astype(np.float32)          # exact in fp32
+                wide = acc.astype(np.float64) + term.astype(np.float64)
+                if trial % 2:                                                       # truncation towards zero
+                    r = wide.astype(np.float32)
+                    away = np.abs(r.astype(np.float64)) > np.abs(wide)
+                    r = np.where(away, np.nextafter(r, np.float32(0)), r).astype(np.float32)
+                    acc = r
+                else:
+                    acc = wide.astype(np.float32)
+            assert (np.abs(acc.astype(np.float64) - exact) <= bound).all()
+    # the closed form on a case worked by hand: d = 64 terms of 0.5 * 0.25
+    one = F8.score_error_bound(np.full((1, 64), 0.5), np.full((1, 64), 0.25))
+    assert one[0, 0] == 64 * 2.0 ** -23 * 8.0
+
+
+def test_alternatives_of_a_hand_worked_row():
+    """Two keys.  Key 0 carries the row maximum 0 (P = 256 exactly), key 1 a score that puts P one part in 10^6
+    below 11.5, the midpoint of the E4M3 neighbours 11 and 12: the nominal rounding is 11, the alternative 12."""
+    d = 64
+    target = math.log2(11.5 * (1.0 - 1e-5)) - 8.0        # score of key 1 relative to the reference -8
+    # the score is spelt out over eight coordinates of falling weight (2^-9 is the smallest E4M3 value), each
+    # taking the E4M3 value nearest to what is left
+    q8 = np.zeros((1, d))
+    k8 = np.zeros((2, d))
+    rest = target
+    for c, weight in enumerate([1.0, 2.0 ** -3, 2.0 ** -6] + [2.0 ** -9] * 5):
+        q8[0, c] = weight
+        k8[1, c] = F8.round_e4m3(np.array([rest / weight]))[0]
+        rest -= k8[1, c] * weight
+    assert np.array_equal(F8.round_e4m3(q8), q8) and abs(rest) < 3e-6
+    s = float(q8[0] @ k8[1])
+    p = 2.0 ** (s + 8.0)
+    assert 2e-6 < 1.0 - p / 11.5 < 2e-5, p               # on the low side of the midpoint, inside the error bound
+    v8 = np.array([[1.0] + [0.0] * (d - 1), [-2.0] + [0.5] * (d - 1)])
+    mask = np.ones((1, 2), dtype=bool)
+    out, cands, slack = F8.attention_rows_fp8_alternatives(q8, k8, v8, mask)
+    assert np.array_equal(out, F8.attention_rows_fp8(q8, k8, v8, mask))
+    assert cands[0].shape == (2, d) and not slack.any()
+    want_nominal = (256.0 * v8[0] + 11.0 * v8[1]) / 267.0
+    want_other = (256.0 * v8[0] + 12.0 * v8[1]) / 268.0
+    assert np.allclose(cands[0][0], want_nominal, rtol=0, atol=1e-15)
+    assert np.allclose(cands[0][1], want_other, rtol=0, atol=1e-15)
+
+
+def test_no_alternatives_without_a_rounding_boundary_in_reach():
+    """Zero queries: every score is 0, every P is 256 exactly, nothing is ambiguous."""
+    rng = np.random.default_rng(6)
+    k8, v8 = F8.quantise_k(rng.standard_normal((50, 64))), F8.quantise_v(rng.standard_normal((50, 64)))
+    mask = rng.random((7, 50)) < 0.5
+    mask[:, 0] = True
+    out, cands, slack = F8.attention_rows_fp8_alternatives(np.zeros((7, 64)), k8, v8, mask)
+    assert all(c.shape[0] == 1 for c in cands) and not slack.any()
+    assert np.array_equal(np.concatenate(cands), out)
+
+
+@pytest.mark.parametrize("d,max_flips", [(64, 6), (128, 6), (128, 1), (128, 0)])
+def test_alternatives_cover_every_result_within_the_score_error(d, max_flips):
+    """Simulated implementations: the exact scores moved by up to the bound (random, and all to one side), then
+    the definition's own rounding.  Every such result lies within the row's slack of one of its candidates -
+    also when few or no decisions are enumerated and the rest goes to the slack."""
+    rng = np.random.default_rng(7 + d)
+    L, R = 3000, 96
+    q8 = F8.quantise_q(rng.standard_normal((R, d)))
+    k8, v8 = F8.quantise_k(rng.standard_normal((L, d))), F8.quantise_v(rng.standard_normal((L, d)))
+    mask = np.ones((R, L), dtype=bool)
+    out, cands, slack = F8.attention_rows_fp8_alternatives(q8, k8, v8, mask, max_flips=max_flips)
+    assert sum(c.shape[0] > 1 for c in cands) >= (R // 4 if max_flips else 0)      # the case is not empty
+    bound = F8.score_error_bound(q8, k8)
+    s2 = q8 @ k8.T
+    m = np.ceil(s2.max(axis=1, keepdims=True)) - F8.P_HEADROOM
+    flipped_rows = 0
+    for trial in range(8):
+        err = {0: bound, 1: -bound}.get(trial, bound * rng.uniform(-1.0, 1.0, size=bound.shape))
+        p8 = F8.round_e4m3(np.exp2(s2 + err - m))
+        got = (p8 @ v8) / p8.sum(axis=1, keepdims=True)
+        for r in range(R):
+            over = np.abs(got[r][None, :] - cands[r]) - slack[r][None, :]
+            assert over.max(axis=1).min() <= 1e-12, (trial, r, over.max(axis=1).min())
+        flipped_rows += int((np.abs(got - out).max(axis=1) > 1e-12).sum())
+    assert flipped_rows > R                                                         # the simulated errors do flip decisions

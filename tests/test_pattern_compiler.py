@@ -33,8 +33,11 @@ def _compile(wl, bq, bk):
     return svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, bq, bk)
 
 
-def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
-    plan = _compile(wl, bq, bk)
+def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None, plan=None):
+    """plan = None: compiled here with the explicit shape bq x bk.  A given plan (for instance one compiled with
+    the library's defaults) is checked group by group on the query tile the group reports; q_blocks may then be
+    a function of the number of query blocks."""
+    plan = _compile(wl, bq, bk) if plan is None else plan
     got_groups = plan.groups()
     want_groups = O.head_groups(wl.strategy_table, wl.pattern_params)
     assert [(g["mode"], g["heads"], g["list_id"], g["rearranged"]) for g in got_groups] == \
@@ -54,6 +57,8 @@ def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
                 assert got["cols"].dtype == np.int32 and np.array_equal(got["cols"], want)
                 continue
             got = plan.band_list(gi, lst)
+            bq = g["block_q"]
+            assert g["block_k"] == bk
             if g["rearranged"]:
                 got["row_map"] = plan.row_map(gi, lst)
                 want = O.block_lists(g["mode"], p, wl.L, bq, bk)
@@ -66,7 +71,8 @@ def _assert_plan_matches_oracle(wl, bq, bk, q_blocks=None):
             else:
                 runs = O.delta_runs(g["mode"], p, wl.L)
                 assert np.array_equal(got["runs"], runs)
-                for qb in q_blocks:
+                assert got["row_ptr"].size == -(-wl.L // bq) + 1
+                for qb in (q_blocks(-(-wl.L // bq)) if callable(q_blocks) else q_blocks):
                     kb, fl, rf, rc = O.query_block_entries(g["mode"], p, wl.L, bq, bk, qb, runs)
                     s, e = got["row_ptr"][qb], got["row_ptr"][qb + 1]
                     assert np.array_equal(got["kv_block_idx"][s:e], kb), (wl.name, qb)
@@ -354,3 +360,49 @@ def test_default_plan_gives_narrow_band_groups_the_small_query_tile():
     plan = svd.svd_plan_create(desc, table, params, bq, bk)
     assert {g["block_q"] for g in plan.groups()} == {bq}
     plan.close()
+
+
+_STACK_BAND_LISTS = {}
+
+
+def _stack_band_lists(plan):
+    """{(mode, block_q): band list} of a stack layer's plan (every layer uses one diagonal and one multi-diagonal pattern)."""
+    out = {}
+    for gi, grp in enumerate(plan.groups()):
+        if grp["mode"] in (svd.SVD_DIAG, svd.SVD_MULTIDIAG):
+            assert grp["n_lists"] == 1
+            out[(grp["mode"], grp["block_q"])] = plan.band_list(gi, 0)
+    return out
+
+
+@pytest.mark.parametrize("layer", range(40))
+def test_every_stack_layer_compiles_to_the_oracles_groups_and_lists(layer):
+    """All 40 strategy tables of the layer stack (dense share falling from 80 % to 10 % with depth), host only,
+    both with the kernels' block shape given explicitly and in the plan the library compiles by default (band
+    groups on the small query tile): mode counts, groups, list ids, every column list and the runs of kept
+    diagonals bit-exact against the oracle; element counts against the closed forms.  The band patterns are the
+    same in every layer, so the band lists must equal those of the first layer bit for bit, and those are
+    compared with the oracle's explicit-mask entries on sampled query blocks."""
+    wl = W.stack_layer(layer)
+    counts = W.stack_layer_counts(layer)
+    assert sum(counts.values()) == wl.H == 40
+    assert counts[W.DENSE] == int(round(40 * (0.8 - 0.7 * layer / 39)))
+    assert {m: int((wl.strategy_table == m).sum()) for m in range(5)} == {m: counts.get(m, 0) for m in range(5)}
+    bq, bk = svd.svd_default_blocks(wl.D)
+    first = not _STACK_BAND_LISTS
+    sample = (lambda n_qb: [0, (3 * wl.frame_tokens) // -(-wl.L // n_qb), n_qb - 1]) if first else []
+    explicit = _compile(wl, bq, bk)
+    default = svd.svd_plan_create(svd.tensor_desc(wl.B, wl.H, wl.L, wl.D), wl.strategy_table, wl.pattern_params)
+    lists = {**_stack_band_lists(explicit), **_stack_band_lists(default)}
+    assert {k[1] for k in lists} == {bq, 128}                     # the default plan runs the band groups on 128 rows
+    if first:
+        _STACK_BAND_LISTS.update(lists)
+    for key, bl in lists.items():
+        for name, arr in bl.items():
+            assert np.array_equal(arr, _STACK_BAND_LISTS[key][name]), (layer, key, name)
+    g = GOLDEN["wan2.1"]
+    want_pairs = (counts[W.DENSE] * wl.L ** 2 + counts[W.DIAG] * g["diag"]["pairs"] +
+                  counts[W.MULTIDIAG] * g["multi"]["pairs"] + counts[W.VSTRIPE] * g["vertical"]["pairs"])
+    assert default.work()["kept_pairs"] == float(want_pairs) == explicit.work()["kept_pairs"]
+    _assert_plan_matches_oracle(wl, bq, bk, q_blocks=sample, plan=explicit)
+    _assert_plan_matches_oracle(wl, bq, bk, q_blocks=sample, plan=default)
