@@ -125,8 +125,21 @@ typedef struct {
  * are then empty (their rows come from a dense launch over the group's heads),
  * the other query blocks list the text tiles first, and the column lists gain
  * columns 0..T-1.  0 = no text prefix.  sparse_vdit_attn_forward takes no
- * options and therefore no text prefix. */
-typedef struct { int32_t block_q, block_k, dense_split, text_tokens; } svd_plan_options;
+ * options and therefore no text prefix.
+ * single_launch: Section 4.2 fuses the heads that share a mode into one launch;
+ * with single_launch = 1 the whole layer is ONE launch: resident work-groups (two
+ * of four waves per compute unit) pull (group, head, query tile) items off eight
+ * work queues, one per XCD, heaviest group first, and move on to the other
+ * queues when their own is empty, so no group pays for a partly filled last
+ * round.  Every item runs on the 128-row query tile, dense heads are not split
+ * (dense_split is ignored), text rows of a text prefix are items of the dense
+ * kind, and nothing is forked.  The queue positions are eight words of the plan
+ * workspace that a small fill kernel zeroes ahead of the layer kernel (two
+ * launches in all; no memset, so the call can be captured).  Results are
+ * bit-identical to the grouped launches of a plan with dense_split = 1.
+ * 0 = the library's choice (grouped launches), 2 = grouped launches.  Needs the
+ * kernels' block shape (SVD_ERR_UNSUPPORTED with an explicit other shape). */
+typedef struct { int32_t block_q, block_k, dense_split, text_tokens, single_launch; } svd_plan_options;
 
 typedef struct svd_plan svd_plan;
 
@@ -158,6 +171,10 @@ svd_status svd_plan_destroy(svd_plan* plan);
 /* Key-range chunks per dense query tile this plan launches (1 = no split; always
  * 1 for host-only plans). */
 svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split);
+
+/* 1 when svd_attn_forward_planned runs this plan as one launch (plan option
+ * single_launch), else 0. */
+svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch);
 
 /* Inspection of a compiled plan (host copies owned by the plan, valid until
  * svd_plan_destroy).  Groups are ordered by ascending mode id. */

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "SVD_OK", 1: "SVD_ERR_NULL", 2: "SVD_ERR_SHAPE", 3: "SVD_ERR_
 SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
-           "svd_plan_dense_split", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_group_blocks", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
+           "svd_plan_dense_split", "svd_plan_single_launch", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_group_blocks", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward", "sparse_vdit_attn_forward_static",
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
@@ -50,7 +50,7 @@ class HeadParams(C.Structure):
 
 class PlanOptions(C.Structure):
     _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32), ("dense_split", C.c_int32),
-                ("text_tokens", C.c_int32)]
+                ("text_tokens", C.c_int32), ("single_launch", C.c_int32)]
 
 
 _lib = None
@@ -73,6 +73,7 @@ def lib():
             "svd_plan_create": [C.POINTER(vp), descp, i32p, hpp, optp, vp, C.c_size_t, vp],
             "svd_plan_destroy": [vp],
             "svd_plan_dense_split": [vp, i32p],
+            "svd_plan_single_launch": [vp, i32p],
             "svd_plan_num_groups": [vp, i32p],
             "svd_plan_group_info": [vp, C.c_int32, i32p, i32p, i32pp, i32pp, i32p],
             "svd_plan_group_rearranged": [vp, C.c_int32, i32p],
@@ -186,9 +187,10 @@ def svd_default_blocks(D: int):
 
 
 def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0, dense_split=0,
-                             text_tokens=None) -> int:
+                             text_tokens=None, single_launch=0) -> int:
     m = _Marshalled(strategy_table, pattern_params)
-    opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens))
+    opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens),
+                      single_launch)
     n = C.c_size_t()
     _check(lib().svd_plan_workspace_bytes(C.byref(desc), _ptr(m.table), m.params, C.byref(opt), C.byref(n)),
            "svd_plan_workspace_bytes")
@@ -227,6 +229,11 @@ class Plan:
         n = C.c_int32()
         _check(lib().svd_plan_dense_split(self.handle, C.byref(n)), "svd_plan_dense_split")
         return n.value
+
+    def single_launch(self) -> bool:
+        n = C.c_int32()
+        _check(lib().svd_plan_single_launch(self.handle, C.byref(n)), "svd_plan_single_launch")
+        return bool(n.value)
 
     def groups(self):
         L_ = lib()
@@ -283,13 +290,14 @@ class Plan:
 
 
 def svd_plan_create(desc, strategy_table, pattern_params, block_q=0, block_k=0, workspace=None, stream=None,
-                    dense_split=0, text_tokens=None) -> Plan:
+                    dense_split=0, text_tokens=None, single_launch=0) -> Plan:
     """workspace: a torch uint8/int32 CUDA tensor of at least svd_plan_workspace_bytes
     bytes, or None for a host-only plan (inspection, no launches).  text_tokens:
     the plan option; None reads it from the "text_tokens" key of the sparse
     heads' parameter dicts."""
     m = _Marshalled(strategy_table, pattern_params)
-    opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens))
+    opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens),
+                      single_launch)
     handle = C.c_void_p()
     ws_ptr = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0

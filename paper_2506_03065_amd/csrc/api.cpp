@@ -5,6 +5,7 @@
 // of Section 4.2 (one fused launch per mode present in the layer).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -41,6 +42,12 @@ struct svd_plan {
   // that computes the text rows of its heads, and the byte offset of its scratch
   std::vector<int> text_split;
   std::vector<size_t> text_partial_offset;
+  // single launch (plan option): the segments of the layer kernel, heaviest first, and
+  // the byte offset of its queue positions in the workspace
+  bool single_launch = false;
+  svd::LayerLaunch layer{};
+  size_t counters_offset = 0;
+  int n_cu = 0;
   ~svd_plan() {
     for (int i = 0; i < kSideStreams; ++i) {
       if (side[i]) (void)hipStreamDestroy(side[i]);
@@ -66,8 +73,12 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
   if (opt && opt->dense_split < 0) return SVD_ERR_UNSUPPORTED;
   if (opt && opt->text_tokens < 0) return SVD_ERR_PARAMS;
   *native = (*bq == kq && *bk == kk);
+  if (opt && (opt->single_launch < 0 || opt->single_launch > 2)) return SVD_ERR_PARAMS;
+  if (opt && opt->single_launch == 1 && !*native) return SVD_ERR_UNSUPPORTED;
   return SVD_OK;
 }
+
+bool wants_single_launch(const svd_plan_options* opt) { return opt && opt->single_launch == 1; }
 
 // The small query tile is offered to the band groups only when the caller left
 // the block shape to the library (an explicit shape applies to every group).
@@ -142,9 +153,17 @@ int choose_text_split(const Plan& p, const svd::Group& g, int n_cu) {
 // Workspace = [compiled lists | padding to 256 bytes | scratch of the dense split |
 // scratch of the text-row launches, one area per sparse group].
 size_t workspace_need(const Plan& p, int dense_split, int n_cu, size_t* partial_offset, std::vector<int>* text_split,
-                      std::vector<size_t>* text_offset) {
+                      std::vector<size_t>* text_offset, bool single_launch = false, size_t* counters_offset = nullptr) {
   size_t end = p.ws_image.size() * sizeof(int32_t);
   if (partial_offset) *partial_offset = 0;
+  if (single_launch) {
+    // no split anywhere; the queue positions of the layer kernel follow the lists
+    if (text_split) text_split->assign(p.groups.size(), 1);
+    if (text_offset) text_offset->assign(p.groups.size(), 0);
+    const size_t off = align_up(end, 256);
+    if (counters_offset) *counters_offset = off;
+    return off + 256;
+  }
   if (dense_split > 1) {
     const size_t off = align_up(end, 256);
     if (partial_offset) *partial_offset = off;
@@ -270,13 +289,63 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   bool native;
   if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
   Plan tmp;
+  const bool single = wants_single_launch(options);
   if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk,
-                                        options ? options->text_tokens : 0, small_block_q(*desc, options), &tmp))
+                                        options ? options->text_tokens : 0, small_block_q(*desc, options), &tmp, single))
     return st;
   const int n_cu = device_compute_units();
-  const int split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), n_cu, options) : 1;
-  *bytes = workspace_need(tmp, split, native ? n_cu : 0, nullptr, nullptr, nullptr);
+  const int split = native && !single ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), n_cu, options) : 1;
+  *bytes = workspace_need(tmp, split, native ? n_cu : 0, nullptr, nullptr, nullptr, single, nullptr);
   return SVD_OK;
+}
+
+// The segments of the single-launch path, heaviest items first: the dense group,
+// the text rows of the sparse groups (dense items over every key), then the
+// sparse groups by their average number of key tiles per item, the zero fill last.
+static void build_layer_segments(svd_plan* sp) {
+  const Plan& p = sp->p;
+  const int bq = svd::layer_block_q(p.desc.D);
+  const int n_qb = (p.desc.L + bq - 1) / bq;
+  svd::LayerLaunch& lay = sp->layer;
+  lay = svd::LayerLaunch{};
+  struct Cand {
+    svd::LayerSegment seg;
+    double cost;
+  };
+  std::vector<Cand> cands;
+  auto segment = [&](const svd::Group& g, int kind, int n_q_blocks) {
+    svd::LayerSegment sgm{};
+    sgm.kind = kind;
+    sgm.n_q_blocks = n_q_blocks;
+    sgm.n_heads = static_cast<int>(g.heads.size());
+    sgm.n_items = n_q_blocks * sgm.n_heads * p.desc.B;
+    sgm.heads = static_cast<int>(g.ws_heads);
+    sgm.list_id = static_cast<int>(g.ws_list_id);
+    sgm.list_table = static_cast<int>(g.ws_list_table);
+    return sgm;
+  };
+  for (const svd::Group& g : p.groups) {
+    if (g.mode == SVD_DENSE) {
+      cands.push_back({segment(g, svd::SEG_DENSE, n_qb), 2.0 * p.n_k_blocks + 1.0});
+    } else if (g.mode == SVD_SKIP) {
+      cands.push_back({segment(g, svd::SEG_ZERO, n_qb), 0.0});
+    } else if (g.mode == SVD_VSTRIPE) {
+      double tiles = 0.0;
+      for (size_t t = 0; t < g.heads.size(); ++t) tiles += static_cast<double>(g.columns[g.list_id[t]].cols.size()) / p.block_k;
+      cands.push_back({segment(g, svd::SEG_GATHER, n_qb), tiles / g.heads.size()});
+    } else {
+      double tiles = 0.0;
+      for (size_t t = 0; t < g.heads.size(); ++t) tiles += static_cast<double>(g.bands[g.list_id[t]].kv_block_idx.size());
+      cands.push_back({segment(g, g.rearranged ? svd::SEG_PBAND : svd::SEG_BAND, g.n_q_blocks),
+                       tiles / g.heads.size() / g.n_q_blocks});
+    }
+    if (has_text_rows(p, g)) cands.push_back({segment(g, svd::SEG_DENSE, p.text_tokens / bq), 2.0 * p.n_k_blocks});
+  }
+  std::stable_sort(cands.begin(), cands.end(), [](const Cand& a, const Cand& b) { return a.cost > b.cost; });
+  lay.n_segments = 0;
+  for (const Cand& c : cands)
+    if (lay.n_segments < svd::kMaxSegments) lay.seg[lay.n_segments++] = c.seg;
+  lay.counters = reinterpret_cast<int*>(static_cast<char*>(p.device_workspace) + sp->counters_offset);
 }
 
 // with_side_streams = false: the plan creates no streams or events of its own and
@@ -294,9 +363,10 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
   svd_plan* sp = new (std::nothrow) svd_plan();
   if (!sp) return SVD_ERR_HIP;
   svd_status st = SVD_OK;
+  const bool single = wants_single_launch(options);
   try {
     st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, options ? options->text_tokens : 0,
-                           small_block_q(*desc, options), &sp->p);
+                           small_block_q(*desc, options), &sp->p, single);
   } catch (...) {
     st = SVD_ERR_UNSUPPORTED;
   }
@@ -306,9 +376,13 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
   }
   if (device_workspace) {
     const int n_cu_ws = device_compute_units();
-    sp->dense_split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), n_cu_ws, options) : 1;
+    sp->dense_split = native && !single ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), n_cu_ws, options) : 1;
     const size_t need = workspace_need(sp->p, sp->dense_split, native ? n_cu_ws : 0, &sp->partial_offset,
-                                       &sp->text_split, &sp->text_partial_offset);
+                                       &sp->text_split, &sp->text_partial_offset, single, &sp->counters_offset);
+    if (single && n_cu_ws < 1) {   // the layer kernel is sized from the compute-unit count
+      delete sp;
+      return SVD_ERR_HIP;
+    }
     if (workspace_bytes < need || !aligned16(device_workspace)) {
       delete sp;
       return SVD_ERR_WORKSPACE;
@@ -322,9 +396,14 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
     }
     sp->p.device_workspace = device_workspace;
     sp->p.launchable = native;
+    if (single) {
+      sp->single_launch = true;
+      sp->n_cu = n_cu_ws;
+      build_layer_segments(sp);
+    }
     // SVD_NO_FORK=1 in the environment keeps every group on the caller's stream
     const char* no_fork = std::getenv("SVD_NO_FORK");
-    if (native && with_side_streams && !(no_fork && no_fork[0] == '1')) {
+    if (native && with_side_streams && !single && !(no_fork && no_fork[0] == '1')) {
       bool ok = hipEventCreateWithFlags(&sp->fork, hipEventDisableTiming) == hipSuccess;
       for (int i = 0; ok && i < kSideStreams; ++i)
         ok = hipStreamCreateWithFlags(&sp->side[i], hipStreamNonBlocking) == hipSuccess &&
@@ -371,6 +450,12 @@ svd_status svd_plan_destroy(svd_plan* plan) {
 svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split) {
   if (!plan || !dense_split) return SVD_ERR_NULL;
   *dense_split = plan->dense_split;
+  return SVD_OK;
+}
+
+svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch) {
+  if (!plan || !single_launch) return SVD_ERR_NULL;
+  *single_launch = plan->single_launch ? 1 : 0;
   return SVD_OK;
 }
 
@@ -592,6 +677,12 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
   if (svd_status st = check_launchable(plan, q, k, v, out, static_cast<hipStream_t>(hip_stream))) return st;
   const Plan& p = plan->p;
   hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
+  if (plan->single_launch) {
+    svd::LayerLaunch lay = plan->layer;
+    lay.a = base_launch(p.desc, q, k, v, out);
+    lay.a.ws = static_cast<const int*>(p.device_workspace);
+    return svd::launch_layer(lay, plan->n_cu, main_stream) == hipSuccess ? SVD_OK : SVD_ERR_HIP;
+  }
   // heaviest first: dense, then the band groups, the gathers, and the zero fill
   static const int order[5] = {SVD_DENSE, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE, SVD_SKIP};
   constexpr int kMaxGroups = 6;   // the five modes plus the rearranged multi-diagonal group

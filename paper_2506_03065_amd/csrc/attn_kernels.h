@@ -64,6 +64,39 @@ struct AttnLaunch {
   float* partial;        // device: partial_floats(...) floats, or nullptr
 };
 
+// The whole layer in ONE launch (Section 4.2: heads that share a mode are fused;
+// here all groups are): a grid of resident work-groups, two of four waves per
+// compute unit, pulls items off eight work queues, one per XCD, heaviest segment
+// first.  A segment is one group's items in the order of a grouped launch (query
+// tiles of a head consecutive), or the text rows of a sparse group as dense
+// items; queue x holds the x-th eighth of every segment, so the query tiles of a
+// head stay on one XCD.  A work-group drains its own XCD's queue and then the
+// others', and leaves when all are empty.  Every item runs on the small query
+// tile (128 rows) and dense heads are not split: the queues fill the tail that
+// a launch per group pays for.
+constexpr int kMaxSegments = 12;
+enum { SEG_DENSE = 0, SEG_BAND = 1, SEG_GATHER = 2, SEG_PBAND = 3, SEG_ZERO = 4 };
+struct LayerSegment {
+  int kind;          // SEG_*
+  int n_items;       // n_q_blocks * n_heads * B
+  int n_q_blocks;    // query tiles of 128 rows per head in this segment
+  int n_heads;
+  int heads;         // word offsets into the plan workspace: head ids of the group,
+  int list_id;       //   the list of every head,
+  int list_table;    //   the group's list records
+  int pad;
+};
+struct LayerLaunch {
+  AttnLaunch a;                      // tensors, shape, strides, scale, ws; the per-group fields are filled per item
+  LayerSegment seg[kMaxSegments];    // heaviest first
+  int n_segments;
+  int* counters;                     // device: 8 queue positions, zeroed by a fill kernel ahead of the layer kernel
+};
+constexpr int kLayerCounterWords = 8;
+// Query rows per item of the single-launch path (the small query tile).
+int layer_block_q(int D);
+hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t stream);
+
 // Floats of scratch one split launch needs (n_items counts chunks).
 size_t partial_floats(int D, int n_items);
 

@@ -85,8 +85,13 @@ __device__ __forceinline__ int swz_v(int row) {
 template <int N>
 using Int = std::integral_constant<int, N>;
 
+// One item = one tile of BR query rows of one head (and, for split dense launches,
+// one chunk of the key range): everything a work-group does between picking the
+// item and storing its rows.  smem: 4 * BC * D * 2 bytes of LDS, 16-byte aligned.
+// Every wave of the work-group calls it with the same item; a return leaves no
+// wave behind at a barrier (all returns are work-group uniform).
 template <int D, int NW, int QB, int BC, int OCC, int MODE>
-__global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch p) {
+__device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, unsigned char* const smem) {
   constexpr bool kBand = MODE == MODE_BAND || MODE == MODE_PBAND;        // walks a CSR list of key tiles
   constexpr bool kIndirect = MODE == MODE_GATHER || MODE == MODE_PBAND;   // key rows come through an index list
   constexpr int NT = NW * 64;
@@ -101,14 +106,9 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
   constexpr int TILE_BYTES = BC * D * 2;
   constexpr int ROW_BYTES = D * 2;
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE_BYTES];
   unsigned char* const sK = smem;                    // [2][BC][D] bf16, swizzled
   unsigned char* const sV = smem + 2 * TILE_BYTES;   // [2][BC][D] bf16, swizzled
 
-  // ---- which tile of which head (XCD-aware: consecutive items share an XCD) ----
-  const int per_xcd = (p.n_items + 7) >> 3;
-  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (item >= p.n_items) return;
   const int qblk = item % p.n_q_blocks;
   const int chunk = (item / p.n_q_blocks) % p.split;   // key-range chunk (dense launches only)
   const int hb = item / p.n_q_blocks / p.split;
@@ -641,6 +641,18 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch
 }
 
 
+// One launch per group: work-group = one item.
+template <int D, int NW, int QB, int BC, int OCC, int MODE>
+__global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_kernel(const AttnLaunch p) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BC * D * 2];
+  // which tile of which head (XCD-aware: consecutive items share an XCD)
+  const int per_xcd = (p.n_items + 7) >> 3;
+  const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (item >= p.n_items) return;
+  attn_item<D, NW, QB, BC, OCC, MODE>(p, item, smem);
+}
+
+
 // Merge of a split dense launch: work-group = (query tile, head, batch entry,
 // slice of RPS accumulator rows), same thread-to-element mapping as
 // attn_fwd_kernel.  Chunks are folded one by one with the online-softmax rule:
@@ -710,6 +722,83 @@ __global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
   }
 }
 
+// ---- the whole layer in one launch ----
+
+__global__ void __launch_bounds__(64) reset_counters_kernel(int* counters) {
+  if (threadIdx.x < kLayerCounterWords) counters[threadIdx.x] = 0;
+}
+
+// Zero fill of one 128-row tile of a skipped head (M_1).
+template <int D>
+__device__ __forceinline__ void zero_item(const AttnLaunch& p, const int item) {
+  constexpr int BR = 128, CH = D / 8;
+  const int qblk = item % p.n_q_blocks;
+  const int hb = item / p.n_q_blocks;
+  const int hg = hb % p.n_heads, b = hb / p.n_heads;
+  const int head = p.heads[hg];
+  __bf16* O = p.out + (int64_t)b * p.stride_b + (int64_t)head * p.stride_h;
+  for (int c = threadIdx.x; c < BR * CH; c += blockDim.x) {
+    const int row = qblk * BR + c / CH;
+    if (row < p.L) *reinterpret_cast<uint4*>(O + (int64_t)row * p.stride_l + (c % CH) * 8) = make_uint4(0, 0, 0, 0);
+  }
+}
+
+template <int D, int BC>
+__global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp) {
+  constexpr int NW = 4, QB = 1, OCC = 2;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BC * D * 2];
+  __shared__ int pick[2];
+  const int home = blockIdx.x & 7;   // work-groups are dealt to the XCDs in turn
+  int probe = 0;                     // queues this work-group has found empty (thread 0 only)
+  for (;;) {
+    if (threadIdx.x == 0) {
+      int seg = -1, item = 0;
+      while (probe < 8) {
+        const int x = (home + probe) & 7;
+        int rest = atomicAdd(lp.counters + x, 1);
+        for (int s = 0; s < lp.n_segments; ++s) {
+          const int n = lp.seg[s].n_items, per = (n + 7) >> 3;
+          int cnt = n - x * per;
+          cnt = cnt < 0 ? 0 : (cnt > per ? per : cnt);
+          if (rest < cnt) {
+            seg = s;
+            item = x * per + rest;
+            break;
+          }
+          rest -= cnt;
+        }
+        if (seg >= 0) break;
+        ++probe;   // queue x is empty for good (positions only grow)
+      }
+      pick[0] = seg;
+      pick[1] = item;
+    }
+    __syncthreads();
+    const int seg = __builtin_amdgcn_readfirstlane(pick[0]);
+    const int item = __builtin_amdgcn_readfirstlane(pick[1]);
+    if (seg < 0) return;   // every queue is empty: the whole work-group leaves
+    const LayerSegment sg = lp.seg[seg];
+    AttnLaunch a = lp.a;
+    a.n_q_blocks = sg.n_q_blocks;
+    a.n_heads = sg.n_heads;
+    a.n_items = sg.n_items;
+    a.heads = lp.a.ws + sg.heads;
+    a.list_id = lp.a.ws + sg.list_id;
+    a.list_table = sg.list_table;
+    a.split = 1;
+    a.partial = nullptr;
+    switch (sg.kind) {
+      case SEG_DENSE: attn_item<D, NW, QB, BC, OCC, MODE_DENSE>(a, item, smem); break;
+      case SEG_BAND: attn_item<D, NW, QB, BC, OCC, MODE_BAND>(a, item, smem); break;
+      case SEG_GATHER: attn_item<D, NW, QB, BC, OCC, MODE_GATHER>(a, item, smem); break;
+      case SEG_PBAND: attn_item<D, NW, QB, BC, OCC, MODE_PBAND>(a, item, smem); break;
+      default: zero_item<D>(a, item); break;
+    }
+    // the next pick overwrites `pick`, the next item the LDS tiles: everyone must be done with both
+    __syncthreads();
+  }
+}
+
 template <int D, int NW, int QB, int BC, int OCC>
 hipError_t launch_mode(const AttnLaunch& p, int mode, hipStream_t stream) {
   const int per_xcd = (p.n_items + 7) / 8;
@@ -776,6 +865,32 @@ hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, b
     return launch_mode<128, Tile128::NW, Tile128::QB, Tile128::BC, Tile128::OCC>(p, mode, stream);
   if (p.D == 64) return launch_mode<64, Tile64::NW, Tile64::QB, Tile64::BC, Tile64::OCC>(p, mode, stream);
   return hipErrorInvalidValue;
+}
+
+int layer_block_q(int D) { return kernel_small_block_q(D); }
+
+hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t stream) {
+  if (p.n_segments < 1) return hipSuccess;
+  if (p.n_segments > kMaxSegments || !p.counters || n_compute_units < 1) return hipErrorInvalidValue;
+  static_assert(Tile128s::NW == 4 && Tile64s::NW == 4 && Tile128s::QB == 1 && Tile64s::QB == 1,
+                "the layer kernel runs the small query tile: four waves of 32 rows");
+  long long total = 0;
+  for (int s = 0; s < p.n_segments; ++s) {
+    if (p.seg[s].n_items < 0 || p.seg[s].kind < SEG_DENSE || p.seg[s].kind > SEG_ZERO) return hipErrorInvalidValue;
+    total += p.seg[s].n_items;
+  }
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, stream, p.counters);
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  // two resident work-groups per compute unit, a multiple of eight so that every XCD gets its share
+  long long groups = 2LL * n_compute_units;
+  if (groups > total) groups = total;
+  groups = (groups + 7) / 8 * 8;
+  const dim3 grid((unsigned)groups), block(256);
+  if (p.a.D == 128) hipLaunchKernelGGL((attn_layer_kernel<128, Tile128s::BC>), grid, block, 0, stream, p);
+  else if (p.a.D == 64) hipLaunchKernelGGL((attn_layer_kernel<64, Tile64s::BC>), grid, block, 0, stream, p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
 }
 
 size_t partial_floats(int D, int n_items) {

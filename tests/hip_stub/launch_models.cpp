@@ -210,6 +210,53 @@ hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, b
   return model_attention(p, nullptr, mode, stream, small_q);
 }
 
+int layer_block_q(int D) { return kernel_small_block_q(D); }
+
+// The single-launch path: every item of every segment, on the small query tile; the queue positions.
+hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t stream) {
+  if (p.n_segments < 1) return hipSuccess;
+  if (p.n_segments > kMaxSegments || !p.counters || n_compute_units < 1) return hipErrorInvalidValue;
+  stub::note_launch(stream, "reset_counters_kernel");
+  touch_write(p.counters, kLayerCounterWords * sizeof(int), "queue positions", 0x00);
+  stub::note_launch(stream, "attn_layer_kernel");
+  const int BR = layer_block_q(p.a.D);
+  for (int s = 0; s < p.n_segments; ++s) {
+    const LayerSegment& sg = p.seg[s];
+    if (sg.kind < SEG_DENSE || sg.kind > SEG_ZERO || sg.n_items < 0) return hipErrorInvalidValue;
+    if (s > 0 && sg.kind == SEG_DENSE && p.seg[s - 1].kind != SEG_DENSE)
+      stub::violation("segments are not heaviest first: a dense segment follows a lighter one");
+    AttnLaunch a = p.a;
+    a.n_q_blocks = sg.n_q_blocks;
+    a.n_heads = sg.n_heads;
+    a.n_items = sg.n_items;
+    a.heads = p.a.ws + sg.heads;
+    a.list_id = p.a.ws + sg.list_id;
+    a.list_table = sg.list_table;
+    a.split = 1;
+    a.partial = nullptr;
+    if (sg.n_items != sg.n_q_blocks * sg.n_heads * a.B) stub::violation("segment %d: n_items does not match its item space", s);
+    for (int item = 0; item < sg.n_items; ++item) {
+      if (sg.kind != SEG_ZERO) {
+        const int mode = sg.kind == SEG_DENSE ? MODE_DENSE : sg.kind == SEG_BAND ? MODE_BAND
+                         : sg.kind == SEG_GATHER ? MODE_GATHER : MODE_PBAND;
+        model_item(a, nullptr, mode, true, item);
+        continue;
+      }
+      const int qblk = item % a.n_q_blocks, hb = item / a.n_q_blocks;
+      const int hg = hb % a.n_heads, b = hb / a.n_heads;
+      const int head = read_word(a.heads + hg, "heads");
+      if (head < 0 || head >= a.H || b >= a.B) {
+        stub::violation("zero item %d decodes to head %d, batch entry %d", item, head, b);
+        continue;
+      }
+      for (int r = 0; r < BR; ++r)
+        if (qblk * BR + r < a.L)
+          touch_write(const_cast<__bf16*>(row_of(a.out, a, b, head, qblk * BR + r)), (size_t)a.D * 2, "out row (zero item)", 0x00, true);
+    }
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream) {
   if (p.split <= 1 || p.n_items <= 0) return hipSuccess;
   if (!p.partial) return hipErrorInvalidValue;

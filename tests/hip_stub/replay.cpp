@@ -147,6 +147,39 @@ void run_layer(const Layer& l) {
     expect(svd_plan_destroy(plan) == SVD_OK, l, "svd_plan_destroy");
     stub::device_free(ws);
   }
+  {
+    // the same layer as ONE launch: eagerly, and under capture (refused with a text prefix)
+    svd_plan_options one = opt;
+    one.single_launch = 1;
+    size_t bytes = 0;
+    int st = svd_plan_workspace_bytes(&desc, l.table.data(), l.params.data(), &one, &bytes);
+    expect(st == SVD_OK, l, "svd_plan_workspace_bytes (single launch)", st);
+    void* ws = stub::device_alloc(bytes > g_short ? bytes - g_short : 1);
+    svd_plan* plan = nullptr;
+    st = svd_plan_create(&plan, &desc, l.table.data(), l.params.data(), &one, ws, bytes, nullptr);
+    expect(st == SVD_OK, l, "svd_plan_create (single launch)", st);
+    if (st == SVD_OK) {
+      int32_t is_single = 0;
+      svd_plan_single_launch(plan, &is_single);
+      expect(is_single == 1, l, "the plan reports the single launch");
+      const long before = stub::launches();
+      st = svd_attn_forward_planned(plan, q, k, v, out, nullptr);
+      expect(st == SVD_OK, l, "single-launch forward", st);
+      expect(stub::launches() == before + 2, l, "a single-launch forward is two launches (fill + layer kernel)");
+      hipStream_t side = stub::create_stream();
+      stub::begin_capture(side);
+      st = svd_attn_forward_planned(plan, q, k, v, out, side);
+      expect(l.text > 0 ? st == SVD_ERR_UNSUPPORTED : st == SVD_OK, l, "single-launch forward under capture", st);
+      expect(stub::end_capture(side) == hipSuccess, l, "capture ends");
+      stub::destroy_stream(side);
+      if (l.tensors) {
+        st = svd_attn_forward_fp8(plan, q, k, v, out, ws8, bytes8, nullptr);   // the FP8 path runs such a plan group by group
+        expect(st == SVD_OK, l, "fp8 forward with a single-launch plan", st);
+      }
+      expect(svd_plan_destroy(plan) == SVD_OK, l, "svd_plan_destroy");
+    }
+    stub::device_free(ws);
+  }
   if (l.text == 0) {
     // the entry point that allocates nothing: a miss (copy of the lists into the library's buffer),
     // a hit, and a hit under capture; a miss under capture is refused
