@@ -385,9 +385,11 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     desc = svd.desc_of(q)
 
     t0 = time.perf_counter()
-    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params),
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params,
+                                                  single_launch=args.single_launch),
                      dtype=torch.uint8, device=dev)
-    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws,
+                               single_launch=args.single_launch)
     plan_ms = (time.perf_counter() - t0) * 1e3
     work = plan.work()
 
@@ -413,6 +415,23 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ms_per_step = start.elapsed_time(stop) / args.steps
+
+    # ---- the same layer through the other launch form (single launch <-> grouped launches) ----
+    other = None
+    if not fp8:
+        alt_single = 0 if plan.single_launch() else 1
+        ws_alt = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params,
+                                                          single_launch=alt_single or 2),
+                             dtype=torch.uint8, device=dev)
+        plan_alt = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws_alt,
+                                       single_launch=alt_single or 2)
+        alt_ms = gpu_time_ms(lambda: svd.svd_attn_forward_planned(plan_alt, q, k, v, out), args.steps, args.warmup, torch)
+        other = {"form": "single launch" if plan_alt.single_launch() else "grouped launches",
+                 "ms": round(alt_ms, 4),
+                 "computed_tile_frac_of_bf16_peak": round(plan_alt.work()["computed_flops"] / 1e9 / alt_ms / BF16_MFMA_PEAK_TFLOPS, 4),
+                 "dense_split": plan_alt.dense_split()}
+        plan_alt.close()
+        del ws_alt
 
     # ---- per-group kernels (one launch each), HIP events on the launch stream ----
     groups = []
@@ -476,6 +495,7 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
                    "text_tokens_with_dense_borders": text, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
+                   "launch_form": "single launch" if plan.single_launch() else "grouped launches",
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
         "wall_ms_per_step": round(wall_ms, 4),
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),
@@ -494,6 +514,7 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
         "speedup_vs_dense_kernel": round(dense_ms / ms_per_step, 3) if dense_ms else None,
         "plan_create_ms": round(plan_ms, 2),
         "input_gen_s": round(gen_s, 1),
+        "other_launch_form": other,
         "groups": groups,
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -509,7 +530,7 @@ def brief(rec):
     """The sub-record of a workload that is not the headline."""
     keys = ("config", "ms_per_step", "steps", "computed_tile_tflops", "computed_tile_frac_of_bf16_peak",
             "computed_tile_frac_of_measured_mfma_peak", "dense_all_heads_ms", "speedup_vs_dense_kernel",
-            "flop_reduction_block_level", "flop_reduction_element_level", "groups", "roofline", "cpu_baseline",
+            "flop_reduction_block_level", "flop_reduction_element_level", "other_launch_form", "groups", "roofline", "cpu_baseline",
             "check_vs_oracle", "plan_create_ms")
     out = {"ms": rec["ms_per_step"]}
     out.update({k: rec[k] for k in keys if k in rec})
@@ -539,6 +560,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=None,
                     help="budget of the CPU-oracle leg (0 = skip; default 25, with --workload all 20 for the headline "
                          "and 8 for each other workload)")
+    ap.add_argument("--single-launch", type=int, default=0, choices=[0, 1, 2],
+                    help="plan option single_launch: 0 = the library's choice, 1 = the whole layer as one launch, "
+                         "2 = one launch per mode group")
     ap.add_argument("--no-calibrate", action="store_true",
                     help="skip the calibration leg (matrix-instruction loop and streaming copy)")
     ap.add_argument("--copy-calibration", action="store_true",

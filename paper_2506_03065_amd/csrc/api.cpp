@@ -162,7 +162,7 @@ size_t workspace_need(const Plan& p, int dense_split, int n_cu, size_t* partial_
     if (text_offset) text_offset->assign(p.groups.size(), 0);
     const size_t off = align_up(end, 256);
     if (counters_offset) *counters_offset = off;
-    return off + 256;
+    return off + align_up(svd::kLayerCounterWords * sizeof(int32_t), 256);
   }
   if (dense_split > 1) {
     const size_t off = align_up(end, 256);

@@ -69,11 +69,12 @@ struct AttnLaunch {
 // compute unit, pulls items off eight work queues, one per XCD, heaviest segment
 // first.  A segment is one group's items in the order of a grouped launch (query
 // tiles of a head consecutive), or the text rows of a sparse group as dense
-// items; queue x holds the x-th eighth of every segment, so the query tiles of a
-// head stay on one XCD.  A work-group drains its own XCD's queue and then the
-// others', and leaves when all are empty.  Every item runs on the small query
-// tile (128 rows) and dense heads are not split: the queues fill the tail that
-// a launch per group pays for.
+// items; every segment has eight queues, queue x holding its x-th eighth, so the
+// query tiles of a head stay on one XCD.  Segment after segment a work-group
+// drains its own XCD's queue, then the other XCDs', and moves on; it leaves after
+// the last segment.  Every item runs on the small query tile (128 rows) and
+// dense heads are not split: the next segment fills the tail that a launch per
+// group pays for.
 constexpr int kMaxSegments = 12;
 enum { SEG_DENSE = 0, SEG_BAND = 1, SEG_GATHER = 2, SEG_PBAND = 3, SEG_ZERO = 4 };
 struct LayerSegment {
@@ -90,9 +91,9 @@ struct LayerLaunch {
   AttnLaunch a;                      // tensors, shape, strides, scale, ws; the per-group fields are filled per item
   LayerSegment seg[kMaxSegments];    // heaviest first
   int n_segments;
-  int* counters;                     // device: 8 queue positions, zeroed by a fill kernel ahead of the layer kernel
+  int* counters;                     // device: kLayerCounterWords queue positions, zeroed by a fill kernel ahead of the layer kernel
 };
-constexpr int kLayerCounterWords = 8;
+constexpr int kLayerCounterWords = 8 * kMaxSegments;   // one queue position per (segment, XCD)
 // Query rows per item of the single-launch path (the small query tile).
 int layer_block_q(int D);
 hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t stream);

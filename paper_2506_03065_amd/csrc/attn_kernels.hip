@@ -85,6 +85,33 @@ __device__ __forceinline__ int swz_v(int row) {
 template <int N>
 using Int = std::integral_constant<int, N>;
 
+// Uniform values held in vector registers (arguments of a non-inlined function, words loaded
+// through a vector load) moved to scalar registers; a no-op on values that already are scalar.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+template <typename T>
+__device__ __forceinline__ T* uni(T* ptr) {
+  const unsigned long long u = (unsigned long long)ptr;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
+  return (T*)(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ int64_t uni(int64_t x) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)x);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)x >> 32));
+  return (int64_t)(((unsigned long long)hi << 32) | lo);
+}
+__device__ __forceinline__ float uni(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
+}
+// a pointer into the constant address space (the plan's lists), made scalar
+template <typename T>
+__device__ __forceinline__ const T __attribute__((address_space(4)))* uni_const(const T __attribute__((address_space(4)))* ptr) {
+  const unsigned long long u = (unsigned long long)(uintptr_t)ptr;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
+  return (const T __attribute__((address_space(4)))*)(uintptr_t)(((unsigned long long)hi << 32) | lo);
+}
+
 // One item = one tile of BR query rows of one head (and, for split dense launches,
 // one chunk of the key range): everything a work-group does between picking the
 // item and storing its rows.  smem: 4 * BC * D * 2 bytes of LDS, 16-byte aligned.
@@ -114,7 +141,7 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
   const int hb = item / p.n_q_blocks / p.split;
   const int hg = hb % p.n_heads;
   const int b = hb / p.n_heads;
-  const int head = p.heads ? p.heads[hg] : hg;
+  const int head = uni(p.heads ? p.heads[hg] : hg);   // scalar: the buffer resources of K and V are built from it
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -161,6 +188,16 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
       n_cols = rec[2];
     }
   }
+
+  // The list pointers and counts are uniform but may have been loaded through the vector
+  // memory path: as scalars, the list reads in the loop are scalar loads, which neither
+  // queue behind nor wait for the tile loads in flight.
+  entries = uni_const(entries);
+  runs = uni_const(runs);
+  cols = uni(cols);
+  n_tiles = uni(n_tiles);
+  n_cols = uni(n_cols);
+  t_base = uni(t_base);
 
   // ---- Q fragments: B operand of S^T = K Q^T (lane: query l32, 8 of 16 d) ----
   // Q is multiplied by log2(e) / sqrt(D) here, once, and rounded back to bf16:
@@ -724,7 +761,7 @@ __global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
 
 // ---- the whole layer in one launch ----
 
-__global__ void __launch_bounds__(64) reset_counters_kernel(int* counters) {
+__global__ void __launch_bounds__(128) reset_counters_kernel(int* counters) {
   if (threadIdx.x < kLayerCounterWords) counters[threadIdx.x] = 0;
 }
 
@@ -743,41 +780,53 @@ __device__ __forceinline__ void zero_item(const AttnLaunch& p, const int item) {
   }
 }
 
+// The item bodies of the layer kernel are real functions, not inlined: inlined
+// side by side into one kernel the four loop nests get in each other's way in the
+// register allocator (measured: the same band body ran 25 % slower than in a
+// kernel of its own); as callees each is allocated like the kernel it also is
+// elsewhere in this file.  Arguments of a callee travel in vector registers even
+// when they are uniform, so everything is made scalar again on entry.
+template <int D, int BC, int MODE>
+__device__ __attribute__((noinline)) void layer_item(const AttnLaunch av, const int item_v, const unsigned smem_v) {
+  AttnLaunch a;
+  a.q = uni(av.q);
+  a.k = uni(av.k);
+  a.v = uni(av.v);
+  a.out = uni(av.out);
+  a.B = uni(av.B);
+  a.H = uni(av.H);
+  a.L = uni(av.L);
+  a.D = uni(av.D);
+  a.stride_b = uni(av.stride_b);
+  a.stride_h = uni(av.stride_h);
+  a.stride_l = uni(av.stride_l);
+  a.n_q_blocks = uni(av.n_q_blocks);
+  a.n_heads = uni(av.n_heads);
+  a.n_items = uni(av.n_items);
+  a.heads = uni(av.heads);
+  a.list_id = uni(av.list_id);
+  a.ws = uni(av.ws);
+  a.list_table = uni(av.list_table);
+  a.scale_log2e = uni(av.scale_log2e);
+  a.split = 1;
+  a.partial = nullptr;
+  typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+  unsigned char* const smem = (unsigned char*)(lds_bytes)(uintptr_t)uni((int)smem_v);
+  attn_item<D, 4, 1, BC, 2, MODE>(a, uni(item_v), smem);
+}
+
 template <int D, int BC>
 __global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp) {
-  constexpr int NW = 4, QB = 1, OCC = 2;
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BC * D * 2];
-  __shared__ int pick[2];
+  __shared__ int pick;
+  typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+  const unsigned smem_addr = (unsigned)(uintptr_t)(lds_bytes)smem;
   const int home = blockIdx.x & 7;   // work-groups are dealt to the XCDs in turn
-  int probe = 0;                     // queues this work-group has found empty (thread 0 only)
-  for (;;) {
-    if (threadIdx.x == 0) {
-      int seg = -1, item = 0;
-      while (probe < 8) {
-        const int x = (home + probe) & 7;
-        int rest = atomicAdd(lp.counters + x, 1);
-        for (int s = 0; s < lp.n_segments; ++s) {
-          const int n = lp.seg[s].n_items, per = (n + 7) >> 3;
-          int cnt = n - x * per;
-          cnt = cnt < 0 ? 0 : (cnt > per ? per : cnt);
-          if (rest < cnt) {
-            seg = s;
-            item = x * per + rest;
-            break;
-          }
-          rest -= cnt;
-        }
-        if (seg >= 0) break;
-        ++probe;   // queue x is empty for good (positions only grow)
-      }
-      pick[0] = seg;
-      pick[1] = item;
-    }
-    __syncthreads();
-    const int seg = __builtin_amdgcn_readfirstlane(pick[0]);
-    const int item = __builtin_amdgcn_readfirstlane(pick[1]);
-    if (seg < 0) return;   // every queue is empty: the whole work-group leaves
-    const LayerSegment sg = lp.seg[seg];
+  // Segment after segment, heaviest first; inside a segment a work-group first drains
+  // its own XCD's eighth, then the other XCDs' eighths.  Every queue position only
+  // grows, so every loop below ends, and all waves of a work-group take the same path.
+  for (int s = 0; s < lp.n_segments; ++s) {
+    const LayerSegment sg = lp.seg[s];
     AttnLaunch a = lp.a;
     a.n_q_blocks = sg.n_q_blocks;
     a.n_heads = sg.n_heads;
@@ -785,17 +834,32 @@ __global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp
     a.heads = lp.a.ws + sg.heads;
     a.list_id = lp.a.ws + sg.list_id;
     a.list_table = sg.list_table;
-    a.split = 1;
-    a.partial = nullptr;
-    switch (sg.kind) {
-      case SEG_DENSE: attn_item<D, NW, QB, BC, OCC, MODE_DENSE>(a, item, smem); break;
-      case SEG_BAND: attn_item<D, NW, QB, BC, OCC, MODE_BAND>(a, item, smem); break;
-      case SEG_GATHER: attn_item<D, NW, QB, BC, OCC, MODE_GATHER>(a, item, smem); break;
-      case SEG_PBAND: attn_item<D, NW, QB, BC, OCC, MODE_PBAND>(a, item, smem); break;
-      default: zero_item<D>(a, item); break;
+    const int per = (sg.n_items + 7) >> 3;
+    for (int probe = 0; probe < 8; ++probe) {
+      const int x = (home + probe) & 7;
+      int cnt = sg.n_items - x * per;
+      cnt = cnt < 0 ? 0 : (cnt > per ? per : cnt);
+      if (cnt == 0) continue;
+      for (;;) {
+        if (threadIdx.x == 0) pick = atomicAdd(lp.counters + s * 8 + x, 1);
+        __syncthreads();
+        const int pos = __builtin_amdgcn_readfirstlane(pick);
+        if (pos >= cnt) {
+          __syncthreads();   // the next pick overwrites `pick`
+          break;
+        }
+        const int item = x * per + pos;
+        switch (sg.kind) {
+          case SEG_DENSE: layer_item<D, BC, MODE_DENSE>(a, item, smem_addr); break;
+          case SEG_BAND: layer_item<D, BC, MODE_BAND>(a, item, smem_addr); break;
+          case SEG_GATHER: layer_item<D, BC, MODE_GATHER>(a, item, smem_addr); break;
+          case SEG_PBAND: layer_item<D, BC, MODE_PBAND>(a, item, smem_addr); break;
+          default: zero_item<D>(a, item); break;
+        }
+        // the next pick overwrites `pick`, the next item the LDS tiles: everyone must be done with both
+        __syncthreads();
+      }
     }
-    // the next pick overwrites `pick`, the next item the LDS tiles: everyone must be done with both
-    __syncthreads();
   }
 }
 
@@ -880,7 +944,8 @@ hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t s
     total += p.seg[s].n_items;
   }
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, stream, p.counters);
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(128), 0, stream, p.counters);
+  static_assert(kLayerCounterWords <= 128, "one thread per queue position");
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // two resident work-groups per compute unit, a multiple of eight so that every XCD gets its share
   long long groups = 2LL * n_compute_units;
