@@ -135,9 +135,11 @@ def run_stack(args, torch, np, svd, W, cpu_seconds=None, calib=None, dense_reps=
     t0 = time.perf_counter()
     plans, spaces = [], []
     for wl in layers:
-        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params),
+        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params,
+                                                      single_launch=args.single_launch),
                          dtype=torch.uint8, device=dev)
-        plans.append(svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws))
+        plans.append(svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws,
+                                         single_launch=args.single_launch))
         spaces.append(ws)
     plan_ms = (time.perf_counter() - t0) * 1e3
 
@@ -191,7 +193,8 @@ def run_stack(args, torch, np, svd, W, cpu_seconds=None, calib=None, dense_reps=
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8-e4m3 (fp32 accumulation)" if fp8 else "bf16",
         "data": "synthetic",
         "config": {"workload": "layer-stack (40 layers, Wan2.1-like shape)", "precision": args.precision, "B": wl0.B, "H": wl0.H, "L": wl0.L,
-                   "D": wl0.D, "dense_heads_first_last": [dense_heads[0], dense_heads[-1]]},
+                   "D": wl0.D, "dense_heads_first_last": [dense_heads[0], dense_heads[-1]],
+                   "launch_form": "layer kernel" if plans[0].single_launch() else "grouped launches"},
         "computed_tile_tflops": round(computed / 1e9 / ms_per_step, 1),
         "computed_tile_frac_of_bf16_peak": round(computed / 1e9 / ms_per_step / BF16_MFMA_PEAK_TFLOPS, 4),
         "dense_all_heads_ms": round(dense_ms * n_layers, 1),
@@ -451,6 +454,14 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[{dom['mode']} group]",
                 "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(dom["tflops"] / peak, 4),
                 "traffic": traffic, "traffic_source": traffic_source}
+    if plan.single_launch() and not fp8:
+        # the step IS the dominant kernel: the layer kernel (with the dense kernel's head start ahead of it, and
+        # the 5 us fill of the queue positions); algorithmic FLOPs = the plan's listed tiles
+        tf = work["computed_flops"] / 1e9 / ms_per_step
+        traffic, traffic_source = recorded_traffic(args.precision, wl.name, "layer")
+        roofline = {"bound": "mfma", "kernel": "attn_layer_kernel + attn_fwd_kernel[dense head start] (the whole step)",
+                    "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
+                    "traffic": traffic, "traffic_source": traffic_source}
     add_measured_peak(roofline, calib, fp8)
     bf16_ms = gpu_time_ms(step16, max(3, args.steps // 2), 1, torch) if fp8 else None
 
@@ -495,7 +506,7 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
                    "text_tokens_with_dense_borders": text, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
-                   "launch_form": "single launch" if plan.single_launch() else "grouped launches",
+                   "launch_form": "layer kernel (single launch, dense head start by default)" if plan.single_launch() else "grouped launches",
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
         "wall_ms_per_step": round(wall_ms, 4),
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),
@@ -560,9 +571,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=None,
                     help="budget of the CPU-oracle leg (0 = skip; default 25, with --workload all 20 for the headline "
                          "and 8 for each other workload)")
-    ap.add_argument("--single-launch", type=int, default=0, choices=[0, 1, 2],
+    ap.add_argument("--single-launch", type=int, default=0, choices=[0, 1, 2, 3],
                     help="plan option single_launch: 0 = the library's choice, 1 = the whole layer as one launch, "
-                         "2 = one launch per mode group")
+                         "2 = one launch per mode group, 3 = one launch with a dense head start")
     ap.add_argument("--no-calibrate", action="store_true",
                     help="skip the calibration leg (matrix-instruction loop and streaming copy)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -131,14 +131,25 @@ typedef struct {
  * of four waves per compute unit) pull (group, head, query tile) items off eight
  * work queues, one per XCD, heaviest group first, and move on to the other
  * queues when their own is empty, so no group pays for a partly filled last
- * round.  Every item runs on the 128-row query tile, dense heads are not split
- * (dense_split is ignored), text rows of a text prefix are items of the dense
+ * round.  Every item runs on the 128-row query tile, dense heads are not split,
+ * text rows of a text prefix are items of the dense
  * kind, and nothing is forked.  The queue positions are eight words of the plan
  * workspace that a small fill kernel zeroes ahead of the layer kernel (two
  * launches in all; no memset, so the call can be captured).  Results are
  * bit-identical to the grouped launches of a plan with dense_split = 1.
- * 0 = the library's choice (grouped launches), 2 = grouped launches.  Needs the
- * kernels' block shape (SVD_ERR_UNSUPPORTED with an explicit other shape). */
+ * 3 = the single launch with a DENSE HEAD START: as many whole rounds of dense
+ * items as there are (one work-group per compute unit and round, none partly
+ * filled) first go through the dense kernel on its 256-row tile, which reuses a
+ * K/V tile in LDS for twice as many rows; the rest of the dense group and
+ * everything else is the layer kernel's (three launches in all).  Same bits.
+ * 2 = grouped launches.  0 = the library's choice: form 3 for D = 128, grouped
+ * launches for D = 64 (there the 128-row tile costs the dense items more than
+ * the filled tails bring), and grouped launches whenever dense_split > 1 is
+ * forced, the block shape is not the kernels' or no device is present.  1 and 3
+ * need the kernels' block shape (SVD_ERR_UNSUPPORTED otherwise) and a device
+ * (SVD_ERR_HIP).  The split of the dense heads is still chosen and its scratch
+ * still part of the workspace: the FP8 forward pass and the per-group entry
+ * points run such a plan group by group. */
 typedef struct { int32_t block_q, block_k, dense_split, text_tokens, single_launch; } svd_plan_options;
 
 typedef struct svd_plan svd_plan;
@@ -172,8 +183,8 @@ svd_status svd_plan_destroy(svd_plan* plan);
  * 1 for host-only plans). */
 svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split);
 
-/* 1 when svd_attn_forward_planned runs this plan as one launch (plan option
- * single_launch), else 0. */
+/* 1 when svd_attn_forward_planned runs this plan through the layer kernel (plan
+ * option single_launch 1 or 3, or the library's choice), else 0. */
 svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch);
 
 /* Inspection of a compiled plan (host copies owned by the plan, valid until
@@ -397,8 +408,8 @@ svd_status svd_attn_forward_fp8_group(const svd_plan* plan, int32_t group, const
  * The published matrix peak assumes the peak clock; under load the power limit
  * grants less.  svd_probe_mfma runs a loop of nothing but the bf16 matrix
  * instruction of the attention kernels' two products (v_mfma_f32_32x32x16_bf16,
- * eight independent accumulators per wave, work_groups of 512 threads, two waves
- * per SIMD) and returns the FLOPs of the launch through *flops (HOST); timing is
+ * eight independent accumulators per wave, each with pseudo-random operands of
+ * its own, work_groups of 512 threads, two waves per SIMD) and returns the FLOPs of the launch through *flops (HOST); timing is
  * the caller's.  device_scratch: DEVICE, work_groups * 512 floats at least.
  * svd_probe_copy copies bytes (a multiple of 16) from src to dst (DEVICE, 16-byte
  * aligned, not overlapping) with one plain streaming kernel: bytes read and bytes

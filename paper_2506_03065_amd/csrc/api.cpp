@@ -45,6 +45,10 @@ struct svd_plan {
   // single launch (plan option): the segments of the layer kernel, heaviest first, and
   // the byte offset of its queue positions in the workspace
   bool single_launch = false;
+  // dense head start (plan option single_launch = 3): this many 256-row dense items, whole rounds of
+  // one work-group per compute unit, run through the dense kernel ahead of the layer kernel
+  int dense_head_start = 0;
+  const svd::Group* dense_group = nullptr;
   svd::LayerLaunch layer{};
   size_t counters_offset = 0;
   int n_cu = 0;
@@ -73,12 +77,24 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
   if (opt && opt->dense_split < 0) return SVD_ERR_UNSUPPORTED;
   if (opt && opt->text_tokens < 0) return SVD_ERR_PARAMS;
   *native = (*bq == kq && *bk == kk);
-  if (opt && (opt->single_launch < 0 || opt->single_launch > 2)) return SVD_ERR_PARAMS;
-  if (opt && opt->single_launch == 1 && !*native) return SVD_ERR_UNSUPPORTED;
+  if (opt && (opt->single_launch < 0 || opt->single_launch > 3)) return SVD_ERR_PARAMS;
+  if (opt && (opt->single_launch == 1 || opt->single_launch == 3) && !*native) return SVD_ERR_UNSUPPORTED;
   return SVD_OK;
 }
 
-bool wants_single_launch(const svd_plan_options* opt) { return opt && opt->single_launch == 1; }
+// How svd_attn_forward_planned runs the plan: 0 = a launch per group, 1 = the layer kernel alone, 3 = the layer
+// kernel after a dense head start.  The library's own choice: the layer kernel saves the partly filled last round
+// of every group (3-5 % of a layer) but runs dense items on the 128-row tile, which costs about 4 % of their rate at
+// D = 128 and 14 % at D = 64 (measured); the head start takes most of that back for the dense group.  So: head start
+// form at D = 128, grouped launches at D = 64 - and grouped launches whenever the caller forces a dense split or there
+// is no device to size the grid from.
+int layer_form(const svd_plan_options* opt, const svd_tensor_desc& d, bool native, int n_cu) {
+  const int asked = opt ? opt->single_launch : 0;
+  if (asked == 1 || asked == 3) return asked;
+  if (asked == 2 || !native || n_cu < 1) return 0;
+  if (opt && opt->dense_split > 1) return 0;
+  return d.D == 128 ? 3 : 0;
+}
 
 // The small query tile is offered to the band groups only when the caller left
 // the block shape to the library (an explicit shape applies to every group).
@@ -156,14 +172,6 @@ size_t workspace_need(const Plan& p, int dense_split, int n_cu, size_t* partial_
                       std::vector<size_t>* text_offset, bool single_launch = false, size_t* counters_offset = nullptr) {
   size_t end = p.ws_image.size() * sizeof(int32_t);
   if (partial_offset) *partial_offset = 0;
-  if (single_launch) {
-    // no split anywhere; the queue positions of the layer kernel follow the lists
-    if (text_split) text_split->assign(p.groups.size(), 1);
-    if (text_offset) text_offset->assign(p.groups.size(), 0);
-    const size_t off = align_up(end, 256);
-    if (counters_offset) *counters_offset = off;
-    return off + align_up(svd::kLayerCounterWords * sizeof(int32_t), 256);
-  }
   if (dense_split > 1) {
     const size_t off = align_up(end, 256);
     if (partial_offset) *partial_offset = off;
@@ -182,6 +190,11 @@ size_t workspace_need(const Plan& p, int dense_split, int n_cu, size_t* partial_
     if (text_offset) (*text_offset)[gi] = off;
     const int items = (p.text_tokens / p.block_q) * static_cast<int>(g.heads.size()) * p.desc.B * split;
     end = off + svd::partial_floats(p.desc.D, items) * sizeof(float);
+  }
+  if (single_launch) {   // the queue positions of the layer kernel come last
+    const size_t off = align_up(end, 256);
+    if (counters_offset) *counters_offset = off;
+    end = off + align_up(svd::kLayerCounterWords * sizeof(int32_t), 256);
   }
   return end;
 }
@@ -289,12 +302,14 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   bool native;
   if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
   Plan tmp;
-  const bool single = wants_single_launch(options);
+  const int n_cu = device_compute_units();
+  const int form = layer_form(options, *desc, native, n_cu);
+  const bool single = form != 0;
   if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk,
                                         options ? options->text_tokens : 0, small_block_q(*desc, options), &tmp, single))
     return st;
-  const int n_cu = device_compute_units();
-  const int split = native && !single ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), n_cu, options) : 1;
+  // (the split of the dense heads still serves the grouped launches of such a plan: the FP8 path, the per-group calls)
+  const int split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(tmp), n_cu, options) : 1;
   *bytes = workspace_need(tmp, split, native ? n_cu : 0, nullptr, nullptr, nullptr, single, nullptr);
   return SVD_OK;
 }
@@ -326,7 +341,17 @@ static void build_layer_segments(svd_plan* sp) {
   };
   for (const svd::Group& g : p.groups) {
     if (g.mode == SVD_DENSE) {
-      cands.push_back({segment(g, svd::SEG_DENSE, n_qb), 2.0 * p.n_k_blocks + 1.0});
+      svd::LayerSegment dense = segment(g, svd::SEG_DENSE, n_qb);
+      if (sp->dense_head_start > 0) {
+        // the head start covers the first items of the (batch, head, 256-row tile) order: whole heads, then
+        // the first tiles of one more; a 256-row tile is two 128-row items (one at a ragged end)
+        const int heads_done = sp->dense_head_start / p.n_q_blocks, tiles_done = sp->dense_head_start % p.n_q_blocks;
+        const int halves = 2 * tiles_done < n_qb ? 2 * tiles_done : n_qb;
+        dense.first_item = heads_done * n_qb + halves;
+        dense.n_items -= dense.first_item;
+        sp->dense_group = &g;
+      }
+      cands.push_back({dense, 2.0 * p.n_k_blocks + 1.0});
     } else if (g.mode == SVD_SKIP) {
       cands.push_back({segment(g, svd::SEG_ZERO, n_qb), 0.0});
     } else if (g.mode == SVD_VSTRIPE) {
@@ -363,7 +388,12 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
   svd_plan* sp = new (std::nothrow) svd_plan();
   if (!sp) return SVD_ERR_HIP;
   svd_status st = SVD_OK;
-  const bool single = wants_single_launch(options);
+  const int form = device_workspace ? layer_form(options, *desc, native, device_compute_units()) : 0;
+  if (device_workspace && options && (options->single_launch == 1 || options->single_launch == 3) && device_compute_units() < 1) {
+    delete sp;
+    return SVD_ERR_HIP;   // the layer kernel is sized from the compute-unit count
+  }
+  const bool single = form != 0;
   try {
     st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk, options ? options->text_tokens : 0,
                            small_block_q(*desc, options), &sp->p, single);
@@ -376,13 +406,10 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
   }
   if (device_workspace) {
     const int n_cu_ws = device_compute_units();
-    sp->dense_split = native && !single ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), n_cu_ws, options) : 1;
+    sp->dense_split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), n_cu_ws, options) : 1;
     const size_t need = workspace_need(sp->p, sp->dense_split, native ? n_cu_ws : 0, &sp->partial_offset,
                                        &sp->text_split, &sp->text_partial_offset, single, &sp->counters_offset);
-    if (single && n_cu_ws < 1) {   // the layer kernel is sized from the compute-unit count
-      delete sp;
-      return SVD_ERR_HIP;
-    }
+
     if (workspace_bytes < need || !aligned16(device_workspace)) {
       delete sp;
       return SVD_ERR_WORKSPACE;
@@ -399,6 +426,10 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
     if (single) {
       sp->single_launch = true;
       sp->n_cu = n_cu_ws;
+      if (form == 3) {
+        const long long items = static_cast<long long>(sp->p.n_q_blocks) * count_dense_heads(sp->p) * desc->B;
+        sp->dense_head_start = static_cast<int>(items / n_cu_ws * n_cu_ws);
+      }
       build_layer_segments(sp);
     }
     // SVD_NO_FORK=1 in the environment keeps every group on the caller's stream
@@ -678,6 +709,20 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
   const Plan& p = plan->p;
   hipStream_t main_stream = static_cast<hipStream_t>(hip_stream);
   if (plan->single_launch) {
+    if (plan->dense_head_start > 0) {
+      // whole rounds of the dense kernel on its 256-row tile; what is left of the dense group is in the queues
+      const svd::Group& g = *plan->dense_group;
+      const int* ws = static_cast<const int*>(p.device_workspace);
+      svd::AttnLaunch a = base_launch(p.desc, q, k, v, out);
+      a.n_q_blocks = g.n_q_blocks;
+      a.n_heads = static_cast<int>(g.heads.size());
+      a.n_items = plan->dense_head_start;
+      a.heads = ws + g.ws_heads;
+      a.list_id = ws + g.ws_list_id;
+      a.ws = ws;
+      a.list_table = static_cast<int>(g.ws_list_table);
+      if (svd::launch_attention(a, svd::MODE_DENSE, main_stream) != hipSuccess) return SVD_ERR_HIP;
+    }
     svd::LayerLaunch lay = plan->layer;
     lay.a = base_launch(p.desc, q, k, v, out);
     lay.a.ws = static_cast<const int*>(p.device_workspace);

@@ -79,13 +79,13 @@ constexpr int kMaxSegments = 12;
 enum { SEG_DENSE = 0, SEG_BAND = 1, SEG_GATHER = 2, SEG_PBAND = 3, SEG_ZERO = 4 };
 struct LayerSegment {
   int kind;          // SEG_*
-  int n_items;       // n_q_blocks * n_heads * B
+  int n_items;       // n_q_blocks * n_heads * B - first_item
   int n_q_blocks;    // query tiles of 128 rows per head in this segment
   int n_heads;
   int heads;         // word offsets into the plan workspace: head ids of the group,
   int list_id;       //   the list of every head,
   int list_table;    //   the group's list records
-  int pad;
+  int first_item;    // items below this one are computed elsewhere (the dense head start); n_items counts the rest
 };
 struct LayerLaunch {
   AttnLaunch a;                      // tensors, shape, strides, scale, ws; the per-group fields are filled per item

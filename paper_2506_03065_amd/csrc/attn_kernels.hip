@@ -830,7 +830,7 @@ __global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp
     AttnLaunch a = lp.a;
     a.n_q_blocks = sg.n_q_blocks;
     a.n_heads = sg.n_heads;
-    a.n_items = sg.n_items;
+    a.n_items = sg.n_items + sg.first_item;
     a.heads = lp.a.ws + sg.heads;
     a.list_id = lp.a.ws + sg.list_id;
     a.list_table = sg.list_table;
@@ -848,7 +848,7 @@ __global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp
           __syncthreads();   // the next pick overwrites `pick`
           break;
         }
-        const int item = x * per + pos;
+        const int item = sg.first_item + x * per + pos;
         switch (sg.kind) {
           case SEG_DENSE: layer_item<D, BC, MODE_DENSE>(a, item, smem_addr); break;
           case SEG_BAND: layer_item<D, BC, MODE_BAND>(a, item, smem_addr); break;
@@ -940,7 +940,8 @@ hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t s
                 "the layer kernel runs the small query tile: four waves of 32 rows");
   long long total = 0;
   for (int s = 0; s < p.n_segments; ++s) {
-    if (p.seg[s].n_items < 0 || p.seg[s].kind < SEG_DENSE || p.seg[s].kind > SEG_ZERO) return hipErrorInvalidValue;
+    if (p.seg[s].n_items < 0 || p.seg[s].first_item < 0 || p.seg[s].kind < SEG_DENSE || p.seg[s].kind > SEG_ZERO)
+      return hipErrorInvalidValue;
     total += p.seg[s].n_items;
   }
   if (total == 0) return hipSuccess;

@@ -12,7 +12,8 @@
 namespace svd {
 
 // Every wave runs `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16
-// (the instruction of the attention kernels' two products); returns the FLOPs of
+// (the instruction of the attention kernels' two products) on pseudo-random bf16
+// operands that differ from one instruction to the next; returns the FLOPs of
 // the launch through *flops.  out: device floats, 64 per wave (kept so that the
 // loop has a use).  work_groups of 512 threads, two waves per SIMD.
 hipError_t launch_mfma_probe(float* out, size_t out_floats, int iters, int work_groups, double* flops,

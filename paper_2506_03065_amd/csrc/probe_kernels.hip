@@ -9,14 +9,34 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kProbeAcc = 8;   // independent accumulators per wave: enough to cover the MFMA latency
 
+// Operand bits from a small integer hash: bf16 values of either sign with exponents around one and
+// random mantissas, different in every lane and for every accumulator, so that successive matrix
+// instructions see operands that differ (a loop over one constant operand pair toggles no input
+// and is granted the full clock; attention operands are not like that).
+__device__ __forceinline__ unsigned mix(unsigned x) {
+  x ^= x >> 16;
+  x *= 0x7feb352du;
+  x ^= x >> 15;
+  x *= 0x846ca68bu;
+  x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ __bf16 random_bf16(unsigned seed) {
+  const unsigned r = mix(seed);
+  const unsigned short bits = (unsigned short)(((r & 1u) << 15) | ((124u + ((r >> 1) & 3u)) << 7) | ((r >> 8) & 0x7fu));
+  return __builtin_bit_cast(__bf16, bits);
+}
+
 __global__ void __launch_bounds__(512, 2) mfma_probe_kernel(float* __restrict__ out, const int iters) {
-  const int lane = threadIdx.x & 63;
-  bf16x8 a, b;
+  const unsigned id = blockIdx.x * 512u + threadIdx.x;
+  bf16x8 a[kProbeAcc], b[kProbeAcc];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(float)((lane + i) & 3);
-    b[i] = (__bf16)(1.0f / (float)(1 + ((lane * 3 + i) & 7)));
-  }
+  for (int j = 0; j < kProbeAcc; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[j][i] = random_bf16(id * 131u + j * 17u + i);
+      b[j][i] = random_bf16(id * 257u + j * 29u + i + 7919u);
+    }
   f32x16 acc[kProbeAcc];
 #pragma unroll
   for (int j = 0; j < kProbeAcc; ++j)
@@ -24,7 +44,7 @@ __global__ void __launch_bounds__(512, 2) mfma_probe_kernel(float* __restrict__ 
     for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < kProbeAcc; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < kProbeAcc; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc[j], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -34,10 +54,19 @@ __global__ void __launch_bounds__(512, 2) mfma_probe_kernel(float* __restrict__ 
   out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
+// Four independent 16-byte loads per thread and step, then the four stores.
 __global__ void __launch_bounds__(256) copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                          const size_t n16) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
-    dst[i] = src[i];
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+    dst[i] = v0;
+    dst[i + stride] = v1;
+    dst[i + 2 * stride] = v2;
+    dst[i + 3 * stride] = v3;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 }  // namespace

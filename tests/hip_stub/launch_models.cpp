@@ -179,7 +179,9 @@ hipError_t model_attention(const AttnLaunch& p, const Fp8Launch* f8, int mode, h
   if (p.D != 64 && p.D != 128) return hipErrorInvalidValue;
   if (small_q && !f8 && mode != MODE_BAND && mode != MODE_PBAND) return hipErrorInvalidValue;
   if (small_q && f8 && mode == MODE_DENSE) return hipErrorInvalidValue;
-  if (p.n_items != p.n_q_blocks * p.n_heads * p.B * p.split) stub::violation("n_items does not match the item space");
+  const int space = p.n_q_blocks * p.n_heads * p.B * p.split;
+  if (p.n_items != space && !(mode == MODE_DENSE && p.split == 1 && p.n_items > 0 && p.n_items < space))
+    stub::violation("n_items does not match the item space");
   stub::note_launch(stream, f8 ? "attn_fwd_fp8_kernel" : "attn_fwd_kernel");
   for (int item = 0; item < p.n_items; ++item) model_item(p, f8, mode, small_q, item);
   return hipSuccess;
@@ -228,14 +230,16 @@ hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t s
     AttnLaunch a = p.a;
     a.n_q_blocks = sg.n_q_blocks;
     a.n_heads = sg.n_heads;
-    a.n_items = sg.n_items;
+    a.n_items = sg.n_items + sg.first_item;
     a.heads = p.a.ws + sg.heads;
     a.list_id = p.a.ws + sg.list_id;
     a.list_table = sg.list_table;
     a.split = 1;
     a.partial = nullptr;
-    if (sg.n_items != sg.n_q_blocks * sg.n_heads * a.B) stub::violation("segment %d: n_items does not match its item space", s);
-    for (int item = 0; item < sg.n_items; ++item) {
+    if (sg.first_item < 0 || sg.n_items + sg.first_item != sg.n_q_blocks * sg.n_heads * a.B)
+      stub::violation("segment %d: first_item + n_items does not match its item space", s);
+    if (sg.first_item > 0 && sg.kind != SEG_DENSE) stub::violation("segment %d: only dense segments have a head start", s);
+    for (int item = sg.first_item; item < sg.first_item + sg.n_items; ++item) {
       if (sg.kind != SEG_ZERO) {
         const int mode = sg.kind == SEG_DENSE ? MODE_DENSE : sg.kind == SEG_BAND ? MODE_BAND
                          : sg.kind == SEG_GATHER ? MODE_GATHER : MODE_PBAND;

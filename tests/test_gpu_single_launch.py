@@ -21,7 +21,7 @@ def run_plan(wl, q, k, v, **options):
                      dtype=torch.uint8, device=DEV)
     ws.fill_(0xA5)                                # the queue positions must not depend on what the workspace held
     plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, **options)
-    assert plan.single_launch() == (options.get("single_launch", 0) == 1)
+    assert plan.single_launch() == (options.get("single_launch", 0) in (1, 3))
     out = torch.full_like(q, float("nan"))
     svd.svd_attn_forward_planned(plan, q, k, v, out)
     torch.cuda.synchronize()
@@ -45,7 +45,7 @@ def test_small_layers_all_rows_equal_the_grouped_launches(L, D, H, seed, B):
     wl = W.small(L=L, D=D, H=H, seed=seed, B=B)
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
     one, plan, ws = run_plan(wl, q, k, v, single_launch=1)
-    grouped, plan_g, _ = run_plan(wl, q, k, v, dense_split=1)
+    grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
     assert_same_bits(one, grouped)
     check_layer(wl, q, k, v, one)
     # a second and third pass with the same plan (the queue positions are reset by the call itself)
@@ -65,7 +65,7 @@ def test_random_layers(seed):
     wl, _ = random_layer(seed)
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
     one, plan, _ = run_plan(wl, q, k, v, single_launch=1)
-    grouped, plan_g, _ = run_plan(wl, q, k, v, dense_split=1)
+    grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
     assert_same_bits(one, grouped, first_row=wl.text_tokens)
     dense = [h for h in range(wl.H) if wl.strategy_table[h] in (W.DENSE, W.SKIP)]
     assert_same_bits(one[:, dense], grouped[:, dense])
@@ -80,7 +80,7 @@ def test_rearranged_heads_and_strided_layout():
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
     q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))   # token-major storage
     one, plan, _ = run_plan(wl, q, k, v, single_launch=1)
-    grouped, plan_g, _ = run_plan(wl, q, k, v, dense_split=1)
+    grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
     assert_same_bits(one, grouped)
     plan.close()
     plan_g.close()
@@ -111,13 +111,29 @@ def test_captured_single_launch_replays_to_the_eager_bits():
     plan.close()
 
 
+def test_dense_head_start_covers_whole_rounds_and_leaves_the_rest_to_the_queues():
+    """26 dense heads of 11 256-row tiles: 286 dense items, of which 256 (one round of the 256 compute units) go
+    through the dense kernel; the queues' dense segment starts in the middle of a head, at a 128-row item."""
+    wl = W.small(L=2600, D=64, H=30, seed=19)
+    for h in range(4, 30):
+        wl.strategy_table[h] = W.DENSE
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    one, plan, _ = run_plan(wl, q, k, v, single_launch=3)
+    grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
+    assert_same_bits(one, grouped)
+    check_layer(wl, q, k, v, one, heads=[0, 1, 2, 3, 4, 17, 26, 27, 28, 29])
+    plan.close()
+    plan_g.close()
+
+
+@pytest.mark.parametrize("form", [1, 3])
 @pytest.mark.parametrize("name", ["cogvideox1.5", "hunyuanvideo", "wan2.1"])
-def test_benchmark_shapes_sampled_rows(name):
+def test_benchmark_shapes_sampled_rows(name, form):
     wl = W.BY_NAME[name]()
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
-    one, plan, _ = run_plan(wl, q, k, v, single_launch=1)
+    one, plan, _ = run_plan(wl, q, k, v, single_launch=form)
     assert torch.isfinite(one.float()).all()
-    grouped, plan_g, _ = run_plan(wl, q, k, v, dense_split=1)
+    grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
     assert_same_bits(one, grouped)
     rows = W.sample_rows(wl, n_random=24)
     check_layer(wl, q, k, v, one, rows=rows)
