@@ -149,8 +149,11 @@ typedef struct {
  * need the kernels' block shape (SVD_ERR_UNSUPPORTED otherwise) and a device
  * (SVD_ERR_HIP).  The split of the dense heads is still chosen and its scratch
  * still part of the workspace: the FP8 forward pass and the per-group entry
- * points run such a plan group by group. */
-typedef struct { int32_t block_q, block_k, dense_split, text_tokens, single_launch; } svd_plan_options;
+ * points run such a plan group by group.
+ * no_fork: 1 = grouped launches always run one after the other on the caller's
+ * stream (see svd_attn_forward_planned); 0 = the library forks them onto its own
+ * streams when that fills an otherwise idle last round. */
+typedef struct { int32_t block_q, block_k, dense_split, text_tokens, single_launch, no_fork; } svd_plan_options;
 
 typedef struct svd_plan svd_plan;
 
@@ -250,8 +253,8 @@ svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* com
  * joined on hip_stream before the call returns; either way everything is
  * ordered on hip_stream for the caller.  One forward pass per plan may be in
  * flight at a time (calls with the same plan on one stream are fine; concurrent
- * calls on different streams need different plans).  SVD_NO_FORK=1 in the
- * environment at plan creation disables the fork.  Only kernel launches and
+ * calls on different streams need different plans).  The plan option no_fork
+ * disables the fork.  Only kernel launches and
  * event records/waits are enqueued, so the call may be recorded into a stream
  * capture - except for a plan with a text prefix: while hip_stream is capturing,
  * such a plan is refused with SVD_ERR_UNSUPPORTED before anything is enqueued
@@ -321,9 +324,21 @@ svd_status svd_head_mse(const void* o, const void* o_ref, const svd_tensor_desc*
                         void* device_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* S_i of Eq. 2 for every head of a plan: the share of the L x L attention map the
- * head's mode leaves out (0 dense, 1 skip, element-level count for the patterns).
+ * head's mode leaves out (0 dense, 1 skip, element-level count for the patterns:
+ * this library's reading, since the block size of the paper's kernels is not
+ * given and an element count does not depend on one).
  * sparsity: HOST double[H]. */
 svd_status svd_plan_head_sparsity(const svd_plan* plan, double* sparsity);
+
+/* The block-level count of the same quantity, in the wording of Section 4.2 ("the
+ * ratio of actual computation blocks to the total number of blocks"): 1 minus the
+ * number of block_q x block_k tiles the head's launches compute over the number
+ * of tiles of the map, on the tile shape of the head's group (a tile that holds
+ * one kept pair counts whole, the text rows of a text prefix count as dense
+ * tiles).  It depends on the tile shape; the element-level figure above is its
+ * limit for small tiles and is what svd_search_layer uses for S_i.
+ * sparsity: HOST double[H]. */
+svd_status svd_plan_head_block_sparsity(const svd_plan* plan, double* sparsity);
 
 /* Eq. 2 and Eq. 3 on the host.  mse (float) and sparsity (double) are HOST arrays
  * of 4 * H values, row i - 1 = mode i; table: HOST int32[H], out; loss: HOST

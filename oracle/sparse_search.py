@@ -11,7 +11,9 @@ all five modes M_0..M_4; for every head h and every sparse mode i = 1..4
     L_i[h] = MSE(O_i[h] - O_0[h]) + lambda * (1 - S_i[h])              (Eq. 2)
 
 with S_i[h] the share of the attention map that mode i leaves out for that head
-(1 for the skip mode).  The head keeps full attention (mode 0) when all four
+(1 for the skip mode).  Section 4.2 words S_i as a ratio of blocks of the authors'
+kernels, whose block size is not given; this oracle counts elements (head_sparsity),
+which no block size enters, and states the block count as well (head_block_sparsity).  The head keeps full attention (mode 0) when all four
 losses exceed epsilon, otherwise it takes the mode with the smallest loss
 (Eq. 3).  The layer's output x^o carries, per head, the output of the chosen
 mode (Algorithm 1, "Per-Head Optimization").
@@ -36,6 +38,25 @@ def head_sparsity(mode, params, L):
     if mode == A.MODE_DENSE:
         return 0.0
     return 1.0 - A.mask_popcount(mode, params, L) / float(L * L)
+
+
+def head_block_sparsity(mode, params, L, block_q, block_k):
+    """The block-level count of S_i in the wording of Section 4.2 ("the ratio of actual computation blocks to the
+    total number of blocks"): 1 - computed tiles / all tiles of the map for tiles of block_q x block_k.  A tile is
+    computed when the explicit mask keeps at least one pair in it (band modes), a vertical-stripe head computes
+    ceil(|C| / block_k) column tiles for every query tile, and the rows of a text prefix are computed as dense
+    tiles on top of the pattern's own tiles."""
+    if mode == A.MODE_SKIP:
+        return 1.0
+    if mode == A.MODE_DENSE:
+        return 0.0
+    n_qb, n_kb = -(-L // block_q), -(-L // block_k)
+    text_tiles = (A.text_tokens_of(params) // block_q) * n_kb
+    if mode == A.MODE_VSTRIPE:
+        computed = n_qb * (A.column_list(params, L, block_k).size // block_k) + text_tiles
+    else:
+        computed = A.block_lists(mode, params, L, block_q, block_k)["kv_block_idx"].size + text_tiles
+    return 1.0 - computed / float(n_qb * n_kb)
 
 
 def head_mse(o, o_ref):

@@ -26,7 +26,7 @@ EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", 
            "svd_plan_dense_split", "svd_plan_single_launch", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_group_blocks", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
            "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward", "sparse_vdit_attn_forward_static",
            "svd_dense_attn_forward", "svd_status_string",
-           "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_search_select",
+           "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_plan_head_block_sparsity", "svd_search_select",
            "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
            "svd_fp8_workspace_bytes", "svd_attn_forward_fp8", "svd_attn_forward_fp8_group", "svd_rearrange_tokens", "svd_probe_mfma", "svd_probe_copy"]
 
@@ -50,7 +50,7 @@ class HeadParams(C.Structure):
 
 class PlanOptions(C.Structure):
     _fields_ = [("block_q", C.c_int32), ("block_k", C.c_int32), ("dense_split", C.c_int32),
-                ("text_tokens", C.c_int32), ("single_launch", C.c_int32)]
+                ("text_tokens", C.c_int32), ("single_launch", C.c_int32), ("no_fork", C.c_int32)]
 
 
 _lib = None
@@ -91,6 +91,7 @@ def lib():
             "svd_head_mse_workspace_bytes": [descp, C.POINTER(C.c_size_t)],
             "svd_head_mse": [vp, vp, descp, vp, vp, C.c_size_t, vp],
             "svd_plan_head_sparsity": [vp, C.POINTER(C.c_double)],
+            "svd_plan_head_block_sparsity": [vp, C.POINTER(C.c_double)],
             "svd_search_select": [C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_double), C.c_double, C.c_double,
                                   i32p, C.POINTER(C.c_double)],
             "svd_select_heads": [C.POINTER(vp), descp, i32p, vp, descp, vp],
@@ -187,10 +188,10 @@ def svd_default_blocks(D: int):
 
 
 def svd_plan_workspace_bytes(desc, strategy_table, pattern_params, block_q=0, block_k=0, dense_split=0,
-                             text_tokens=None, single_launch=0) -> int:
+                             text_tokens=None, single_launch=0, no_fork=0) -> int:
     m = _Marshalled(strategy_table, pattern_params)
     opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens),
-                      single_launch)
+                      single_launch, no_fork)
     n = C.c_size_t()
     _check(lib().svd_plan_workspace_bytes(C.byref(desc), _ptr(m.table), m.params, C.byref(opt), C.byref(n)),
            "svd_plan_workspace_bytes")
@@ -223,6 +224,12 @@ class Plan:
         out = np.zeros(self.desc.H, dtype=np.float64)
         _check(lib().svd_plan_head_sparsity(self.handle, out.ctypes.data_as(C.POINTER(C.c_double))),
                "svd_plan_head_sparsity")
+        return out
+
+    def head_block_sparsity(self):
+        out = np.zeros(self.desc.H, dtype=np.float64)
+        _check(lib().svd_plan_head_block_sparsity(self.handle, out.ctypes.data_as(C.POINTER(C.c_double))),
+               "svd_plan_head_block_sparsity")
         return out
 
     def dense_split(self) -> int:
@@ -290,14 +297,14 @@ class Plan:
 
 
 def svd_plan_create(desc, strategy_table, pattern_params, block_q=0, block_k=0, workspace=None, stream=None,
-                    dense_split=0, text_tokens=None, single_launch=0) -> Plan:
+                    dense_split=0, text_tokens=None, single_launch=0, no_fork=0) -> Plan:
     """workspace: a torch uint8/int32 CUDA tensor of at least svd_plan_workspace_bytes
     bytes, or None for a host-only plan (inspection, no launches).  text_tokens:
     the plan option; None reads it from the "text_tokens" key of the sparse
     heads' parameter dicts."""
     m = _Marshalled(strategy_table, pattern_params)
     opt = PlanOptions(block_q, block_k, dense_split, _text_tokens(strategy_table, pattern_params, text_tokens),
-                      single_launch)
+                      single_launch, no_fork)
     handle = C.c_void_p()
     ws_ptr = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0

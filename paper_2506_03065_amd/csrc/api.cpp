@@ -7,7 +7,6 @@
 
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -432,9 +431,7 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
       }
       build_layer_segments(sp);
     }
-    // SVD_NO_FORK=1 in the environment keeps every group on the caller's stream
-    const char* no_fork = std::getenv("SVD_NO_FORK");
-    if (native && with_side_streams && !single && !(no_fork && no_fork[0] == '1')) {
+    if (native && with_side_streams && !single && !(options && options->no_fork)) {
       bool ok = hipEventCreateWithFlags(&sp->fork, hipEventDisableTiming) == hipSuccess;
       for (int i = 0; ok && i < kSideStreams; ++i)
         ok = hipStreamCreateWithFlags(&sp->side[i], hipStreamNonBlocking) == hipSuccess &&
@@ -951,6 +948,26 @@ svd_status svd_plan_head_sparsity(const svd_plan* plan, double* sparsity) {
         kept = n_cols * p.desc.L + static_cast<double>(p.text_tokens) * (p.desc.L - n_cols);
       }
       sparsity[g.heads[t]] = 1.0 - kept / all;
+    }
+  }
+  return SVD_OK;
+}
+
+svd_status svd_plan_head_block_sparsity(const svd_plan* plan, double* sparsity) {
+  if (!plan || !sparsity) return SVD_ERR_NULL;
+  const Plan& p = plan->p;
+  for (const svd::Group& g : p.groups) {
+    const double all = static_cast<double>(g.n_q_blocks) * p.n_k_blocks;
+    const double text_rows = has_text_rows(p, g) ? static_cast<double>(p.text_tokens / g.block_q) * p.n_k_blocks : 0.0;
+    for (size_t t = 0; t < g.heads.size(); ++t) {
+      double listed = 0.0;
+      if (g.mode == SVD_DENSE) listed = all;
+      else if (g.mode == SVD_DIAG || g.mode == SVD_MULTIDIAG)
+        listed = static_cast<double>(g.bands[g.list_id[t]].kv_block_idx.size()) + text_rows;
+      else if (g.mode == SVD_VSTRIPE)
+        listed = static_cast<double>(g.n_q_blocks) * static_cast<double>(g.columns[g.list_id[t]].cols.size() / p.block_k) +
+                 text_rows;   // the stripe launch covers every query tile; the text rows are then computed densely on top
+      sparsity[g.heads[t]] = 1.0 - listed / all;
     }
   }
   return SVD_OK;

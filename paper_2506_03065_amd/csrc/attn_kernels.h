@@ -17,28 +17,16 @@ enum { MODE_DENSE = 0, MODE_BAND = 1, MODE_GATHER = 2, MODE_PBAND = 3 };
 // Tile shapes the kernels are instantiated for.  Query tile = NW waves x QB
 // blocks of 32 rows; key tile = BC keys.
 // OCC = waves per SIMD the kernel is compiled for (register budget 512 / OCC).
-#ifndef SVD_T128
-#define SVD_T128 8, 1, 64, 2
-#endif
-#ifndef SVD_T64
-#define SVD_T64 8, 1, 128, 2
-#endif
 // Small query tile (half the waves, two work-groups per compute unit) for band
 // groups whose bands are narrow: with 128 instead of 256 query rows per tile the
 // listed tiles hug the band more closely, which saves more work than the halved
 // reuse of a K/V tile costs.  Same key tile, so one plan geometry along the keys.
-#ifndef SVD_T128S
-#define SVD_T128S 4, 1, 64, 2
-#endif
-#ifndef SVD_T64S
-#define SVD_T64S 4, 1, 128, 2
-#endif
 template <int NW_, int QB_, int BC_, int OCC_>
 struct TileShape { static constexpr int NW = NW_, QB = QB_, BC = BC_, OCC = OCC_; };
-using Tile128 = TileShape<SVD_T128>;   // D = 128
-using Tile64 = TileShape<SVD_T64>;     // D = 64
-using Tile128s = TileShape<SVD_T128S>;
-using Tile64s = TileShape<SVD_T64S>;
+using Tile128 = TileShape<8, 1, 64, 2>;    // D = 128
+using Tile64 = TileShape<8, 1, 128, 2>;    // D = 64
+using Tile128s = TileShape<4, 1, 64, 2>;   // D = 128, small query tile
+using Tile64s = TileShape<4, 1, 128, 2>;   // D = 64, small query tile
 static_assert(Tile128s::BC == Tile128::BC && Tile64s::BC == Tile64::BC, "the small query tile keeps the key tile");
 
 struct AttnLaunch {

@@ -179,10 +179,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
   constexpr int KS = D / 64;         // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;         // 32-row blocks of O^T
   constexpr int TILE_BYTES = BC * D;
-#ifndef SVD_FP8_DEEP
-#define SVD_FP8_DEEP (D == 128 && MODE == MODE_DENSE)
-#endif
-  constexpr bool DEEP = SVD_FP8_DEEP;   // pipeline shape, see the stages below
+  constexpr bool DEEP = D == 128 && MODE == MODE_DENSE;   // pipeline shape, see the stages below
   constexpr int LPT = TILE_BYTES / (NW * 1024);   // load instructions per wave, tile and matrix
   static_assert(TILE_BYTES % (NW * 1024) == 0 && LPT >= 1, "tile must split evenly over the waves");
   static_assert(BC % 64 == 0, "key tiles are whole groups of 64");
@@ -531,7 +528,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       exponentiate(s_cur, pf);
       if (has1) tile_max(s_next);
       accumulate(Int<PAR>{}, pf);
-#ifndef SVD_FP8_NO_SCHED
       if (has1) {
         // Issue order: one MFMA, the LDS reads that feed the MFMAs two steps later,
         // then a share of the vector work (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
@@ -559,7 +555,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
           __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
         }
       }
-#endif
       if (has1) asm volatile("" : "+v"(mx_raw));   // keeps the maximum chain of the next tile inside this block
       __syncthreads();
     };
@@ -630,7 +625,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       if (!FIRST) accumulate(Int<PAR ^ 1>{}, pf_prev);
       exponentiate(s_cur, pf_cur);
       if (has1) tile_max(s_next);
-#ifndef SVD_FP8_NO_SCHED
       if (has1 && !FIRST) {
         // Issue order: one MFMA, the LDS reads that feed the MFMAs two steps later,
         // then a share of the vector work (0x008 MFMA, 0x100 DS read, 0x002 VALU, 0x400 TRANS).
@@ -658,7 +652,6 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
           __builtin_amdgcn_sched_group_barrier(0x402, VALU_PER, 0);
         }
       }
-#endif
       if (has1) asm volatile("" : "+v"(mx_raw));   // keeps the maximum chain of the next tile inside this block
       // the loads issued at the top of the stage must have landed before anyone reads them
       __syncthreads();

@@ -11,10 +11,7 @@ namespace {
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMseThreads = 256;
-#ifndef SVD_MSE_CHUNK
-#define SVD_MSE_CHUNK (1 << 18)
-#endif
-constexpr int kMseChunkBytes = SVD_MSE_CHUNK;   // of one tensor, per work-group
+constexpr int kMseChunkBytes = 1 << 18;   // of one tensor, per work-group
 
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __builtin_bit_cast(float, w & 0xffff0000u); }

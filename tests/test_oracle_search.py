@@ -103,3 +103,26 @@ def test_epsilon_zero_and_lambda_large_keep_every_head_dense():
     assert (loss[1:] > 0).all()          # every sparse mode here has a positive loss ...
     assert (loss[0] > 0).all()           # ... and so has skipping
     assert table.tolist() == [0, 0, 0]
+
+
+def test_block_sparsity_closed_forms_and_its_limit():
+    L = 200
+    assert S.head_block_sparsity(A.MODE_SKIP, {}, L, 16, 16) == 1.0 and S.head_block_sparsity(A.MODE_DENSE, {}, L, 16, 16) == 0.0
+    # vertical stripes: 21 columns are two column tiles of 16 for each of the 13 query tiles
+    cols = tuple(range(3, 200, 10))[:21] + (7,)
+    cols = tuple(sorted(set(cols)))[:21]
+    assert len(cols) == 21
+    assert np.isclose(S.head_block_sparsity(A.MODE_VSTRIPE, {"cols": cols}, L, 16, 16), 1 - 2 / 13)
+    # a diagonal of half width 0 with square tiles that divide L: exactly the n diagonal tiles
+    assert np.isclose(S.head_block_sparsity(A.MODE_DIAG, {"half_width": 0}, 192, 16, 16), 1 - 12 / 144)
+    # half width 16: rows 16a..16a+15 reach keys 16a-16..16a+31, the diagonal tile and both neighbours
+    assert np.isclose(S.head_block_sparsity(A.MODE_DIAG, {"half_width": 16}, 192, 16, 16), 1 - (12 + 2 * 11) / 144)
+    # half width 17: one key further, into the tiles two away
+    assert np.isclose(S.head_block_sparsity(A.MODE_DIAG, {"half_width": 17}, 192, 16, 16), 1 - (12 + 2 * 11 + 2 * 10) / 144)
+    # tiles of one element: the block count is the element count
+    for mode, p in ((A.MODE_DIAG, {"half_width": 9}), (A.MODE_MULTIDIAG, {"half_width": 3, "offsets": (-40, 0, 25)}),
+                    (A.MODE_VSTRIPE, {"cols": (1, 5, 77)})):
+        assert np.isclose(S.head_block_sparsity(mode, p, 90, 1, 1), S.head_sparsity(mode, p, 90))
+    # coarser tiles can only compute more
+    for bs in (2, 4, 8, 16):
+        assert S.head_block_sparsity(A.MODE_DIAG, {"half_width": 9}, 90, bs, bs) <= S.head_sparsity(A.MODE_DIAG, {"half_width": 9}, 90) + 1e-12

@@ -132,3 +132,18 @@ def test_fp8_entry_points_validate_before_any_launch():
     assert lib.svd_attn_forward_fp8(plan.handle, p16, p16, p16, p16, C.c_void_p(0x10000), 1 << 30, None) == 8
     assert lib.svd_attn_forward_fp8(plan.handle, None, p16, p16, p16, C.c_void_p(0x10000), 1 << 30, None) == 1
     plan.close()
+
+
+@pytest.mark.parametrize("L,D,text", [(333, 64, 0), (1000, 128, 0), (900, 128, 256), (1300, 64, 512)])
+def test_plan_head_block_sparsity_matches_the_explicit_mask_tiles(L, D, text):
+    """The block-level S_i (Section 4.2's wording) from the plan's lists against the oracle's count over explicit-mask tiles."""
+    wl = W.small(L=L, D=D, H=5, seed=29)
+    if text:
+        wl = W.with_text_borders(wl, text)
+    plan = svd.svd_plan_create(svd.tensor_desc(wl.B, wl.H, wl.L, wl.D), wl.strategy_table, wl.pattern_params)
+    got = plan.head_block_sparsity()
+    for g in plan.groups():
+        for h in g["heads"]:
+            want = S.head_block_sparsity(int(wl.strategy_table[h]), wl.pattern_params[h], wl.L, g["block_q"], g["block_k"])
+            assert abs(got[h] - want) <= 1e-15, (h, g["mode"], got[h], want)
+    plan.close()
