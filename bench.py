@@ -451,17 +451,34 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     dom = max(compute_groups, key=lambda g: g["ms"])
     peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
     traffic, traffic_source = recorded_traffic(args.precision, wl.name, dom["mode"])
-    roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[{dom['mode']} group]",
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    kname = "attn_fwd_fp8_kernel" if fp8 else "attn_fwd_kernel"
+    dom_g = next(g for g in plan.groups() if MODE_NAMES[g["mode"]] == dom["mode"])
+    dom_threads = 64 * (8 if dom_g["block_q"] == svd.svd_default_blocks(wl.D)[0] else 4)
+    dom_items = -(-wl.L // dom_g["block_q"]) * len(dom_g["heads"]) * wl.B * (plan.dense_split() if dom["mode"] == "dense" else 1)
+    dispatches = [{"kernel": kname, "grid_size": -(-dom_items // 8) * 8 * dom_threads}]
+    if dom["mode"] == "dense" and plan.dense_split() > 1:
+        dispatches.append({"kernel": "combine_partials_kernel"})
+    if fp8:
+        dispatches.append({"kernel": "quantise_kv_kernel", "grid_size": (-(-wl.L // 128) * 128 // 64) * len(dom_g["heads"]) * wl.B * 256})
+    roofline = {"bound": "mfma", "kernel": f"{kname}[{dom['mode']} group]",
                 "achieved": dom["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(dom["tflops"] / peak, 4),
-                "traffic": traffic, "traffic_source": traffic_source}
+                "traffic": traffic, "traffic_source": traffic_source, "traffic_key": dom["mode"], "dispatches": dispatches}
     if plan.single_launch() and not fp8:
         # the step IS the dominant kernel: the layer kernel (with the dense kernel's head start ahead of it, and
         # the 5 us fill of the queue positions); algorithmic FLOPs = the plan's listed tiles
         tf = work["computed_flops"] / 1e9 / ms_per_step
         traffic, traffic_source = recorded_traffic(args.precision, wl.name, "layer")
+        dispatches = [{"kernel": "attn_layer_kernel"}]
+        n_dense = int((wl.strategy_table == 0).sum())
+        bq = svd.svd_default_blocks(wl.D)[0]
+        head_start = (-(-wl.L // bq) * n_dense * wl.B) // n_cu * n_cu      # whole rounds of one dense item per compute unit
+        if head_start:
+            dispatches.append({"kernel": f"attn_fwd_kernel<{wl.D}, 8, 1, {svd.svd_default_blocks(wl.D)[1]}, 2, 0>",
+                               "grid_size": -(-head_start // 8) * 8 * 512})
         roofline = {"bound": "mfma", "kernel": "attn_layer_kernel + attn_fwd_kernel[dense head start] (the whole step)",
                     "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
-                    "traffic": traffic, "traffic_source": traffic_source}
+                    "traffic": traffic, "traffic_source": traffic_source, "traffic_key": "layer", "dispatches": dispatches}
     add_measured_peak(roofline, calib, fp8)
     bf16_ms = gpu_time_ms(step16, max(3, args.steps // 2), 1, torch) if fp8 else None
 

@@ -133,16 +133,17 @@ typedef struct {
  * queues when their own is empty, so no group pays for a partly filled last
  * round.  Every item runs on the 128-row query tile, dense heads are not split,
  * text rows of a text prefix are items of the dense
- * kind, and nothing is forked.  The queue positions are eight words of the plan
- * workspace that a small fill kernel zeroes ahead of the layer kernel (two
- * launches in all; no memset, so the call can be captured).  Results are
+ * kind, and nothing is forked.  The queue positions are words of the plan
+ * workspace that a small fill kernel zeroes ahead of the layer kernel (no
+ * memset, so the call can be captured); with vertical-stripe heads the gather
+ * pre-pass of their K and V rows runs ahead of it too.  Results are
  * bit-identical to the grouped launches of a plan with dense_split = 1.
  * 3 = the single launch with a DENSE HEAD START: as many whole rounds of dense
  * items as there are (one work-group per compute unit and round, none partly
  * filled) first go through the dense kernel on its 256-row tile, which reuses a
  * K/V tile in LDS for twice as many rows; the rest of the dense group and
- * everything else is the layer kernel's (three launches in all).  Same bits.
- * 2 = grouped launches.  0 = the library's choice: form 3 for D = 128, grouped
+ * everything else is the layer kernel's.  Same bits.
+ * 2 = grouped launches.  0 = the library's choice: form 3 for D = 128 (head start), grouped
  * launches for D = 64 (there the 128-row tile costs the dense items more than
  * the filled tails bring), and grouped launches whenever dense_split > 1 is
  * forced, the block shape is not the kernels' or no device is present.  1 and 3

@@ -43,6 +43,9 @@ struct svd_plan {
   std::vector<size_t> text_partial_offset;
   // single launch (plan option): the segments of the layer kernel, heaviest first, and
   // the byte offset of its queue positions in the workspace
+  // vertical-stripe group: byte offset of its gathered K/V rows in the workspace, rows per head
+  size_t gather_offset = 0;
+  int gather_pad = 0;
   bool single_launch = false;
   // dense head start (plan option single_launch = 3): this many 256-row dense items, whole rounds of
   // one work-group per compute unit, run through the dense kernel ahead of the layer kernel
@@ -167,10 +170,28 @@ int choose_text_split(const Plan& p, const svd::Group& g, int n_cu) {
 
 // Workspace = [compiled lists | padding to 256 bytes | scratch of the dense split |
 // scratch of the text-row launches, one area per sparse group].
+// Longest padded column list of the plan's vertical-stripe group (0: no such group).
+int stripe_gather_pad(const Plan& p) {
+  int pad = 0;
+  for (const svd::Group& g : p.groups)
+    if (g.mode == SVD_VSTRIPE)
+      for (const svd::ColumnList& cl : g.columns) pad = std::max(pad, static_cast<int>(cl.cols.size()));
+  return pad;
+}
+
 size_t workspace_need(const Plan& p, int dense_split, int n_cu, size_t* partial_offset, std::vector<int>* text_split,
-                      std::vector<size_t>* text_offset, bool single_launch = false, size_t* counters_offset = nullptr) {
+                      std::vector<size_t>* text_offset, bool single_launch = false, size_t* counters_offset = nullptr,
+                      size_t* gather_offset = nullptr) {
   size_t end = p.ws_image.size() * sizeof(int32_t);
   if (partial_offset) *partial_offset = 0;
+  if (gather_offset) *gather_offset = 0;
+  for (const svd::Group& g : p.groups) {
+    if (g.mode != SVD_VSTRIPE) continue;
+    // the gathered K and V rows of the stripe heads (filled by every forward pass)
+    const size_t off = align_up(end, 256);
+    if (gather_offset) *gather_offset = off;
+    end = off + svd::gathered_elements(p.desc.B, static_cast<int>(g.heads.size()), stripe_gather_pad(p), p.desc.D) * 2;
+  }
   if (dense_split > 1) {
     const size_t off = align_up(end, 256);
     if (partial_offset) *partial_offset = off;
@@ -407,7 +428,9 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
     const int n_cu_ws = device_compute_units();
     sp->dense_split = native ? choose_dense_split(*desc, bq, bk, count_dense_heads(sp->p), n_cu_ws, options) : 1;
     const size_t need = workspace_need(sp->p, sp->dense_split, native ? n_cu_ws : 0, &sp->partial_offset,
-                                       &sp->text_split, &sp->text_partial_offset, single, &sp->counters_offset);
+                                       &sp->text_split, &sp->text_partial_offset, single, &sp->counters_offset,
+                                       &sp->gather_offset);
+    sp->gather_pad = stripe_gather_pad(sp->p);
 
     if (workspace_bytes < need || !aligned16(device_workspace)) {
       delete sp;
@@ -669,6 +692,13 @@ static svd_status launch_group(const svd_plan& sp, const svd::Group& g, const vo
       a.n_items *= a.split;
       a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.partial_offset);
     }
+    if (g.mode == SVD_VSTRIPE) {
+      a.gathered = reinterpret_cast<__bf16*>(static_cast<char*>(p.device_workspace) + sp.gather_offset);
+      a.gather_pad = sp.gather_pad;
+      a.skip_q_blocks = p.text_tokens / p.block_q;   // the text rows come from the dense launch below
+      err = svd::launch_gather_kv(a, stream);
+      if (err != hipSuccess) return SVD_ERR_HIP;
+    }
     err = svd::launch_attention(a, kmode, stream, small_q);
     if (err == hipSuccess && a.split > 1) err = svd::launch_combine(a, stream);
     if (err == hipSuccess && has_text_rows(p, g)) {
@@ -723,6 +753,21 @@ svd_status svd_attn_forward_planned(const svd_plan* plan, const void* q, const v
     svd::LayerLaunch lay = plan->layer;
     lay.a = base_launch(p.desc, q, k, v, out);
     lay.a.ws = static_cast<const int*>(p.device_workspace);
+    for (const svd::Group& g : p.groups) {
+      if (g.mode != SVD_VSTRIPE) continue;
+      // the stripe heads' K and V rows are gathered ahead of the layer kernel
+      svd::AttnLaunch a = lay.a;
+      a.n_heads = static_cast<int>(g.heads.size());
+      a.heads = lay.a.ws + g.ws_heads;
+      a.list_id = lay.a.ws + g.ws_list_id;
+      a.list_table = static_cast<int>(g.ws_list_table);
+      a.gathered = reinterpret_cast<__bf16*>(static_cast<char*>(p.device_workspace) + plan->gather_offset);
+      a.gather_pad = plan->gather_pad;
+      if (svd::launch_gather_kv(a, main_stream) != hipSuccess) return SVD_ERR_HIP;
+      lay.a.gathered = a.gathered;
+      lay.a.gather_pad = a.gather_pad;
+      lay.a.skip_q_blocks = p.text_tokens / svd::layer_block_q(p.desc.D);   // text rows are items of the dense kind
+    }
     return svd::launch_layer(lay, plan->n_cu, main_stream) == hipSuccess ? SVD_OK : SVD_ERR_HIP;
   }
   // heaviest first: dense, then the band groups, the gathers, and the zero fill
@@ -1214,12 +1259,15 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
     a.n_q_blocks = (d.L + svd::kernel_small_block_q(d.D) - 1) / svd::kernel_small_block_q(d.D);
     a.n_items = a.n_q_blocks * a.n_heads * a.B;
   }
+  if (g.mode == SVD_VSTRIPE)   // the text rows come from the dense launch below
+    a.skip_q_blocks = p.text_tokens / (small_q ? svd::kernel_small_block_q(d.D) : p.block_q);
   if (svd::launch_attention_fp8(f, kmode, stream, small_q) != hipSuccess) return SVD_ERR_HIP;
   if (a.split > 1 && svd::launch_combine(a, stream) != hipSuccess) return SVD_ERR_HIP;
   if (has_text_rows(p, g)) {
     // text rows: dense over every key; a stripe head's arrays hold its columns
     // only, so they are quantised once more, uncompacted
     a.split = 1;
+    a.skip_q_blocks = 0;
     a.n_q_blocks = g.n_q_blocks;
     a.n_items = a.n_q_blocks * a.n_heads * a.B;
     if (g.mode == SVD_VSTRIPE && svd::launch_quantise_kv(f, svd::MODE_DENSE, stream) != hipSuccess) return SVD_ERR_HIP;

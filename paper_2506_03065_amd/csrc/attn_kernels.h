@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
 
 namespace svd {
@@ -50,7 +51,23 @@ struct AttnLaunch {
   // `partial`; a second kernel merges the chunks and writes out.
   int split;             // 1 = off; n_items counts chunks
   float* partial;        // device: partial_floats(...) floats, or nullptr
+  // Vertical-stripe groups (MODE_GATHER): the K and V rows of every head's listed
+  // columns, gathered by launch_gather_kv ahead of the attention launch, so that
+  // the attention loop walks a short dense head: [B * n_heads][2 (K, V)][gather_pad][D],
+  // rows past a head's padded list length zero.  gather_pad = the longest padded
+  // list of the group (a multiple of the key tile).
+  __bf16* gathered;
+  int gather_pad;
+  // MODE_GATHER: the first skip_q_blocks query tiles of every head belong to another launch (the
+  // text rows of a layer with a text prefix, computed densely) and are left alone
+  int skip_q_blocks;
 };
+// Elements of `gathered` for a group of n_heads heads.
+inline size_t gathered_elements(int B, int n_heads, int gather_pad, int D) {
+  return static_cast<size_t>(B) * n_heads * 2 * gather_pad * D;
+}
+// Pre-pass of a vertical-stripe group: fills p.gathered from p.k, p.v through the group's column lists.
+hipError_t launch_gather_kv(const AttnLaunch& p, hipStream_t stream);
 
 // The whole layer in ONE launch (Section 4.2: heads that share a mode are fused;
 // here all groups are): a grid of resident work-groups, two of four waves per

@@ -120,7 +120,8 @@ __device__ __forceinline__ const T __attribute__((address_space(4)))* uni_const(
 template <int D, int NW, int QB, int BC, int OCC, int MODE>
 __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, unsigned char* const smem) {
   constexpr bool kBand = MODE == MODE_BAND || MODE == MODE_PBAND;        // walks a CSR list of key tiles
-  constexpr bool kIndirect = MODE == MODE_GATHER || MODE == MODE_PBAND;   // key rows come through an index list
+  constexpr bool kIndirect = MODE == MODE_PBAND;   // key rows come through an index list (the row map)
+  constexpr bool kGathered = MODE == MODE_GATHER;  // K and V are the group's gathered rows: a short dense head
   constexpr int NT = NW * 64;
   constexpr int QW = QB * 32;       // query rows per wave
   constexpr int BR = NW * QW;       // query rows per work-group
@@ -151,8 +152,8 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
 
   const int64_t base = (int64_t)b * p.stride_b + (int64_t)head * p.stride_h;
   const __bf16* __restrict__ Q = p.q + base;
-  const __bf16* __restrict__ K = p.k + base;
-  const __bf16* __restrict__ V = p.v + base;
+  const __bf16* __restrict__ K = kGathered ? p.gathered + (size_t)hb * 2 * p.gather_pad * D : p.k + base;
+  const __bf16* __restrict__ V = kGathered ? K + (size_t)p.gather_pad * D : p.v + base;
   __bf16* __restrict__ O = p.out + base;
   const int L = p.L;
 
@@ -166,8 +167,8 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
   typedef const i32x2 __attribute__((address_space(4)))* const_int2_ptr;
   const_int2_ptr entries = nullptr;   // BAND
   const_int2_ptr runs = nullptr;      // BAND
-  const int* __restrict__ cols = nullptr;      // GATHER: the head's columns; PBAND: the row map
-  int n_cols = 0;
+  const int* __restrict__ cols = nullptr;      // PBAND: the row map
+  int n_cols = 0;                              // GATHER: the head's columns (the keys of its gathered arrays)
   if (MODE == MODE_DENSE) {
     const int n_all = (L + BC - 1) / BC;
     t_base = chunk * n_all / p.split;
@@ -183,7 +184,7 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
       if (n_tiles == 0) return;   // rows that another launch computes (text rows of a layer with a text prefix)
       if (MODE == MODE_PBAND) cols = p.ws + rec[3];
     } else {
-      cols = p.ws + rec[0];
+      if (qblk < p.skip_q_blocks) return;   // text rows: another launch computes them
       n_tiles = rec[1] / BC;
       n_cols = rec[2];
     }
@@ -271,9 +272,9 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
   static_assert(TILE_BYTES % (NW * 1024) == 0, "tile must split evenly over the waves");
   typedef __attribute__((address_space(3))) void* lds_ptr;
   typedef __attribute__((address_space(1))) const void* glb_ptr;
-  const unsigned stride_bytes = (unsigned)p.stride_l * 2u;
-  unsigned g_k[LPT], g_v[LPT];   // DENSE, BAND: byte offset inside the tile; GATHER: chunk offset inside the row
-  unsigned g_r[LPT];             // GATHER: 4 * row of the slab's lane inside the tile
+  const unsigned stride_bytes = kGathered ? (unsigned)ROW_BYTES : (unsigned)p.stride_l * 2u;   // of a key row
+  unsigned g_k[LPT], g_v[LPT];   // DENSE, BAND, GATHER: byte offset inside the tile; PBAND: chunk offset inside the row
+  unsigned g_r[LPT];             // PBAND: 4 * row of the slab's lane inside the tile
 #pragma unroll
   for (int u = 0; u < LPT; ++u) {
     const int byte = (wave * LPT + u) * 1024 + lane * 16;
@@ -284,7 +285,8 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
     g_v[u] = kIndirect ? cv : (unsigned)r * stride_bytes + cv;
   }
   // buffer resources of this head's K and V (raw buffers: base, byte range, no swizzle)
-  const unsigned head_bytes = (unsigned)(L - 1) * stride_bytes + (unsigned)ROW_BYTES;
+  const unsigned head_bytes = kGathered ? (unsigned)p.gather_pad * (unsigned)ROW_BYTES
+                                        : (unsigned)(L - 1) * stride_bytes + (unsigned)ROW_BYTES;
   const __amdgpu_buffer_rsrc_t rsrc_k = __builtin_amdgcn_make_buffer_rsrc((void*)K, 0, (int)head_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_v = __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)head_bytes, 0x00020000);
   // INNER: the tile is known to lie inside [0, L) (anything but the last tile of a list)
@@ -295,9 +297,8 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
     const __amdgpu_buffer_rsrc_t rsrc = IS_K ? rsrc_k : rsrc_v;
     unsigned char* dst = (IS_K ? sK : sV) + buf * TILE_BYTES + wave * (LPT * 1024);
     if (kIndirect) {
-      // key rows come from the head's column list, or from the row map at the tile the band
-      // list names (-1 = padding: any valid row, masked later)
-      const char* list = reinterpret_cast<const char*>(cols + (kBand ? entries[t].x : t) * BC);
+      // key rows come from the row map at the tile the band list names (-1 = padding: any valid row, masked later)
+      const char* list = reinterpret_cast<const char*>(cols + entries[t].x * BC);
 #pragma unroll
       for (int u = 0; u < LPT; ++u) {
         int c = *reinterpret_cast<const int*>(list + g_r[u]);
@@ -308,7 +309,7 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
     } else {
       const int row0 = (kBand ? entries[t].x : t + t_base) * BC;
       const char* base_b = src_b + (unsigned)row0 * stride_bytes;
-      if (INNER || row0 + BC <= L) {
+      if (INNER || kGathered || row0 + BC <= L) {   // gathered arrays are padded to whole tiles
 #pragma unroll
         for (int u = 0; u < LPT; ++u)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(dst + u * 1024), 16, (int)(IS_K ? g_k[u] : g_v[u]),
@@ -743,6 +744,35 @@ __global__ void __launch_bounds__(NW * 64) combine_partials_kernel(const AttnLau
   }
 }
 
+// Pre-pass of a vertical-stripe group (M_4): work-group = 64 key slots of one (batch entry, head).
+// Slot j of the head's gathered arrays takes row cols[j] of K and of V; slots past the padded list
+// and padding entries are zero (a masked score times a zero row, never times stale bits).
+template <int D>
+__global__ void __launch_bounds__(256) gather_kv_kernel(const AttnLaunch p) {
+  constexpr int CH = D / 8;
+  const int hb = blockIdx.y;
+  const int hg = hb % p.n_heads, b = hb / p.n_heads;
+  const int head = p.heads[hg];
+  const int* rec = p.ws + p.list_table + 4 * p.list_id[hg];
+  const int* cols = p.ws + rec[0];
+  const int padded = rec[1];
+  const int64_t base = (int64_t)b * p.stride_b + (int64_t)head * p.stride_h;
+  __bf16* Kg = p.gathered + (size_t)hb * 2 * p.gather_pad * D;
+  __bf16* Vg = Kg + (size_t)p.gather_pad * D;
+  for (int c = threadIdx.x; c < 64 * CH; c += 256) {
+    const int j = blockIdx.x * 64 + c / CH, piece = (c % CH) * 8;
+    if (j >= p.gather_pad) continue;
+    const int src = j < padded ? cols[j] : -1;
+    uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+    if (src >= 0) {
+      kk = *reinterpret_cast<const uint4*>(p.k + base + (int64_t)src * p.stride_l + piece);
+      vv = *reinterpret_cast<const uint4*>(p.v + base + (int64_t)src * p.stride_l + piece);
+    }
+    *reinterpret_cast<uint4*>(Kg + (size_t)j * D + piece) = kk;
+    *reinterpret_cast<uint4*>(Vg + (size_t)j * D + piece) = vv;
+  }
+}
+
 // M_1 (Section 4.2): the output of a skipped head is zero.
 __global__ void __launch_bounds__(256) zero_heads_kernel(const AttnLaunch p) {
   const int hg = blockIdx.y % p.n_heads;
@@ -810,6 +840,9 @@ __device__ __attribute__((noinline)) void layer_item(const AttnLaunch av, const 
   a.scale_log2e = uni(av.scale_log2e);
   a.split = 1;
   a.partial = nullptr;
+  a.gathered = uni(av.gathered);
+  a.gather_pad = uni(av.gather_pad);
+  a.skip_q_blocks = uni(av.skip_q_blocks);
   typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
   unsigned char* const smem = (unsigned char*)(lds_bytes)(uintptr_t)uni((int)smem_v);
   attn_item<D, 4, 1, BC, 2, MODE>(a, uni(item_v), smem);
@@ -920,6 +953,7 @@ void kernel_blocks(int D, int* block_q, int* block_k) {
 hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, bool small_q) {
   if (p.n_items <= 0) return hipSuccess;
   if (p.split < 1 || (p.split > 1 && (mode != MODE_DENSE || !p.partial))) return hipErrorInvalidValue;
+  if (mode == MODE_GATHER && (!p.gathered || p.gather_pad < 1)) return hipErrorInvalidValue;
   if (small_q) {
     if (p.D == 128) return launch_band_small<128, Tile128s::NW, Tile128s::QB, Tile128s::BC, Tile128s::OCC>(p, mode, stream);
     if (p.D == 64) return launch_band_small<64, Tile64s::NW, Tile64s::QB, Tile64s::BC, Tile64s::OCC>(p, mode, stream);
@@ -981,6 +1015,16 @@ hipError_t launch_combine(const AttnLaunch& p, hipStream_t stream) {
   } else {
     return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_kv(const AttnLaunch& p, hipStream_t stream) {
+  if (p.n_heads <= 0) return hipSuccess;
+  if (!p.gathered || p.gather_pad < 1 || !p.heads || !p.list_id || !p.ws) return hipErrorInvalidValue;
+  const dim3 grid((p.gather_pad + 63) / 64, p.n_heads * p.B), block(256);
+  if (p.D == 128) hipLaunchKernelGGL(gather_kv_kernel<128>, grid, block, 0, stream, p);
+  else if (p.D == 64) hipLaunchKernelGGL(gather_kv_kernel<64>, grid, block, 0, stream, p);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -234,6 +234,7 @@ __global__ void __launch_bounds__(NW * 64, OCC) attn_fwd_fp8_kernel(const Fp8Lau
       if (n_tiles == 0) return;   // rows that another launch computes (text rows of a layer with a text prefix)
       if (MODE == MODE_PBAND) row_map = p.ws + rec[3];
     } else {
+      if (qblk < p.skip_q_blocks) return;   // text rows: another launch computes them
       n_tiles = rec[1] / BC;
       n_keys = rec[2];
     }

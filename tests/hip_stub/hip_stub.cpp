@@ -13,6 +13,7 @@
 #include <cstring>
 #include <map>
 #include <set>
+#include <unordered_set>
 
 struct ihipStream_t {
   unsigned magic = 0x57AEA3u;
@@ -63,6 +64,15 @@ int violations() { return g_violations; }
 long launches() { return g_launches; }
 long captured_nodes() { return g_nodes; }
 void set_compute_units(int n) { g_cu = n; }
+
+namespace {
+std::unordered_set<const void*> g_out_rows;
+}
+void new_forward() { g_out_rows.clear(); }
+void note_out_row(const void* row) {
+  if (!g_out_rows.insert(row).second) violation("an output row is stored twice in one forward pass (launch %ld)", launches());
+}
+size_t out_rows_written() { return g_out_rows.size(); }
 void set_tensor_checks(bool on) { g_tensor_checks = on; }
 bool tensor_checks() { return g_tensor_checks; }
 

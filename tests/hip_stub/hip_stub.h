@@ -21,6 +21,13 @@ void destroy_stream(hipStream_t s);
 void begin_capture(hipStream_t s);         // s becomes the origin of a capture
 hipError_t end_capture(hipStream_t s);     // hipErrorStreamCaptureUnjoined when forked work was not joined back
 
+// One forward pass writes every row of `out` exactly once: the harness opens a pass, the launch models
+// report the rows they store (a second store of a row is a violation: two launches or items own it),
+// the harness reads the count.
+void new_forward();
+void note_out_row(const void* row);
+size_t out_rows_written();
+
 // called by the launch models: the stream handle is checked, captured launches are counted
 void note_launch(hipStream_t s, const char* what);
 void violation(const char* fmt, ...);      // prints and counts a broken rule

@@ -38,6 +38,7 @@ void touch_read(const void* p, size_t bytes, const char* what, bool tensor = fal
 }
 void touch_write(void* p, size_t bytes, const char* what, unsigned char value, bool tensor = false) {
   if (tensor && !stub::tensor_checks()) return;
+  if (what[0] == 'o' && what[1] == 'u' && what[2] == 't') stub::note_out_row(p);   // "out row ..."
   if (!stub::in_device(p, bytes)) {
     stub::violation("%s: write of %zu bytes outside every device allocation", what, bytes);
     return;
@@ -104,9 +105,10 @@ void model_item(const AttnLaunch& p, const Fp8Launch* f8, int mode, bool small_q
       if (n_tiles <= 0) return;
       if (mode == MODE_PBAND) map = p.ws + rec[3];
     } else {
-      map = p.ws + rec[0];
+      if (qblk < p.skip_q_blocks) return;
       n_tiles = rec[1] / BC;
       if (rec[1] % BC) stub::violation("column list not padded to the key tile");
+      if (!f8 && (!p.gathered || rec[1] > p.gather_pad)) stub::violation("gathered arrays missing or shorter than a padded list");
     }
   }
   // query rows (clamped to L - 1 on load, stored only below L)
@@ -151,6 +153,12 @@ void model_item(const AttnLaunch& p, const Fp8Launch* f8, int mode, bool small_q
       continue;
     }
     if (!stub::tensor_checks() && mode != MODE_GATHER && mode != MODE_PBAND) continue;   // no workspace word involved
+    if (mode == MODE_GATHER && !f8) {   // the group's gathered rows: a short dense head
+      const __bf16* Kg = p.gathered + (size_t)hb * 2 * p.gather_pad * p.D;
+      touch_read(Kg + (size_t)tile * BC * p.D, (size_t)BC * p.D * 2, "gathered K tile");
+      touch_read(Kg + (size_t)p.gather_pad * p.D + (size_t)tile * BC * p.D, (size_t)BC * p.D * 2, "gathered V tile");
+      continue;
+    }
     for (int r = 0; r < BC; ++r) {
       int row = tile * BC + r;
       if (mode == MODE_GATHER || mode == MODE_PBAND) {
@@ -257,6 +265,33 @@ hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t s
         if (qblk * BR + r < a.L)
           touch_write(const_cast<__bf16*>(row_of(a.out, a, b, head, qblk * BR + r)), (size_t)a.D * 2, "out row (zero item)", 0x00, true);
     }
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_gather_kv(const AttnLaunch& p, hipStream_t stream) {
+  if (p.n_heads <= 0) return hipSuccess;
+  if (!p.gathered || p.gather_pad < 1 || !p.heads || !p.list_id || !p.ws) return hipErrorInvalidValue;
+  stub::note_launch(stream, "gather_kv_kernel");
+  for (int hb = 0; hb < p.n_heads * p.B; ++hb) {
+    const int hg = hb % p.n_heads, b = hb / p.n_heads;
+    const int head = read_word(p.heads + hg, "heads");
+    if (head < 0 || head >= p.H) {
+      stub::violation("gather: head %d", head);
+      continue;
+    }
+    const int* rec = p.ws + p.list_table + 4 * read_word(p.list_id + hg, "list_id");
+    touch_read(rec, 16, "list record");
+    const int* cols = p.ws + rec[0];
+    for (int j = 0; j < rec[1] && j < p.gather_pad; ++j) {
+      const int src = read_word(cols + j, "column list (gather)");
+      if (src >= p.L) stub::violation("gather: source row %d outside [0, %d)", src, p.L);
+      if (src >= 0 && src < p.L) {
+        touch_read(row_of(p.k, p, b, head, src), (size_t)p.D * 2, "k row (gather)", true);
+        touch_read(row_of(p.v, p, b, head, src), (size_t)p.D * 2, "v row (gather)", true);
+      }
+    }
+    touch_write(p.gathered + (size_t)hb * 2 * p.gather_pad * p.D, (size_t)2 * p.gather_pad * p.D * 2, "gathered rows", 0x00);
   }
   return hipSuccess;
 }

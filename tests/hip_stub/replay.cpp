@@ -117,12 +117,17 @@ void run_layer(const Layer& l) {
         return fp8 ? (l.tensors ? svd_attn_forward_fp8(plan, q, k, v, out, ws8, bytes8, s) : SVD_OK)
                    : svd_attn_forward_planned(plan, q, k, v, out, s);
       };
+      stub::new_forward();
       st = call(nullptr);   // eager, default stream
       expect(st == SVD_OK, l, fp8 ? "eager fp8 forward" : "eager forward", st);
+      if (l.tensors && st == SVD_OK)
+        expect(stub::out_rows_written() == static_cast<size_t>(l.B) * l.H * l.L, l, "every output row stored exactly once");
+      stub::new_forward();
       hipStream_t side = stub::create_stream();
       st = call(side);      // warm-up on the capture stream
       expect(st == SVD_OK, l, "forward on a caller stream", st);
       const long nodes_before = stub::captured_nodes();
+      stub::new_forward();
       stub::begin_capture(side);
       st = call(side);
       if (l.text > 0 && (l.tensors || !fp8)) {
@@ -140,6 +145,7 @@ void run_layer(const Layer& l) {
     // the per-group entry points address the same workspace
     int32_t n_groups = 0;
     svd_plan_num_groups(plan, &n_groups);
+    stub::new_forward();
     for (int32_t g = 0; g < n_groups; ++g) {
       st = svd_attn_forward_group(plan, g, q, k, v, out, nullptr);
       expect(st == SVD_OK, l, "svd_attn_forward_group", st);
@@ -164,16 +170,24 @@ void run_layer(const Layer& l) {
       svd_plan_single_launch(plan, &is_single);
       expect(is_single == 1, l, "the plan reports the single launch");
       const long before = stub::launches();
+      stub::new_forward();
       st = svd_attn_forward_planned(plan, q, k, v, out, nullptr);
       expect(st == SVD_OK, l, "single-launch forward", st);
-      expect(form == 1 ? stub::launches() == before + 2 : stub::launches() <= before + 3, l,
-             "a single-launch forward is two launches (fill + layer kernel), three at most with the dense head start");
+      if (l.tensors && st == SVD_OK)
+        expect(stub::out_rows_written() == static_cast<size_t>(l.B) * l.H * l.L, l, "every output row stored exactly once (layer kernel)");
+      stub::new_forward();
+      bool stripes = false;
+      for (int32_t m : l.table) stripes = stripes || m == SVD_VSTRIPE;
+      const long helpers = 1 + (stripes ? 1 : 0);   // the fill of the queue positions, the gather pre-pass of stripe heads
+      expect(form == 1 ? stub::launches() == before + 1 + helpers : stub::launches() <= before + 2 + helpers, l,
+             "a single-launch forward is the layer kernel plus its helpers (plus the dense head start in that form)");
       hipStream_t side = stub::create_stream();
       stub::begin_capture(side);
       st = svd_attn_forward_planned(plan, q, k, v, out, side);
       expect(l.text > 0 ? st == SVD_ERR_UNSUPPORTED : st == SVD_OK, l, "single-launch forward under capture", st);
       expect(stub::end_capture(side) == hipSuccess, l, "capture ends");
       stub::destroy_stream(side);
+      stub::new_forward();
       if (l.tensors) {
         st = svd_attn_forward_fp8(plan, q, k, v, out, ws8, bytes8, nullptr);   // the FP8 path runs such a plan group by group
         expect(st == SVD_OK, l, "fp8 forward with a single-launch plan", st);
@@ -186,12 +200,15 @@ void run_layer(const Layer& l) {
   if (l.text == 0) {
     // the entry point that allocates nothing: a miss (copy of the lists into the library's buffer),
     // a hit, and a hit under capture; a miss under capture is refused
+    stub::new_forward();
     int st = sparse_vdit_attn_forward_static(q, k, v, l.table.data(), l.params.data(), out, &desc, nullptr);
     expect(st == SVD_OK || st == SVD_ERR_STATIC_LIMIT, l, "static one-shot forward", st);
     if (st == SVD_OK) {
+      stub::new_forward();
       st = sparse_vdit_attn_forward_static(q, k, v, l.table.data(), l.params.data(), out, &desc, nullptr);
       expect(st == SVD_OK, l, "static one-shot forward, cached plan", st);
       hipStream_t side = stub::create_stream();
+      stub::new_forward();
       stub::begin_capture(side);
       st = sparse_vdit_attn_forward_static(q, k, v, l.table.data(), l.params.data(), out, &desc, side);
       expect(st == SVD_OK, l, "static one-shot forward under capture, cached plan", st);
@@ -204,6 +221,7 @@ void run_layer(const Layer& l) {
         st = sparse_vdit_attn_forward_static(q, k, v, other.data(), pp.data(), out, &desc, side);
         expect(st == SVD_ERR_UNSUPPORTED, l, "static one-shot forward under capture with a new table is refused", st);
         expect(stub::end_capture(side) == hipSuccess, l, "capture ends");
+        stub::new_forward();
         st = sparse_vdit_attn_forward_static(q, k, v, other.data(), pp.data(), out, &desc, side);
         expect(st == SVD_OK, l, "static one-shot forward with a new table on another stream", st);
       }
