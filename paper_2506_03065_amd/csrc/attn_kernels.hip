@@ -810,14 +810,21 @@ __device__ __forceinline__ void zero_item(const AttnLaunch& p, const int item) {
   }
 }
 
-// The item bodies of the layer kernel are real functions, not inlined: inlined
+// The segment loops of the layer kernel are real functions, not inlined: inlined
 // side by side into one kernel the four loop nests get in each other's way in the
-// register allocator (measured: the same band body ran 25 % slower than in a
-// kernel of its own); as callees each is allocated like the kernel it also is
+// register allocator; as callees each is allocated like the kernel it also is
 // elsewhere in this file.  Arguments of a callee travel in vector registers even
 // when they are uniform, so everything is made scalar again on entry.
-template <int D, int BC, int MODE>
-__device__ __attribute__((noinline)) void layer_item(const AttnLaunch av, const int item_v, const unsigned smem_v) {
+// One segment of the layer kernel: the work-group pulls items of the segment off the eight
+// queues, its own XCD's first, until all are empty.  A real function, called once per segment
+// (a call per item would save and restore the callee-saved half of the register file around
+// every item: measured as more than a gigabyte of scratch traffic per layer).
+// KIND = a MODE_* of attn_item, or kZeroKind for the zero fill of skipped heads.
+constexpr int kZeroKind = 100;
+template <int D, int BC, int KIND>
+__device__ __attribute__((noinline)) void layer_segment(const AttnLaunch av, const int first_item_v, const int n_rest_v,
+                                                        int* const counters_v, const int home_v, const unsigned smem_v,
+                                                        const unsigned pick_v) {
   AttnLaunch a;
   a.q = uni(av.q);
   a.k = uni(av.k);
@@ -843,9 +850,35 @@ __device__ __attribute__((noinline)) void layer_item(const AttnLaunch av, const 
   a.gathered = uni(av.gathered);
   a.gather_pad = uni(av.gather_pad);
   a.skip_q_blocks = uni(av.skip_q_blocks);
+  const int first_item = uni(first_item_v), n_rest = uni(n_rest_v), home = uni(home_v);
+  int* const counters = uni(counters_v);   // this segment's eight queue positions
   typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+  typedef __attribute__((address_space(3))) int* lds_int;
   unsigned char* const smem = (unsigned char*)(lds_bytes)(uintptr_t)uni((int)smem_v);
-  attn_item<D, 4, 1, BC, 2, MODE>(a, uni(item_v), smem);
+  lds_int const pick = (lds_int)(uintptr_t)uni((int)pick_v);
+  const int per = (n_rest + 7) >> 3;
+  // Every queue position only grows, so every loop below ends, and all waves of the
+  // work-group take the same path (the position is read by all of them after a barrier).
+  for (int probe = 0; probe < 8; ++probe) {
+    const int x = (home + probe) & 7;
+    int cnt = n_rest - x * per;
+    cnt = cnt < 0 ? 0 : (cnt > per ? per : cnt);
+    if (cnt == 0) continue;
+    for (;;) {
+      if (threadIdx.x == 0) *pick = atomicAdd(counters + x, 1);
+      __syncthreads();
+      const int pos = __builtin_amdgcn_readfirstlane(*pick);
+      // the next pick overwrites `pick`, the next item the LDS tiles: everyone must be done with both
+      if (pos >= cnt) {
+        __syncthreads();
+        break;
+      }
+      const int item = first_item + x * per + pos;
+      if (KIND == kZeroKind) zero_item<D>(a, item);
+      else attn_item<D, 4, 1, BC, 2, (KIND == kZeroKind ? MODE_DENSE : KIND)>(a, item, smem);
+      __syncthreads();
+    }
+  }
 }
 
 template <int D, int BC>
@@ -853,11 +886,12 @@ __global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BC * D * 2];
   __shared__ int pick;
   typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+  typedef __attribute__((address_space(3))) int* lds_int;
   const unsigned smem_addr = (unsigned)(uintptr_t)(lds_bytes)smem;
+  const unsigned pick_addr = (unsigned)(uintptr_t)(lds_int)&pick;
   const int home = blockIdx.x & 7;   // work-groups are dealt to the XCDs in turn
   // Segment after segment, heaviest first; inside a segment a work-group first drains
-  // its own XCD's eighth, then the other XCDs' eighths.  Every queue position only
-  // grows, so every loop below ends, and all waves of a work-group take the same path.
+  // its own XCD's eighth, then the other XCDs' eighths.
   for (int s = 0; s < lp.n_segments; ++s) {
     const LayerSegment sg = lp.seg[s];
     AttnLaunch a = lp.a;
@@ -867,31 +901,13 @@ __global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp
     a.heads = lp.a.ws + sg.heads;
     a.list_id = lp.a.ws + sg.list_id;
     a.list_table = sg.list_table;
-    const int per = (sg.n_items + 7) >> 3;
-    for (int probe = 0; probe < 8; ++probe) {
-      const int x = (home + probe) & 7;
-      int cnt = sg.n_items - x * per;
-      cnt = cnt < 0 ? 0 : (cnt > per ? per : cnt);
-      if (cnt == 0) continue;
-      for (;;) {
-        if (threadIdx.x == 0) pick = atomicAdd(lp.counters + s * 8 + x, 1);
-        __syncthreads();
-        const int pos = __builtin_amdgcn_readfirstlane(pick);
-        if (pos >= cnt) {
-          __syncthreads();   // the next pick overwrites `pick`
-          break;
-        }
-        const int item = sg.first_item + x * per + pos;
-        switch (sg.kind) {
-          case SEG_DENSE: layer_item<D, BC, MODE_DENSE>(a, item, smem_addr); break;
-          case SEG_BAND: layer_item<D, BC, MODE_BAND>(a, item, smem_addr); break;
-          case SEG_GATHER: layer_item<D, BC, MODE_GATHER>(a, item, smem_addr); break;
-          case SEG_PBAND: layer_item<D, BC, MODE_PBAND>(a, item, smem_addr); break;
-          default: zero_item<D>(a, item); break;
-        }
-        // the next pick overwrites `pick`, the next item the LDS tiles: everyone must be done with both
-        __syncthreads();
-      }
+    int* const counters = lp.counters + s * 8;
+    switch (sg.kind) {
+      case SEG_DENSE: layer_segment<D, BC, MODE_DENSE>(a, sg.first_item, sg.n_items, counters, home, smem_addr, pick_addr); break;
+      case SEG_BAND: layer_segment<D, BC, MODE_BAND>(a, sg.first_item, sg.n_items, counters, home, smem_addr, pick_addr); break;
+      case SEG_GATHER: layer_segment<D, BC, MODE_GATHER>(a, sg.first_item, sg.n_items, counters, home, smem_addr, pick_addr); break;
+      case SEG_PBAND: layer_segment<D, BC, MODE_PBAND>(a, sg.first_item, sg.n_items, counters, home, smem_addr, pick_addr); break;
+      default: layer_segment<D, BC, kZeroKind>(a, sg.first_item, sg.n_items, counters, home, smem_addr, pick_addr); break;
     }
   }
 }
