@@ -197,6 +197,7 @@ def run_stack(args, torch, np, svd, W, cpu_seconds=None, calib=None, dense_reps=
                    "launch_form": "layer kernel" if plans[0].single_launch() else "grouped launches"},
         "computed_tile_tflops": round(computed / 1e9 / ms_per_step, 1),
         "computed_tile_frac_of_bf16_peak": round(computed / 1e9 / ms_per_step / BF16_MFMA_PEAK_TFLOPS, 4),
+        "computed_tile_frac_of_measured_mfma_peak": round(computed / 1e9 / ms_per_step / calib["measured_mfma_peak_tflops"], 4) if calib and not fp8 else None,
         "dense_all_heads_ms": round(dense_ms * n_layers, 1),
         "speedup_vs_dense_kernel": round(dense_ms * n_layers / ms_per_step, 3),
         "flop_reduction_block_level": round(dense_flops / computed, 3),
