@@ -423,14 +423,14 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     # ---- the same layer through the other launch form (single launch <-> grouped launches) ----
     other = None
     if not fp8:
-        alt_single = 0 if plan.single_launch() else 1
+        alt_form = 2 if plan.single_launch() else 3      # grouped launches <-> layer kernel with dense head start
         ws_alt = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params,
-                                                          single_launch=alt_single or 2),
+                                                          single_launch=alt_form),
                              dtype=torch.uint8, device=dev)
         plan_alt = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws_alt,
-                                       single_launch=alt_single or 2)
+                                       single_launch=alt_form)
         alt_ms = gpu_time_ms(lambda: svd.svd_attn_forward_planned(plan_alt, q, k, v, out), args.steps, args.warmup, torch)
-        other = {"form": "single launch" if plan_alt.single_launch() else "grouped launches",
+        other = {"form": "layer kernel with dense head start" if plan_alt.single_launch() else "grouped launches",
                  "ms": round(alt_ms, 4),
                  "computed_tile_frac_of_bf16_peak": round(plan_alt.work()["computed_flops"] / 1e9 / alt_ms / BF16_MFMA_PEAK_TFLOPS, 4),
                  "dense_split": plan_alt.dense_split()}
@@ -524,7 +524,7 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
                    "text_tokens_with_dense_borders": text, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
-                   "launch_form": "layer kernel (single launch, dense head start by default)" if plan.single_launch() else "grouped launches",
+                   "launch_form": ("layer kernel" + (" alone" if args.single_launch == 1 else " with dense head start")) if plan.single_launch() else "grouped launches",
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
         "wall_ms_per_step": round(wall_ms, 4),
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),
