@@ -45,3 +45,30 @@ def test_repeated_forward_gives_the_same_bits(L, D, split):
         assert torch.equal(out.view(torch.int16), ref8.view(torch.int16)), f"FP8 call {it} differs from the first"
         if it % 3 == 2:
             plan.close()
+
+
+@pytest.mark.parametrize("L,D,form", [(1500, 128, 3), (1400, 64, 1)])
+def test_layer_kernel_gives_the_same_bits_whoever_takes_which_item(L, D, form):
+    """The single-launch path hands items to work-groups through atomically advanced queue positions: which
+    work-group computes which item changes from call to call, the result must not."""
+    wl = W.small(L=L, D=D, H=10, seed=75, B=2)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params, single_launch=form),
+                     dtype=torch.uint8, device=DEV)
+    ref = None
+    out = torch.empty_like(q)
+    for it in range(150):
+        if it % 3 == 0:
+            plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws, single_launch=form)
+            assert plan.single_launch()
+        out.fill_(float("nan"))
+        svd.svd_attn_forward_planned(plan, q, k, v, out)
+        if it % 2:                                  # back-to-back calls: the fill kernel of the next call follows at once
+            svd.svd_attn_forward_planned(plan, q, k, v, out)
+        torch.cuda.synchronize()
+        if ref is None:
+            ref = out.clone()
+        assert torch.equal(out.view(torch.int16), ref.view(torch.int16)), f"call {it} differs from the first"
+        if it % 3 == 2:
+            plan.close()

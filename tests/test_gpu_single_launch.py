@@ -86,10 +86,21 @@ def test_rearranged_heads_and_strided_layout():
     plan_g.close()
 
 
-def test_captured_single_launch_replays_to_the_eager_bits():
-    wl = W.small(L=1500, D=64, H=6, seed=71, B=2)
+@pytest.mark.parametrize("L,D,form", [(1500, 64, 1), (1300, 128, 0)])
+def test_captured_single_launch_replays_to_the_eager_bits(L, D, form):
+    """form 0 at D = 128: the library's own choice (gather pre-pass, fill, layer kernel)."""
+    wl = W.small(L=L, D=D, H=6, seed=71, B=2)
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
-    eager, plan, _ = run_plan(wl, q, k, v, single_launch=1)
+    if form:
+        eager, plan, _ = run_plan(wl, q, k, v, single_launch=form)
+    else:
+        desc = svd.desc_of(q)
+        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params), dtype=torch.uint8, device=DEV)
+        plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws)
+        assert plan.single_launch()
+        eager = torch.full_like(q, float("nan"))
+        svd.svd_attn_forward_planned(plan, q, k, v, eager)
+        torch.cuda.synchronize()
     out = torch.full_like(q, float("nan"))
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
