@@ -122,10 +122,12 @@ def test_captured_single_launch_replays_to_the_eager_bits(L, D, form):
     plan.close()
 
 
-def test_dense_head_start_covers_whole_rounds_and_leaves_the_rest_to_the_queues():
-    """26 dense heads of 11 256-row tiles: 286 dense items, of which 256 (one round of the 256 compute units) go
-    through the dense kernel; the queues' dense segment starts in the middle of a head, at a 128-row item."""
-    wl = W.small(L=2600, D=64, H=30, seed=19)
+@pytest.mark.parametrize("B", [1, 2])
+def test_dense_head_start_covers_whole_rounds_and_leaves_the_rest_to_the_queues(B):
+    """26 dense heads of 11 256-row tiles: 286 dense items per batch entry, of which 256 (B = 2: 512 of 572) go
+    through the dense kernel, whole rounds of the 256 compute units; the queues' dense segment starts in the middle
+    of a head (B = 2: of a head of the second batch entry), at a 128-row item."""
+    wl = W.small(L=2600, D=64, H=30, seed=19, B=B)
     for h in range(4, 30):
         wl.strategy_table[h] = W.DENSE
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
