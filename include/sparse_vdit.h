@@ -282,7 +282,8 @@ svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
  * workspace: code running under HIP stream capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same result as sparse_vdit_attn_forward, but the
  * compiled lists and the partial results of split dense heads live in a buffer of
- * SVD_STATIC_SCRATCH_BYTES (64 MiB) that is part of the library's device image:
+ * SVD_STATIC_SCRATCH_BYTES (64 MiB) that is part of the library's device image
+ * (as are the gathered rows of stripe heads and the layer kernel's queue positions):
  * every GPU the library runs on holds its own copy until the process ends.  The
  * call allocates no device memory and creates no streams or events; the groups of
  * the layer run one after the other on hip_stream.  A layer whose split dense
@@ -293,8 +294,10 @@ svd_status sparse_vdit_attn_forward(const void* q, const void* k, const void* v,
  * the call waits for that copy - which a capturing stream cannot record
  * (SVD_ERR_UNSUPPORTED), so the first call for a layer belongs before the capture.
  * All calls on one GPU share the buffer, and it keeps what the last call left in
- * it (nothing in it needs to start at zero): calls that overlap in time on one
- * GPU race, whatever their streams.  No text prefix (the call takes no options). */
+ * it; the one thing that must start at zero, the queue positions of the layer
+ * kernel, is cleared by a fill kernel in every call, and the gathered K/V rows of
+ * vertical-stripe heads are rewritten by every call.  Calls that overlap in time
+ * on one GPU race, whatever their streams.  No text prefix (the call takes no options). */
 #define SVD_STATIC_SCRATCH_BYTES (64u << 20)
 svd_status sparse_vdit_attn_forward_static(const void* q, const void* k, const void* v,
                                            const int32_t* strategy_table,

@@ -152,3 +152,21 @@ def test_benchmark_shapes_sampled_rows(name, form):
     check_layer(wl, q, k, v, one, rows=rows)
     plan.close()
     plan_g.close()
+
+
+@pytest.mark.parametrize("form", [1, 3])
+@pytest.mark.parametrize("modes", [[W.SKIP] * 3, [W.DENSE] * 2, [W.VSTRIPE] * 3, [W.DIAG], [W.SKIP, W.MULTIDIAG]])
+def test_degenerate_tables(modes, form):
+    """Layers made of one mode only (a single segment, or none that computes), one head, skip plus one pattern."""
+    L, D = 700, 128
+    base = W.small(L=L, D=D, H=5, seed=23)                      # one parameter set per mode to borrow from
+    by_mode = {int(m): p for m, p in zip(base.strategy_table, base.pattern_params)}
+    wl = W.Workload("degenerate", -1, 1, len(modes), L, D, base.frame_tokens, base.n_frames, 0,
+                    np.asarray(modes, dtype=np.int32), [dict(by_mode[int(m)]) for m in modes], 99)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    one, plan, _ = run_plan(wl, q, k, v, single_launch=form)
+    grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
+    assert_same_bits(one, grouped)
+    check_layer(wl, q, k, v, one)
+    plan.close()
+    plan_g.close()
