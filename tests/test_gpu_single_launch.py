@@ -139,19 +139,21 @@ def test_dense_head_start_covers_whole_rounds_and_leaves_the_rest_to_the_queues(
     plan_g.close()
 
 
-@pytest.mark.parametrize("form", [1, 3])
 @pytest.mark.parametrize("name", ["cogvideox1.5", "hunyuanvideo", "wan2.1"])
-def test_benchmark_shapes_sampled_rows(name, form):
+def test_benchmark_shapes_sampled_rows(name):
+    """Both forms (the layer kernel alone, and after the dense head start) at the benchmark shapes."""
     wl = W.BY_NAME[name]()
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
-    one, plan, _ = run_plan(wl, q, k, v, single_launch=form)
-    assert torch.isfinite(one.float()).all()
     grouped, plan_g, _ = run_plan(wl, q, k, v, single_launch=2, dense_split=1)
-    assert_same_bits(one, grouped)
-    rows = W.sample_rows(wl, n_random=24)
-    check_layer(wl, q, k, v, one, rows=rows)
-    plan.close()
     plan_g.close()
+    rows = W.sample_rows(wl, n_random=24)
+    for form in (1, 3):
+        one, plan, _ = run_plan(wl, q, k, v, single_launch=form)
+        assert torch.isfinite(one.float()).all()
+        assert_same_bits(one, grouped)
+        if form == 3:
+            check_layer(wl, q, k, v, one, rows=rows)
+        plan.close()
 
 
 @pytest.mark.parametrize("form", [1, 3])
