@@ -273,8 +273,9 @@ def run_rearranged(args, torch, np, svd, W):
     desc = svd.desc_of(q)
 
     def planned(table, params):
-        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, table, params), dtype=torch.uint8, device=dev)
-        return svd.svd_plan_create(desc, table, params, workspace=ws), ws
+        ws = torch.empty(svd.svd_plan_workspace_bytes(desc, table, params, single_launch=args.single_launch),
+                         dtype=torch.uint8, device=dev)
+        return svd.svd_plan_create(desc, table, params, workspace=ws, single_launch=args.single_launch), ws
     multi, ws_a = planned(np.full(H, W.MULTIDIAG, dtype=np.int32),
                           [{"half_width": w, "offsets": tuple(kk * N for kk in range(-(F - 1), F))}] * H)
     Wd = w * F + F - 1

@@ -143,10 +143,12 @@ typedef struct {
  * filled) first go through the dense kernel on its 256-row tile, which reuses a
  * K/V tile in LDS for twice as many rows; the rest of the dense group and
  * everything else is the layer kernel's.  Same bits.
- * 2 = grouped launches.  0 = the library's choice: form 3 for D = 128 (head start), grouped
- * launches for D = 64 (there the 128-row tile costs the dense items more than
- * the filled tails bring), and grouped launches whenever dense_split > 1 is
- * forced, the block shape is not the kernels' or no device is present.  1 and 3
+ * 2 = grouped launches.  0 = the library's choice: form 3 for D = 128 when the
+ * layer's items are long (48 key tiles per item or more, averaged over the heads
+ * that compute: picking an item costs a few microseconds), grouped launches
+ * otherwise - for D = 64 (there the 128-row tile costs the dense items more than
+ * the filled tails bring), for short items, whenever dense_split > 1 is forced,
+ * the block shape is not the kernels' or no device is present.  1 and 3
  * need the kernels' block shape (SVD_ERR_UNSUPPORTED otherwise) and a device
  * (SVD_ERR_HIP).  The split of the dense heads is still chosen and its scratch
  * still part of the workspace: the FP8 forward pass and the per-group entry

@@ -90,12 +90,40 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
 // D = 128 and 14 % at D = 64 (measured); the head start takes most of that back for the dense group.  So: head start
 // form at D = 128, grouped launches at D = 64 - and grouped launches whenever the caller forces a dense split or there
 // is no device to size the grid from.
-int layer_form(const svd_plan_options* opt, const svd_tensor_desc& d, bool native, int n_cu) {
+int layer_form(const svd_plan_options* opt, const svd_tensor_desc& d, bool native, int n_cu, double tiles_per_item) {
   const int asked = opt ? opt->single_launch : 0;
   if (asked == 1 || asked == 3) return asked;
   if (asked == 2 || !native || n_cu < 1) return 0;
   if (opt && opt->dense_split > 1) return 0;
+  // picking an item off a queue costs a few microseconds (an atomic round trip, two barriers): with short items
+  // (narrow windows, short sequences) that outweighs the tails (measured: 29 key tiles per item, 8 % slower)
+  if (tiles_per_item < 48.0) return 0;
   return d.D == 128 ? 3 : 0;
+}
+
+// Key tiles per item of the layer on the 128-row tile, averaged over the heads that compute (what the
+// library's choice of the launch form looks at; taken from the table and parameters alone).
+double mean_tiles_per_item(const svd_tensor_desc& d, const int32_t* table, const svd_head_params* pp, int block_k,
+                           int text_tokens) {
+  const double n_kb = std::ceil(static_cast<double>(d.L) / block_k);
+  const double rows = svd::layer_block_q(d.D);
+  double tiles = 0.0;
+  int heads = 0;
+  for (int h = 0; h < d.H; ++h) {
+    double t = 0.0;
+    switch (table[h]) {
+      case SVD_DENSE: t = n_kb; break;
+      case SVD_DIAG: t = (2.0 * pp[h].half_width + rows) / block_k + 1.0; break;
+      case SVD_MULTIDIAG:
+        t = (pp[h].rearr_frames > 0 ? 1 : (pp[h].n_offsets > 0 ? pp[h].n_offsets : 1)) * ((2.0 * pp[h].half_width + rows) / block_k + 1.0);
+        break;
+      case SVD_VSTRIPE: t = std::ceil(static_cast<double>(pp[h].n_cols + text_tokens) / block_k); break;
+      default: continue;
+    }
+    tiles += t < n_kb ? t : n_kb;
+    ++heads;
+  }
+  return heads ? tiles / heads : 0.0;
 }
 
 // The small query tile is offered to the band groups only when the caller left
@@ -323,7 +351,8 @@ svd_status svd_plan_workspace_bytes(const svd_tensor_desc* desc, const int32_t* 
   if (svd_status st = resolve_blocks(*desc, options, &bq, &bk, &native)) return st;
   Plan tmp;
   const int n_cu = device_compute_units();
-  const int form = layer_form(options, *desc, native, n_cu);
+  const int form = layer_form(options, *desc, native, n_cu,
+                              mean_tiles_per_item(*desc, strategy_table, pattern_params, bk, options ? options->text_tokens : 0));
   const bool single = form != 0;
   if (svd_status st = svd::compile_plan(*desc, strategy_table, pattern_params, bq, bk,
                                         options ? options->text_tokens : 0, small_block_q(*desc, options), &tmp, single))
@@ -408,7 +437,15 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
   svd_plan* sp = new (std::nothrow) svd_plan();
   if (!sp) return SVD_ERR_HIP;
   svd_status st = SVD_OK;
-  const int form = device_workspace ? layer_form(options, *desc, native, device_compute_units()) : 0;
+  for (int h = 0; h < desc->H; ++h)
+    if (strategy_table[h] < SVD_DENSE || strategy_table[h] > SVD_VSTRIPE) {
+      delete sp;
+      return SVD_ERR_MODE;
+    }
+  const int form = device_workspace
+                       ? layer_form(options, *desc, native, device_compute_units(),
+                                    mean_tiles_per_item(*desc, strategy_table, pattern_params, bk, options ? options->text_tokens : 0))
+                       : 0;
   if (device_workspace && options && (options->single_launch == 1 || options->single_launch == 3) && device_compute_units() < 1) {
     delete sp;
     return SVD_ERR_HIP;   // the layer kernel is sized from the compute-unit count

@@ -88,12 +88,16 @@ using Int = std::integral_constant<int, N>;
 // Uniform values held in vector registers (arguments of a non-inlined function, words loaded
 // through a vector load) moved to scalar registers; a no-op on values that already are scalar.
 __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+// (Every pointer that goes through here points into global memory.  Rebuilt from two integers it
+// would be a pointer of unknown address space and every access through it a FLAT access, which is
+// slower and shares the LDS counter; the detour through the global address space keeps them global.)
 template <typename T>
 __device__ __forceinline__ T* uni(T* ptr) {
   const unsigned long long u = (unsigned long long)ptr;
   const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
   const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
-  return (T*)(((unsigned long long)hi << 32) | lo);
+  typedef T __attribute__((address_space(1)))* global_ptr;
+  return (T*)(global_ptr)(uintptr_t)(((unsigned long long)hi << 32) | lo);
 }
 __device__ __forceinline__ int64_t uni(int64_t x) {
   const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(unsigned long long)x);
@@ -645,7 +649,8 @@ __device__ __forceinline__ void attn_item(const AttnLaunch& p, const int item, u
   // register (each a coalesced 256-byte row of the wave) ----
   if (MODE == MODE_DENSE && p.split > 1) {
     static_assert(MODE != MODE_DENSE || QB == 1, "the split path keeps one 32-row block per wave");
-    float* dst = p.partial + ((size_t)item * NW + wave) * ((DB * 16 + 2) * 64) + lane;
+    typedef float __attribute__((address_space(1)))* global_float_ptr;   // global stores, not FLAT ones
+    global_float_ptr dst = (global_float_ptr)(uintptr_t)(p.partial + ((size_t)item * NW + wave) * ((DB * 16 + 2) * 64) + lane);
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll

@@ -86,10 +86,11 @@ def test_rearranged_heads_and_strided_layout():
     plan_g.close()
 
 
-@pytest.mark.parametrize("L,D,form", [(1500, 64, 1), (1300, 128, 0)])
+@pytest.mark.parametrize("L,D,form", [(1500, 64, 1), (9000, 128, 0)])
 def test_captured_single_launch_replays_to_the_eager_bits(L, D, form):
-    """form 0 at D = 128: the library's own choice (gather pre-pass, fill, layer kernel)."""
-    wl = W.small(L=L, D=D, H=6, seed=71, B=2)
+    """form 0 at D = 128 on a layer whose items are long enough: the library's own choice is the layer kernel
+    (gather pre-pass, fill, layer kernel)."""
+    wl = W.small(L=L, D=D, H=6, seed=71, B=2 if form else 1)
     q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
     if form:
         eager, plan, _ = run_plan(wl, q, k, v, single_launch=form)
