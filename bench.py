@@ -397,6 +397,8 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
                                single_launch=args.single_launch)
     plan_ms = (time.perf_counter() - t0) * 1e3
     work = plan.work()
+    if fp8:      # the FP8 path walks small-tile lists in every band group
+        work = dict(work, **plan.work_fp8())
 
     # ---- the timed region: K full-layer steps ----
     step16 = lambda: svd.svd_attn_forward_planned(plan, q, k, v, out)
@@ -441,7 +443,7 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     # ---- per-group kernels (one launch each), HIP events on the launch stream ----
     groups = []
     for gi, g in enumerate(plan.groups()):
-        gw = plan.work(gi)
+        gw = plan.work_fp8(gi) if fp8 else plan.work(gi)
         run_group = ((lambda: svd.svd_attn_forward_fp8_group(plan, gi, q, k, v, out, ws8)) if fp8 else
                      (lambda: svd.svd_attn_forward_group(plan, gi, q, k, v, out)))
         ms = gpu_time_ms(run_group, max(3, args.steps // 2), 1, torch)

@@ -198,10 +198,11 @@ svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch);
 svd_status svd_plan_num_groups(const svd_plan* plan, int32_t* n_groups);
 /* Block shape of one group's lists and launches.  block_k is the plan's; block_q
  * is the plan's too, except for a band group (modes 2, 3) of a plan created
- * without an explicit block shape: when its lists cover at least 1 % less area
+ * without an explicit block shape: when its lists cover at least 8 % less area
  * with the kernels' small query tile (128 rows instead of 256: the listed tiles
- * hug the bands more closely, and two work-groups share a compute unit), the
- * group is compiled and launched with it.
+ * hug the bands more closely, and two work-groups share a compute unit; the
+ * large tile is the faster one per listed FLOP), the group is compiled and
+ * launched with it - always, in a plan that runs through the layer kernel.
  * svd_plan_band_list reports the matching number of query blocks. */
 svd_status svd_plan_group_blocks(const svd_plan* plan, int32_t group, int32_t* block_q, int32_t* block_k);
 /* (Rearranged multi-diagonal heads form a group of their own, after the plain
@@ -245,6 +246,13 @@ svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* 
 /* The same figures for one group (all its heads, all batch entries). */
 svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* computed_tiles,
                                double* computed_flops, double* kept_pairs);
+
+/* The work of the FP8 forward pass (svd_attn_forward_fp8): its band groups always walk
+ * small-tile lists (kept in the plan beside the lists of a group that the bf16
+ * kernels run on the large tile), so their tile count and listed area can differ
+ * from svd_plan_group_work.  group = -1: the whole layer. */
+svd_status svd_plan_group_work_fp8(const svd_plan* plan, int32_t group, int64_t* computed_tiles,
+                                   double* computed_flops);
 
 /* Forward pass of one layer with a compiled plan (Section 4.2: one fused launch
  * per mode present in the table, heaviest group first, plus a zero fill for

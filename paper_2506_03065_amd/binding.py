@@ -24,7 +24,7 @@ SVD_DENSE, SVD_SKIP, SVD_DIAG, SVD_MULTIDIAG, SVD_VSTRIPE = range(5)
 
 EXPORTS = ["svd_default_blocks", "svd_plan_workspace_bytes", "svd_plan_create", "svd_plan_destroy",
            "svd_plan_dense_split", "svd_plan_single_launch", "svd_plan_num_groups", "svd_plan_group_info", "svd_plan_group_rearranged", "svd_plan_group_blocks", "svd_plan_row_map", "svd_plan_band_list", "svd_plan_column_list",
-           "svd_plan_work", "svd_plan_group_work", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward", "sparse_vdit_attn_forward_static",
+           "svd_plan_work", "svd_plan_group_work", "svd_plan_group_work_fp8", "svd_attn_forward_planned", "svd_attn_forward_group", "sparse_vdit_attn_forward", "sparse_vdit_attn_forward_static",
            "svd_dense_attn_forward", "svd_status_string",
            "svd_head_mse_workspace_bytes", "svd_head_mse", "svd_plan_head_sparsity", "svd_plan_head_block_sparsity", "svd_search_select",
            "svd_select_heads", "svd_search_layer_workspace_bytes", "svd_search_layer",
@@ -83,6 +83,7 @@ def lib():
             "svd_plan_column_list": [vp, C.c_int32, C.c_int32, i32p, i32p, i32pp],
             "svd_plan_work": [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
             "svd_plan_group_work": [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
+            "svd_plan_group_work_fp8": [vp, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double)],
             "svd_attn_forward_planned": [vp, vp, vp, vp, vp, vp],
             "svd_attn_forward_group": [vp, C.c_int32, vp, vp, vp, vp, vp],
             "sparse_vdit_attn_forward": [vp, vp, vp, i32p, hpp, vp, descp, vp, C.c_size_t, vp],
@@ -285,6 +286,13 @@ class Plan:
         _check(lib().svd_plan_column_list(self.handle, group, lst, C.byref(n), C.byref(padded), C.byref(cols)),
                "svd_plan_column_list")
         return {"n_cols": n.value, "cols": _copy(cols, padded.value)}
+
+    def work_fp8(self, group=None):
+        """Tiles and FLOPs the FP8 forward pass computes (band groups always on the small query tile)."""
+        tiles, flops = C.c_int64(), C.c_double()
+        _check(lib().svd_plan_group_work_fp8(self.handle, -1 if group is None else group, C.byref(tiles), C.byref(flops)),
+               "svd_plan_group_work_fp8")
+        return {"computed_tiles": tiles.value, "computed_flops": flops.value}
 
     def work(self, group=None):
         tiles, flops, pairs = C.c_int64(), C.c_double(), C.c_double()

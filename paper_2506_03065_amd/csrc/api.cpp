@@ -626,8 +626,10 @@ svd_status svd_plan_column_list(const svd_plan* plan, int32_t group, int32_t lis
   return SVD_OK;
 }
 
-static void group_work(const Plan& p, const svd::Group& g, int64_t* tiles, double* area, double* pairs) {
+// fp8: the lists the FP8 path walks (band groups always on the small query tile)
+static void group_work(const Plan& p, const svd::Group& g, int64_t* tiles, double* area, double* pairs, bool fp8 = false) {
   const double L = p.desc.L;
+  const std::vector<svd::BandList>& bands = fp8 && !g.bands_small.empty() ? g.bands_small : g.bands;
   for (size_t t = 0; t < g.heads.size(); ++t) {
     switch (g.mode) {
       case SVD_DENSE:
@@ -637,7 +639,7 @@ static void group_work(const Plan& p, const svd::Group& g, int64_t* tiles, doubl
         break;
       case SVD_DIAG:
       case SVD_MULTIDIAG: {
-        const svd::BandList& bl = g.bands[g.list_id[t]];
+        const svd::BandList& bl = bands[g.list_id[t]];
         *tiles += static_cast<int64_t>(bl.kv_block_idx.size());
         *area += bl.tile_area;
         *pairs += bl.kept_pairs;   // text borders included
@@ -671,6 +673,20 @@ svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* 
   if (computed_tiles) *computed_tiles = tiles * p.desc.B;
   if (computed_flops) *computed_flops = 4.0 * p.desc.D * area * p.desc.B;
   if (kept_pairs) *kept_pairs = pairs * p.desc.B;
+  return SVD_OK;
+}
+
+svd_status svd_plan_group_work_fp8(const svd_plan* plan, int32_t group, int64_t* computed_tiles,
+                                   double* computed_flops) {
+  if (!plan) return SVD_ERR_NULL;
+  const Plan& p = plan->p;
+  if (group < -1 || group >= static_cast<int32_t>(p.groups.size())) return SVD_ERR_SHAPE;
+  int64_t tiles = 0;
+  double area = 0.0, pairs = 0.0;
+  for (int32_t gi = 0; gi < static_cast<int32_t>(p.groups.size()); ++gi)
+    if (group < 0 || gi == group) group_work(p, p.groups[gi], &tiles, &area, &pairs, true);
+  if (computed_tiles) *computed_tiles = tiles * p.desc.B;
+  if (computed_flops) *computed_flops = 4.0 * p.desc.D * area * p.desc.B;
   return SVD_OK;
 }
 
@@ -1289,6 +1305,13 @@ static svd_status launch_group_fp8(const svd_plan& sp, const svd::Group& g, cons
     a.partial = reinterpret_cast<float*>(static_cast<char*>(p.device_workspace) + sp.partial_offset);
   }
   bool small_q = g.block_q != p.block_q;
+  if (!small_q && !g.bands_small.empty()) {
+    // a band group that the bf16 kernels run on the large query tile: the FP8 kernels take the small-tile lists
+    small_q = true;
+    a.list_table = static_cast<int>(g.ws_list_table_small);
+    a.n_q_blocks = g.n_q_blocks_small;
+    a.n_items = a.n_q_blocks * a.n_heads * a.B;
+  }
   if (g.mode == SVD_VSTRIPE && p.launchable) {
     // a compacted stripe head is walked like a short dense head: no list depends on the query tile, and
     // the FP8 kernel runs faster with two small work-groups per compute unit (measured 6-9 %)

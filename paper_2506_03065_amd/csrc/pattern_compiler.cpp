@@ -294,8 +294,11 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
     if (g.heads.empty()) continue;
     g.block_q = block_q;
     if (!g.bands.empty() && block_q_small > 0 && block_q_small < block_q && T % block_q_small == 0) {
-      // the same lists on the small query tile: taken unless the bands are so wide that it saves
-      // less than 1 % of the area (then the halved reuse of a K/V tile costs more than it brings)
+      // the same lists on the small query tile: taken when it saves at least 8 % of the listed area.  The
+      // 256-row tile reuses a K/V tile in LDS for twice as many rows and runs 6 % (D = 128) to 11 % (D = 64)
+      // faster per listed FLOP (measured on the diagonal groups of the benchmark layers, which hold 2-3 %
+      // less area on the small tile and are 4-7 % faster on the large one; the multi-diagonal groups, 6-9 %
+      // less area, break even)
       std::vector<BandList> alt;
       for (const BandList& bl : g.bands) {
         BandList a;
@@ -311,9 +314,12 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
         area += g.bands[g.list_id[t]].tile_area;
         area_small += alt[g.list_id[t]].tile_area;
       }
-      if (always_small || area_small < 0.99 * area) {
+      if (always_small || area_small < 0.92 * area) {
         g.bands.swap(alt);
         g.block_q = block_q_small;
+      } else {
+        g.bands_small.swap(alt);
+        g.n_q_blocks_small = static_cast<int32_t>(ceil_div(L, block_q_small));
       }
     }
     g.n_q_blocks = static_cast<int32_t>(ceil_div(L, g.block_q));
@@ -328,23 +334,30 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
     g.ws_list_id = append(&img, g.list_id);
     const size_t n_lists = g.bands.size() + g.columns.size();
     g.ws_list_table = append(&img, std::vector<int32_t>(n_lists * kListRecordWords, 0));
-    for (size_t l = 0; l < g.bands.size(); ++l) {
-      const BandList& bl = g.bands[l];
-      std::vector<int32_t> entries(bl.kv_block_idx.size() * 2);
-      for (size_t e = 0; e < bl.kv_block_idx.size(); ++e) {
-        entries[2 * e] = bl.kv_block_idx[e];
-        entries[2 * e + 1] = bl.flags[e] | (bl.run_first[e] << 1) | (bl.run_count[e] << 16);
+    auto emit_band_lists = [&img](const std::vector<BandList>& lists, size_t table) {
+      for (size_t l = 0; l < lists.size(); ++l) {
+        const BandList& bl = lists[l];
+        std::vector<int32_t> entries(bl.kv_block_idx.size() * 2);
+        for (size_t e = 0; e < bl.kv_block_idx.size(); ++e) {
+          entries[2 * e] = bl.kv_block_idx[e];
+          entries[2 * e + 1] = bl.flags[e] | (bl.run_first[e] << 1) | (bl.run_count[e] << 16);
+        }
+        const size_t rp = append(&img, bl.row_ptr), en = append(&img, entries), ru = append(&img, bl.runs);
+        int32_t* rec = img.data() + table + l * kListRecordWords;
+        rec[0] = static_cast<int32_t>(rp);
+        rec[1] = static_cast<int32_t>(en);
+        rec[2] = static_cast<int32_t>(ru);
+        rec[3] = static_cast<int32_t>(bl.runs.size() / 2);
+        if (!bl.row_map.empty()) {
+          const size_t rm = append(&img, bl.row_map);
+          img[table + l * kListRecordWords + 3] = static_cast<int32_t>(rm);   // append may have moved the image
+        }
       }
-      const size_t rp = append(&img, bl.row_ptr), en = append(&img, entries), ru = append(&img, bl.runs);
-      int32_t* rec = img.data() + g.ws_list_table + l * kListRecordWords;
-      rec[0] = static_cast<int32_t>(rp);
-      rec[1] = static_cast<int32_t>(en);
-      rec[2] = static_cast<int32_t>(ru);
-      rec[3] = static_cast<int32_t>(bl.runs.size() / 2);
-      if (!bl.row_map.empty()) {
-        const size_t rm = append(&img, bl.row_map);
-        img[g.ws_list_table + l * kListRecordWords + 3] = static_cast<int32_t>(rm);   // append may have moved the image
-      }
+    };
+    emit_band_lists(g.bands, g.ws_list_table);
+    if (!g.bands_small.empty()) {
+      g.ws_list_table_small = append(&img, std::vector<int32_t>(g.bands_small.size() * kListRecordWords, 0));
+      emit_band_lists(g.bands_small, g.ws_list_table_small);
     }
     for (size_t l = 0; l < g.columns.size(); ++l) {
       const ColumnList& cl = g.columns[l];

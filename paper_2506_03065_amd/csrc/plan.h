@@ -47,9 +47,14 @@ struct Group {
   std::vector<int32_t> heads;         // ascending
   std::vector<int32_t> list_id;       // per head of the group
   std::vector<BandList> bands;        // modes 2, 3
+  // the same patterns on the small query tile, kept beside `bands` when the group itself runs on the
+  // large one: the FP8 kernels run band groups faster on the small tile whatever the band width
+  std::vector<BandList> bands_small;
+  int32_t n_q_blocks_small = 0;
   std::vector<ColumnList> columns;    // mode 4
   // word offsets into the device workspace (valid when the plan is launchable)
   size_t ws_heads = 0, ws_list_id = 0, ws_list_table = 0;
+  size_t ws_list_table_small = 0;     // list records of bands_small (0: none)
 };
 
 // Per-list record in the device workspace, 4 int32 words.
@@ -80,7 +85,7 @@ struct Plan {
 // are computed densely by the caller of the kernels), every other query block
 // lists the text key tiles, kept whole, ahead of its band tiles, and the column
 // lists gain the text columns.
-// block_q_small > 0: band groups (modes 2 and 3) whose lists cover at least 1 %
+// block_q_small > 0: band groups (modes 2 and 3) whose lists cover at least 8 %
 // less area with that many query rows per tile are compiled for it; with
 // always_small every band group is (the single-launch path runs every item on
 // the small query tile).

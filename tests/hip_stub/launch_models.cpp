@@ -188,7 +188,7 @@ hipError_t model_attention(const AttnLaunch& p, const Fp8Launch* f8, int mode, h
   if (small_q && !f8 && mode != MODE_BAND && mode != MODE_PBAND) return hipErrorInvalidValue;
   if (small_q && f8 && mode == MODE_DENSE) return hipErrorInvalidValue;
   const int space = p.n_q_blocks * p.n_heads * p.B * p.split;
-  if (p.n_items != space && !(mode == MODE_DENSE && p.split == 1 && p.n_items > 0 && p.n_items < space))
+  if (p.n_items != space && !(mode == MODE_DENSE && p.split == 1 && p.n_items > 0 && p.n_items < space))   // the dense head start
     stub::violation("n_items does not match the item space");
   stub::note_launch(stream, f8 ? "attn_fwd_fp8_kernel" : "attn_fwd_kernel");
   for (int item = 0; item < p.n_items; ++item) model_item(p, f8, mode, small_q, item);

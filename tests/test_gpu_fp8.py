@@ -278,3 +278,32 @@ def test_benchmark_shape_sampled_rows_and_closed_form(name):
         h = int(np.nonzero(wl.strategy_table == mode)[0][0])
         want = _windowed_means(F8.quantise_v(f64(v[0, h].cpu())), mode, wl.pattern_params[h], wl.L)
         assert_close(f64(out0[0, h].cpu()), want, f"fp8 {name} zero-q head {h} mode {mode}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_wide_bands_fp8_walks_the_small_tile_lists(D):
+    """Band groups that the bf16 kernels run on the large query tile (wide bands): the FP8 path takes the small-tile
+    lists the plan keeps beside them.  Grouped launches asked for explicitly, so that the bf16 lists stay large."""
+    L = 2500
+    table = np.asarray([W.DIAG, W.MULTIDIAG, W.DENSE, W.DIAG], dtype=np.int32)
+    params = [{"half_width": 1100, "offsets": (0,), "cols": ()}, {"half_width": 380, "offsets": (-900, 0, 900), "cols": ()},
+              {"half_width": 0, "offsets": (), "cols": ()}, {"half_width": 1100, "offsets": (0,), "cols": ()}]
+    wl = W.Workload("wide-bands", -1, 1, 4, L, D, 500, 5, 0, table, params, 77)
+    q, k, v = _cuda(W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, table, params, single_launch=2), dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, table, params, workspace=ws, single_launch=2)
+    bq, _ = svd.svd_default_blocks(D)
+    assert all(g["block_q"] == bq for g in plan.groups())
+    assert plan.work_fp8()["computed_tiles"] != plan.work()["computed_tiles"]
+    ws8 = torch.full((svd.svd_fp8_workspace_bytes(desc),), 0x7f, dtype=torch.uint8, device=DEV)
+    out = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_fp8(plan, q, k, v, out, ws8)
+    torch.cuda.synchronize()
+    check_layer_fp8(wl, q, k, v, out)
+    out16 = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_planned(plan, q, k, v, out16)
+    torch.cuda.synchronize()
+    from parity_util import check_layer
+    check_layer(wl, q, k, v, out16)
+    plan.close()

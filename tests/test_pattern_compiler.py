@@ -378,8 +378,8 @@ def _stack_band_lists(plan):
 @pytest.mark.parametrize("layer", range(40))
 def test_every_stack_layer_compiles_to_the_oracles_groups_and_lists(layer):
     """All 40 strategy tables of the layer stack (dense share falling from 80 % to 10 % with depth), host only,
-    both with the kernels' block shape given explicitly and in the plan the library compiles by default (band
-    groups on the small query tile): mode counts, groups, list ids, every column list and the runs of kept
+    both with the kernels' block shape given explicitly and in the plan the library compiles by default (the query
+    tile of the band groups is its choice): mode counts, groups, list ids, every column list and the runs of kept
     diagonals bit-exact against the oracle; element counts against the closed forms.  The band patterns are the
     same in every layer, so the band lists must equal those of the first layer bit for bit, and those are
     compared with the oracle's explicit-mask entries on sampled query blocks."""
@@ -394,7 +394,7 @@ def test_every_stack_layer_compiles_to_the_oracles_groups_and_lists(layer):
     explicit = _compile(wl, bq, bk)
     default = svd.svd_plan_create(svd.tensor_desc(wl.B, wl.H, wl.L, wl.D), wl.strategy_table, wl.pattern_params)
     lists = {**_stack_band_lists(explicit), **_stack_band_lists(default)}
-    assert {k[1] for k in lists} == {bq, 128}                     # the default plan runs the band groups on 128 rows
+    assert {k[1] for k in lists} <= {bq, 128}                     # the default plan picks the query tile per band group
     if first:
         _STACK_BAND_LISTS.update(lists)
     for key, bl in lists.items():
@@ -406,3 +406,29 @@ def test_every_stack_layer_compiles_to_the_oracles_groups_and_lists(layer):
     assert default.work()["kept_pairs"] == float(want_pairs) == explicit.work()["kept_pairs"]
     _assert_plan_matches_oracle(wl, bq, bk, q_blocks=sample, plan=explicit)
     _assert_plan_matches_oracle(wl, bq, bk, q_blocks=sample, plan=default)
+
+
+def test_wide_bands_run_on_the_large_tile_and_keep_small_tile_lists_for_the_fp8_path():
+    """A band so wide that the small query tile saves less than 8 % of the listed area: the group is compiled for
+    the large tile, and the plan keeps the small-tile lists for the FP8 kernels; their tile count is the oracle's."""
+    L, D = 3000, 64
+    table = np.asarray([W.DIAG, W.MULTIDIAG, W.DENSE], dtype=np.int32)
+    params = [{"half_width": 1200}, {"half_width": 400, "offsets": (-1000, 0, 1000)}, {}]
+    desc = svd.tensor_desc(1, 3, L, D)
+    plan = svd.svd_plan_create(desc, table, params)
+    bq, bk = svd.svd_default_blocks(D)
+    groups = plan.groups()
+    assert [g["block_q"] for g in groups] == [bq, bq, bq]
+    for gi, g in enumerate(groups):
+        mode = g["mode"]
+        if mode == W.DENSE:
+            assert plan.work_fp8(gi)["computed_tiles"] == plan.work(gi)["computed_tiles"]
+            continue
+        p = params[g["heads"][0]]
+        large = O.block_lists(mode, p, L, bq, bk)["kv_block_idx"].size
+        small = O.block_lists(mode, p, L, bq // 2, bk)["kv_block_idx"].size
+        assert plan.work(gi)["computed_tiles"] == large
+        assert plan.work_fp8(gi)["computed_tiles"] == small
+        assert plan.work_fp8(gi)["computed_flops"] < plan.work(gi)["computed_flops"] <= plan.work_fp8(gi)["computed_flops"] / 0.92
+    assert plan.work_fp8()["computed_tiles"] == sum(plan.work_fp8(gi)["computed_tiles"] for gi in range(len(groups)))
+    plan.close()
