@@ -426,14 +426,14 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
     # ---- the same layer through the other launch form (single launch <-> grouped launches) ----
     other = None
     if not fp8:
-        alt_form = 2 if plan.single_launch() else 3      # grouped launches <-> layer kernel with dense head start
+        alt_form = 2 if plan.single_launch() else 1      # grouped launches <-> the layer kernel
         ws_alt = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params,
                                                           single_launch=alt_form),
                              dtype=torch.uint8, device=dev)
         plan_alt = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws_alt,
                                        single_launch=alt_form)
         alt_ms = gpu_time_ms(lambda: svd.svd_attn_forward_planned(plan_alt, q, k, v, out), args.steps, args.warmup, torch)
-        other = {"form": "layer kernel with dense head start" if plan_alt.single_launch() else "grouped launches",
+        other = {"form": "layer kernel" if plan_alt.single_launch() else "grouped launches",
                  "ms": round(alt_ms, 4),
                  "computed_tile_frac_of_bf16_peak": round(plan_alt.work()["computed_flops"] / 1e9 / alt_ms / BF16_MFMA_PEAK_TFLOPS, 4),
                  "dense_split": plan_alt.dense_split()}
@@ -477,10 +477,10 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
         n_dense = int((wl.strategy_table == 0).sum())
         bq = svd.svd_default_blocks(wl.D)[0]
         head_start = (-(-wl.L // bq) * n_dense * wl.B) // n_cu * n_cu      # whole rounds of one dense item per compute unit
-        if head_start:
+        if head_start and plan.launch_form() == 3:
             dispatches.append({"kernel": f"attn_fwd_kernel<{wl.D}, 8, 1, {svd.svd_default_blocks(wl.D)[1]}, 2, 0>",
                                "grid_size": -(-head_start // 8) * 8 * 512})
-        roofline = {"bound": "mfma", "kernel": "attn_layer_kernel + attn_fwd_kernel[dense head start] (the whole step)",
+        roofline = {"bound": "mfma", "kernel": "attn_layer_kernel" + (" + attn_fwd_kernel[dense head start]" if plan.launch_form() == 3 else "") + " (the whole step)",
                     "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
                     "traffic": traffic, "traffic_source": traffic_source, "traffic_key": "layer", "dispatches": dispatches}
     add_measured_peak(roofline, calib, fp8)
@@ -527,7 +527,8 @@ def measure_layer(wl, args, torch, np, svd, cpu_seconds, dense_reps, calib=None)
                    "text_tokens_with_dense_borders": text, "B": wl.B, "H": wl.H, "L": wl.L, "D": wl.D,
                    "block_q": svd.svd_default_blocks(wl.D)[0], "block_k": svd.svd_default_blocks(wl.D)[1],
                    "dense_split": plan.dense_split(),
-                   "launch_form": ("layer kernel" + (" alone" if args.single_launch == 1 else " with dense head start")) if plan.single_launch() else "grouped launches",
+                   "launch_form": {0: "grouped launches", 1: "layer kernel (the whole layer in one launch)",
+                                   3: "layer kernel after a dense head start"}[plan.launch_form()],
                    "heads_by_mode": {MODE_NAMES[m]: int((wl.strategy_table == m).sum()) for m in range(5)}},
         "wall_ms_per_step": round(wall_ms, 4),
         "dense_equiv_tflops": round(dense_flops / 1e9 / ms_per_step, 1),

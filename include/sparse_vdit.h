@@ -127,11 +127,12 @@ typedef struct {
  * columns 0..T-1.  0 = no text prefix.  sparse_vdit_attn_forward takes no
  * options and therefore no text prefix.
  * single_launch: Section 4.2 fuses the heads that share a mode into one launch;
- * with single_launch = 1 the whole layer is ONE launch: resident work-groups (two
- * of four waves per compute unit) pull (group, head, query tile) items off eight
+ * with single_launch = 1 the whole layer is ONE launch: resident work-groups (one
+ * of eight waves per compute unit) pull (group, head, query tile) items off eight
  * work queues, one per XCD, heaviest group first, and move on to the other
  * queues when their own is empty, so no group pays for a partly filled last
- * round.  Every item runs on the 128-row query tile, dense heads are not split,
+ * round.  Every item runs on the kernels' 256-row query tile (one work-group of
+ * eight waves per compute unit), dense heads are not split,
  * text rows of a text prefix are items of the dense
  * kind, and nothing is forked.  The queue positions are words of the plan
  * workspace that a small fill kernel zeroes ahead of the layer kernel (no
@@ -140,14 +141,13 @@ typedef struct {
  * bit-identical to the grouped launches of a plan with dense_split = 1.
  * 3 = the single launch with a DENSE HEAD START: as many whole rounds of dense
  * items as there are (one work-group per compute unit and round, none partly
- * filled) first go through the dense kernel on its 256-row tile, which reuses a
- * K/V tile in LDS for twice as many rows; the rest of the dense group and
- * everything else is the layer kernel's.  Same bits.
- * 2 = grouped launches.  0 = the library's choice: form 3 for D = 128 when the
+ * filled) first go through the dense kernel in a launch of its own; the rest of
+ * the dense group and everything else is the layer kernel's.  Same bits.
+ * 2 = grouped launches.  0 = the library's choice: form 1 for D = 128 when the
  * layer's items are long (48 key tiles per item or more, averaged over the heads
  * that compute: picking an item costs a few microseconds), grouped launches
- * otherwise - for D = 64 (there the 128-row tile costs the dense items more than
- * the filled tails bring), for short items, whenever dense_split > 1 is forced,
+ * otherwise - for D = 64 (there they measure 2-8 % faster than both forms), for
+ * short items, whenever dense_split > 1 is forced,
  * the block shape is not the kernels' or no device is present.  1 and 3
  * need the kernels' block shape (SVD_ERR_UNSUPPORTED otherwise) and a device
  * (SVD_ERR_HIP).  The split of the dense heads is still chosen and its scratch
@@ -189,8 +189,9 @@ svd_status svd_plan_destroy(svd_plan* plan);
  * 1 for host-only plans). */
 svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split);
 
-/* 1 when svd_attn_forward_planned runs this plan through the layer kernel (plan
- * option single_launch 1 or 3, or the library's choice), else 0. */
+/* How svd_attn_forward_planned runs this plan: 1 = the layer kernel alone, 3 = the
+ * layer kernel after the dense head start (plan option single_launch, or the
+ * library's choice), 0 = a launch per group. */
 svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch);
 
 /* Inspection of a compiled plan (host copies owned by the plan, valid until

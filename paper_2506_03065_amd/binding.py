@@ -238,10 +238,14 @@ class Plan:
         _check(lib().svd_plan_dense_split(self.handle, C.byref(n)), "svd_plan_dense_split")
         return n.value
 
-    def single_launch(self) -> bool:
+    def launch_form(self) -> int:
+        """0 = a launch per group, 1 = the layer kernel alone, 3 = the layer kernel after the dense head start."""
         n = C.c_int32()
         _check(lib().svd_plan_single_launch(self.handle, C.byref(n)), "svd_plan_single_launch")
-        return bool(n.value)
+        return n.value
+
+    def single_launch(self) -> bool:
+        return self.launch_form() != 0
 
     def groups(self):
         L_ = lib()

@@ -47,6 +47,7 @@ struct svd_plan {
   size_t gather_offset = 0;
   int gather_pad = 0;
   bool single_launch = false;
+  bool head_start_asked = false;   // form 3, whether or not a whole round of dense items exists
   // dense head start (plan option single_launch = 3): this many 256-row dense items, whole rounds of
   // one work-group per compute unit, run through the dense kernel ahead of the layer kernel
   int dense_head_start = 0;
@@ -85,11 +86,11 @@ svd_status resolve_blocks(const svd_tensor_desc& desc, const svd_plan_options* o
 }
 
 // How svd_attn_forward_planned runs the plan: 0 = a launch per group, 1 = the layer kernel alone, 3 = the layer
-// kernel after a dense head start.  The library's own choice: the layer kernel saves the partly filled last round
-// of every group (3-5 % of a layer) but runs dense items on the 128-row tile, which costs about 4 % of their rate at
-// D = 128 and 14 % at D = 64 (measured); the head start takes most of that back for the dense group.  So: head start
-// form at D = 128, grouped launches at D = 64 - and grouped launches whenever the caller forces a dense split or there
-// is no device to size the grid from.
+// kernel after a dense head start.  The library's own choice follows the measurements: the layer kernel saves the
+// partly filled last round of every group, 3-5 % of a layer at D = 128 (HunyuanVideo-, Wan2.1-like layers, the
+// stack), where the head start brings nothing on top; at D = 64 the grouped launches with their three-way dense
+// split stay 2-8 % ahead of both forms.  Grouped launches also whenever the caller forces a dense split, the items
+// are short, or there is no device to size the grid from.
 int layer_form(const svd_plan_options* opt, const svd_tensor_desc& d, bool native, int n_cu, double tiles_per_item) {
   const int asked = opt ? opt->single_launch : 0;
   if (asked == 1 || asked == 3) return asked;
@@ -98,7 +99,7 @@ int layer_form(const svd_plan_options* opt, const svd_tensor_desc& d, bool nativ
   // picking an item off a queue costs a few microseconds (an atomic round trip, two barriers): with short items
   // (narrow windows, short sequences) that outweighs the tails (measured: 29 key tiles per item, 8 % slower)
   if (tiles_per_item < 48.0) return 0;
-  return d.D == 128 ? 3 : 0;
+  return d.D == 128 ? 1 : 0;
 }
 
 // Key tiles per item of the layer on the 128-row tile, averaged over the heads that compute (what the
@@ -395,8 +396,9 @@ static void build_layer_segments(svd_plan* sp) {
         // the head start covers the first items of the (batch, head, 256-row tile) order: whole heads, then
         // the first tiles of one more; a 256-row tile is two 128-row items (one at a ragged end)
         const int heads_done = sp->dense_head_start / p.n_q_blocks, tiles_done = sp->dense_head_start % p.n_q_blocks;
-        const int halves = 2 * tiles_done < n_qb ? 2 * tiles_done : n_qb;
-        dense.first_item = heads_done * n_qb + halves;
+        const int per_tile = p.block_q / bq;   // items of the queues per tile of the head start (1: the same tile)
+        const int parts = per_tile * tiles_done < n_qb ? per_tile * tiles_done : n_qb;
+        dense.first_item = heads_done * n_qb + parts;
         dense.n_items -= dense.first_item;
         sp->dense_group = &g;
       }
@@ -485,6 +487,7 @@ static svd_status create_plan(svd_plan** plan, const svd_tensor_desc* desc,
     if (single) {
       sp->single_launch = true;
       sp->n_cu = n_cu_ws;
+      sp->head_start_asked = form == 3;
       if (form == 3) {
         const long long items = static_cast<long long>(sp->p.n_q_blocks) * count_dense_heads(sp->p) * desc->B;
         sp->dense_head_start = static_cast<int>(items / n_cu_ws * n_cu_ws);
@@ -543,7 +546,7 @@ svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split) {
 
 svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch) {
   if (!plan || !single_launch) return SVD_ERR_NULL;
-  *single_launch = plan->single_launch ? 1 : 0;
+  *single_launch = plan->single_launch ? (plan->dense_head_start > 0 || plan->head_start_asked ? 3 : 1) : 0;
   return SVD_OK;
 }
 

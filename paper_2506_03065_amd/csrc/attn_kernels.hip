@@ -800,10 +800,15 @@ __global__ void __launch_bounds__(128) reset_counters_kernel(int* counters) {
   if (threadIdx.x < kLayerCounterWords) counters[threadIdx.x] = 0;
 }
 
-// Zero fill of one 128-row tile of a skipped head (M_1).
+// Waves per work-group of the layer kernel: eight, one work-group per compute unit, every item on the
+// 256-row query tile (a K/V tile in LDS then serves twice the rows of the four-wave form, which ran the
+// dense items 4-14 % and the wide-band items 4-7 % slower).
+constexpr int kLayerWaves = 8;
+
+// Zero fill of one query tile of a skipped head (M_1).
 template <int D>
 __device__ __forceinline__ void zero_item(const AttnLaunch& p, const int item) {
-  constexpr int BR = 128, CH = D / 8;
+  constexpr int BR = kLayerWaves * 32, CH = D / 8;
   const int qblk = item % p.n_q_blocks;
   const int hb = item / p.n_q_blocks;
   const int hg = hb % p.n_heads, b = hb / p.n_heads;
@@ -880,14 +885,14 @@ __device__ __attribute__((noinline)) void layer_segment(const AttnLaunch av, con
       }
       const int item = first_item + x * per + pos;
       if (KIND == kZeroKind) zero_item<D>(a, item);
-      else attn_item<D, 4, 1, BC, 2, (KIND == kZeroKind ? MODE_DENSE : KIND)>(a, item, smem);
+      else attn_item<D, kLayerWaves, 1, BC, 2, (KIND == kZeroKind ? MODE_DENSE : KIND)>(a, item, smem);
       __syncthreads();
     }
   }
 }
 
 template <int D, int BC>
-__global__ void __launch_bounds__(256, 2) attn_layer_kernel(const LayerLaunch lp) {
+__global__ void __launch_bounds__(kLayerWaves * 64, 2) attn_layer_kernel(const LayerLaunch lp) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BC * D * 2];
   __shared__ int pick;
   typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
@@ -986,13 +991,13 @@ hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, b
   return hipErrorInvalidValue;
 }
 
-int layer_block_q(int D) { return kernel_small_block_q(D); }
+int layer_block_q(int) { return kLayerWaves * 32; }
 
 hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t stream) {
   if (p.n_segments < 1) return hipSuccess;
   if (p.n_segments > kMaxSegments || !p.counters || n_compute_units < 1) return hipErrorInvalidValue;
-  static_assert(Tile128s::NW == 4 && Tile64s::NW == 4 && Tile128s::QB == 1 && Tile64s::QB == 1,
-                "the layer kernel runs the small query tile: four waves of 32 rows");
+  static_assert(Tile128::NW == kLayerWaves && Tile64::NW == kLayerWaves && Tile128::QB == 1 && Tile64::QB == 1,
+                "the layer kernel runs the kernels' own query tile: eight waves of 32 rows");
   long long total = 0;
   for (int s = 0; s < p.n_segments; ++s) {
     if (p.seg[s].n_items < 0 || p.seg[s].first_item < 0 || p.seg[s].kind < SEG_DENSE || p.seg[s].kind > SEG_ZERO)
@@ -1003,13 +1008,13 @@ hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t s
   hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(128), 0, stream, p.counters);
   static_assert(kLayerCounterWords <= 128, "one thread per queue position");
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  // two resident work-groups per compute unit, a multiple of eight so that every XCD gets its share
-  long long groups = 2LL * n_compute_units;
+  // one resident work-group of eight waves per compute unit, a multiple of eight so that every XCD gets its share
+  long long groups = static_cast<long long>(8 / kLayerWaves) * n_compute_units;
   if (groups > total) groups = total;
   groups = (groups + 7) / 8 * 8;
-  const dim3 grid((unsigned)groups), block(256);
-  if (p.a.D == 128) hipLaunchKernelGGL((attn_layer_kernel<128, Tile128s::BC>), grid, block, 0, stream, p);
-  else if (p.a.D == 64) hipLaunchKernelGGL((attn_layer_kernel<64, Tile64s::BC>), grid, block, 0, stream, p);
+  const dim3 grid((unsigned)groups), block(kLayerWaves * 64);
+  if (p.a.D == 128) hipLaunchKernelGGL((attn_layer_kernel<128, Tile128::BC>), grid, block, 0, stream, p);
+  else if (p.a.D == 64) hipLaunchKernelGGL((attn_layer_kernel<64, Tile64::BC>), grid, block, 0, stream, p);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

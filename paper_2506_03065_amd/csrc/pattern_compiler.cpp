@@ -168,7 +168,7 @@ svd_status validate_desc(const svd_tensor_desc* desc) {
 
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
-                        int32_t text_tokens, int32_t block_q_small, Plan* plan, bool always_small) {
+                        int32_t text_tokens, int32_t block_q_small, Plan* plan, bool always_large) {
   if (!strategy_table || !pattern_params || !plan) return SVD_ERR_NULL;
   if (svd_status st = validate_desc(&desc)) return st;
   if (block_q < 1 || block_k < 1) return SVD_ERR_UNSUPPORTED;
@@ -314,7 +314,7 @@ svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_tab
         area += g.bands[g.list_id[t]].tile_area;
         area_small += alt[g.list_id[t]].tile_area;
       }
-      if (always_small || area_small < 0.92 * area) {
+      if (!always_large && area_small < 0.92 * area) {
         g.bands.swap(alt);
         g.block_q = block_q_small;
       } else {

@@ -87,11 +87,11 @@ struct Plan {
 // lists gain the text columns.
 // block_q_small > 0: band groups (modes 2 and 3) whose lists cover at least 8 %
 // less area with that many query rows per tile are compiled for it; with
-// always_small every band group is (the single-launch path runs every item on
-// the small query tile).
+// always_large none is (the single-launch path runs every item on the large
+// query tile) - the small-tile lists are then still kept beside them (bands_small).
 svd_status compile_plan(const svd_tensor_desc& desc, const int32_t* strategy_table,
                         const svd_head_params* pattern_params, int32_t block_q, int32_t block_k,
-                        int32_t text_tokens, int32_t block_q_small, Plan* plan, bool always_small = false);
+                        int32_t text_tokens, int32_t block_q_small, Plan* plan, bool always_large = false);
 
 svd_status validate_desc(const svd_tensor_desc* desc);
 

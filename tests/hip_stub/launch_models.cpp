@@ -220,7 +220,11 @@ hipError_t launch_attention(const AttnLaunch& p, int mode, hipStream_t stream, b
   return model_attention(p, nullptr, mode, stream, small_q);
 }
 
-int layer_block_q(int D) { return kernel_small_block_q(D); }
+int layer_block_q(int D) {
+  int bq = 0, bk = 0;
+  kernel_blocks(D, &bq, &bk);
+  return bq;   // the layer kernel runs the kernels' own (large) query tile
+}
 
 // The single-launch path: every item of every segment, on the small query tile; the queue positions.
 hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t stream) {
@@ -251,7 +255,7 @@ hipError_t launch_layer(const LayerLaunch& p, int n_compute_units, hipStream_t s
       if (sg.kind != SEG_ZERO) {
         const int mode = sg.kind == SEG_DENSE ? MODE_DENSE : sg.kind == SEG_BAND ? MODE_BAND
                          : sg.kind == SEG_GATHER ? MODE_GATHER : MODE_PBAND;
-        model_item(a, nullptr, mode, true, item);
+        model_item(a, nullptr, mode, false, item);
         continue;
       }
       const int qblk = item % a.n_q_blocks, hb = item / a.n_q_blocks;

@@ -168,7 +168,7 @@ void run_layer(const Layer& l) {
     if (st == SVD_OK) {
       int32_t is_single = 0;
       svd_plan_single_launch(plan, &is_single);
-      expect(is_single == 1, l, "the plan reports the single launch");
+      expect(is_single == form, l, "the plan reports its launch form");
       const long before = stub::launches();
       stub::new_forward();
       st = svd_attn_forward_planned(plan, q, k, v, out, nullptr);
