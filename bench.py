@@ -175,6 +175,11 @@ def run_stack(args, torch, np, svd, W, cpu_seconds=None, calib=None, dense_reps=
         peak = FP8_MFMA_PEAK_TFLOPS if fp8 else BF16_MFMA_PEAK_TFLOPS
         roofline = {"bound": "mfma", "kernel": f"{'attn_fwd_fp8_kernel' if fp8 else 'attn_fwd_kernel'}[dense group of layer 0]",
                     "achieved": round(tf0, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf0 / peak, 4), "traffic": None}
+        if plans[0].single_launch() and not fp8:
+            # every layer is one launch of the layer kernel: the step is the dominant kernel, 40 times over
+            tf = computed / 1e9 / ms_per_step
+            roofline = {"bound": "mfma", "kernel": "attn_layer_kernel (one launch per layer, the whole step)",
+                        "achieved": round(tf, 1), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4), "traffic": None}
         add_measured_peak(roofline, calib, fp8)
     dense_flops = wl0.dense_flops * n_layers
     cpu, max_err, mean_err = None, None, None
