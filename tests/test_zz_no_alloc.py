@@ -43,3 +43,28 @@ def test_static_entry_point_matches_the_workspace_entry_point():
         svd.sparse_vdit_attn_forward_static(q, k, v, big.strategy_table, big.pattern_params, got)
     torch.cuda.synchronize()
     assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+
+
+def test_static_entry_point_with_a_layer_that_runs_as_one_launch():
+    """A D = 128 layer with long items: the library's choice is the layer kernel, whose queue positions and gathered
+    stripe rows then live in the static buffer too (the positions are cleared by every call)."""
+    wl = W.small(L=9000, D=128, H=6, seed=93)
+    q, k, v = (t.to(DEV) for t in W.make_qkv(wl))
+    desc = svd.desc_of(q)
+    ws = torch.empty(svd.svd_plan_workspace_bytes(desc, wl.strategy_table, wl.pattern_params), dtype=torch.uint8, device=DEV)
+    plan = svd.svd_plan_create(desc, wl.strategy_table, wl.pattern_params, workspace=ws)
+    assert plan.launch_form() == 1
+    want = torch.full_like(q, float("nan"))
+    svd.svd_attn_forward_planned(plan, q, k, v, want)
+    torch.cuda.synchronize()
+    plan.close()
+    for call in range(3):                       # a miss, then two hits on the cached plan
+        got = torch.full_like(q, float("nan"))
+        svd.sparse_vdit_attn_forward_static(q, k, v, wl.strategy_table, wl.pattern_params, got)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"call {call}"
+    one_shot = torch.full_like(q, float("nan"))
+    svd.sparse_vdit_attn_forward(q, k, v, wl.strategy_table, wl.pattern_params, one_shot, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(one_shot.view(torch.int16), want.view(torch.int16))
+    check_layer(wl, q, k, v, got, rows=W.sample_rows(wl, n_random=32))
