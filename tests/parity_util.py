@@ -9,15 +9,12 @@ from paper_2506_03065_amd import binding as svd
 # The contract: max abs error <= 2e-2 and mean abs error <= 2e-3 against the
 # oracle.  With N(0,1) inputs the outputs of long heads are small, so two
 # scale-free gates are added per head: relative L2 error <= 1e-2 and
-# max abs error <= 8e-2 * rms(reference) + 1e-3.  Expected level from bf16
-# rounding of P and of the output: about 3e-3 relative.  Single elements go
-# further: the bf16 rounding of the pre-scaled Q moves a logit s by up to
-# 2^-9 |s| and P is rounded to bf16 against a reference that depends on the
-# order of the tiles.  In a sweep of 60 random layers the largest deviation was
-# 5.6 % of a head's rms; a CPU emulation of that arithmetic (bf16 scaled Q,
-# bf16 P against the exact maximum) was 2.8e-3 from the oracle there, the
-# kernel 2.0e-3 from the emulation and 4.7e-3 from the oracle, identical for
-# both query-tile shapes.
+# max abs error <= 8e-2 * rms(reference) + 1e-3.  Where the 8e-2 comes from:
+# the precision this build specifies (bf16 pre-scaled Q, bf16 P, bf16 output,
+# everything else exact), carried out on the CPU, already deviates from the
+# exact definition by up to 6.6 % of a head's rms on a single element of a
+# narrow-band head (tests/test_tolerance_derivation.py, which also holds the
+# gate to at most 1.5 times that); the kernel adds the order of its tiles.
 MAX_ABS, MEAN_ABS, REL_L2, MAX_OVER_RMS = 2e-2, 2e-3, 1e-2, 8e-2
 
 
