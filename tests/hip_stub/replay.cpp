@@ -197,6 +197,29 @@ void run_layer(const Layer& l) {
     stub::device_free(ws);
     }
   }
+  {
+    // what the library chooses when the caller leaves the launch form to it
+    svd_plan_options own = opt;
+    own.dense_split = 0;
+    size_t bytes = 0;
+    int st = svd_plan_workspace_bytes(&desc, l.table.data(), l.params.data(), &own, &bytes);
+    void* ws = stub::device_alloc(bytes ? bytes : 1);
+    svd_plan* plan = nullptr;
+    if (st == SVD_OK) st = svd_plan_create(&plan, &desc, l.table.data(), l.params.data(), &own, ws, bytes, nullptr);
+    expect(st == SVD_OK, l, "plan with the library's choice of the launch form", st);
+    if (st == SVD_OK) {
+      int32_t form = -1;
+      svd_plan_single_launch(plan, &form);
+      std::printf("layer %s: the library's launch form is %d\n", l.name.c_str(), form);
+      stub::new_forward();
+      st = svd_attn_forward_planned(plan, q, k, v, out, nullptr);
+      expect(st == SVD_OK, l, "forward with the library's choice of the launch form", st);
+      if (l.tensors && st == SVD_OK)
+        expect(stub::out_rows_written() == static_cast<size_t>(l.B) * l.H * l.L, l, "every output row stored exactly once (library's choice)");
+      svd_plan_destroy(plan);
+    }
+    stub::device_free(ws);
+  }
   if (l.text == 0) {
     // the entry point that allocates nothing: a miss (copy of the lists into the library's buffer),
     // a hit, and a hit under capture; a miss under capture is refused

@@ -95,6 +95,20 @@ def test_benchmark_layers_index_arithmetic(replay, tmp_path):
     layers.append(layer_text(W.stack_layer(0), 0, rounds=1, tensors=0))
     res = run(replay, tmp_path, layers)
     assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-4000:]
+    # the library's own choice of the launch form with 256 compute units: the whole layer in one launch at D = 128
+    # (long items), a launch per group at D = 64
+    forms = {line.split()[1].rstrip(":"): int(line.split()[-1]) for line in res.stdout.splitlines() if "launch form is" in line}
+    assert forms == {"cogvideox1.5": 0, "hunyuanvideo": 1, "wan2.1": 1, "hunyuanvideo+text256": 1, "stack-layer0": 1}, forms
+
+
+def test_short_items_and_missing_device_keep_the_grouped_launches(replay, tmp_path):
+    """Small layers (few key tiles per item) stay on grouped launches whatever the head size; so does everything
+    when no device is there to size the grid from."""
+    layers = [layer_text(*random_layer(seed), rounds=1) for seed in range(6)]
+    res = run(replay, tmp_path, layers)
+    assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-4000:]
+    forms = [int(line.split()[-1]) for line in res.stdout.splitlines() if "launch form is" in line]
+    assert forms == [0] * 6, forms
 
 
 def test_the_harness_sees_a_planted_shortfall(replay, tmp_path):
