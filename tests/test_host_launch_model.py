@@ -101,9 +101,8 @@ def test_benchmark_layers_index_arithmetic(replay, tmp_path):
     assert forms == {"cogvideox1.5": 0, "hunyuanvideo": 1, "wan2.1": 1, "hunyuanvideo+text256": 1, "stack-layer0": 1}, forms
 
 
-def test_short_items_and_missing_device_keep_the_grouped_launches(replay, tmp_path):
-    """Small layers (few key tiles per item) stay on grouped launches whatever the head size; so does everything
-    when no device is there to size the grid from."""
+def test_short_items_keep_the_grouped_launches(replay, tmp_path):
+    """Small layers (few key tiles per item) stay on grouped launches whatever the head size."""
     layers = [layer_text(*random_layer(seed), rounds=1) for seed in range(6)]
     res = run(replay, tmp_path, layers)
     assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-4000:]
