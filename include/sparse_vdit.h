@@ -189,7 +189,8 @@ svd_status svd_plan_destroy(svd_plan* plan);
  * 1 for host-only plans). */
 svd_status svd_plan_dense_split(const svd_plan* plan, int32_t* dense_split);
 
-/* How svd_attn_forward_planned runs this plan: 1 = the layer kernel alone, 3 = the
+/* How svd_attn_forward_planned runs this plan (Section 4.2, fusion of heads; plan
+ * option single_launch): 1 = the layer kernel alone, 3 = the
  * layer kernel after the dense head start (plan option single_launch, or the
  * library's choice), 0 = a launch per group. */
 svd_status svd_plan_single_launch(const svd_plan* plan, int32_t* single_launch);
@@ -248,7 +249,7 @@ svd_status svd_plan_work(const svd_plan* plan, int64_t* computed_tiles, double* 
 svd_status svd_plan_group_work(const svd_plan* plan, int32_t group, int64_t* computed_tiles,
                                double* computed_flops, double* kept_pairs);
 
-/* The work of the FP8 forward pass (svd_attn_forward_fp8): its band groups always walk
+/* The work of the FP8 forward pass (svd_attn_forward_fp8, the Appendix B variant): its band groups always walk
  * small-tile lists (kept in the plan beside the lists of a group that the bf16
  * kernels run on the large tile), so their tile count and listed area can differ
  * from svd_plan_group_work.  group = -1: the whole layer. */

@@ -147,3 +147,16 @@ def test_plan_head_block_sparsity_matches_the_explicit_mask_tiles(L, D, text):
             want = S.head_block_sparsity(int(wl.strategy_table[h]), wl.pattern_params[h], wl.L, g["block_q"], g["block_k"])
             assert abs(got[h] - want) <= 1e-15, (h, g["mode"], got[h], want)
     plan.close()
+
+
+def test_probe_entry_points_validate_on_the_host():
+    """The calibration probes refuse bad arguments before any launch (no GPU needed for that)."""
+    import ctypes as C
+    lib = svd.lib()
+    flops = C.c_double()
+    assert lib.svd_probe_mfma(None, 0, 1, 1, C.byref(flops), None) == 1                    # SVD_ERR_NULL
+    assert lib.svd_probe_mfma(C.c_void_p(256), 4096, 0, 1, C.byref(flops), None) == 2      # SVD_ERR_SHAPE: no iterations
+    assert lib.svd_probe_mfma(C.c_void_p(256), 100, 1, 1, C.byref(flops), None) == 8       # SVD_ERR_WORKSPACE: scratch too small
+    assert lib.svd_probe_copy(None, C.c_void_p(256), 16, None) == 1
+    assert lib.svd_probe_copy(C.c_void_p(256), C.c_void_p(512), 24, None) == 2             # not a multiple of 16 bytes
+    assert lib.svd_probe_copy(C.c_void_p(8), C.c_void_p(512), 32, None) == 4               # SVD_ERR_ALIGN
